@@ -1,0 +1,129 @@
+"""Packing of round segments into the flat buffers the device library reads.
+
+Two layouts, both round-indexed:
+
+contiguous (block_size == 0)
+    Each round r of sequence b is one block of ``Hkv * len * d`` elements stored head-major,
+    ``[Hkv][len][d]``, so the keys of one (KV head, round) pair form a single contiguous run.
+    ``seg_off[b, r]`` is the block's start in units of tokens: element index of
+    (g, t, c) = ``(seg_off * Hkv + g * len + t) * d + c``.
+
+paged (block_size == 16)
+    Storage is an array of physical blocks ``[n_blocks][Hkv][16][d]``.  A round starts on a block
+    boundary and owns ``ceil(len / 16)`` consecutive slots of its sequence's row of the block
+    table (its last block may be partly filled).  ``seg_off[b, r]`` is the round's first slot;
+    the physical block of token t is ``block_table[b, seg_off + t // 16]`` and the element index
+    of (g, t, c) = ``((block * Hkv + g) * 16 + t % 16) * d + c``.
+
+Pure data movement: nothing here computes anything of the method.
+"""
+from __future__ import annotations
+
+import dataclasses
+from concurrent.futures import ThreadPoolExecutor
+from typing import Optional
+
+import numpy as np
+
+from .workloads import Workload, to_bf16_bits
+
+
+@dataclasses.dataclass
+class PackedLayer:
+    k: np.ndarray                       # flat; uint16 (bf16 bits) or float32
+    v: Optional[np.ndarray]             # same shape as k, or None when only keys were packed
+    seg_off: np.ndarray                 # int64 [B, R_max]
+    seg_len: np.ndarray                 # int32 [B, R_max]
+    n_rounds: np.ndarray                # int32 [B]
+    block_table: Optional[np.ndarray]   # int32 [B, max_blocks] (paged) or None
+    block_size: int
+    max_tokens: int                     # max over sequences of the total history tokens
+
+
+def _encode(x: np.ndarray, dtype: str) -> np.ndarray:
+    return to_bf16_bits(x) if dtype == "bf16" else np.ascontiguousarray(x, dtype=np.float32)
+
+
+def pack_layer(w: Workload, layer: int, with_v: bool = True, block_size: Optional[int] = None,
+               threads: int = 8, seq_range: Optional[range] = None) -> PackedLayer:
+    """Generate one layer's history K (and V) for every sequence and pack it for the device."""
+    bs = w.block_size if block_size is None else block_size
+    assert bs in (0, 16)
+    B, R_max, Hkv, d = w.B, w.R_max, w.Hkv, w.d
+    R_alloc = max(R_max, 1)
+    seg_off = np.zeros((B, R_alloc), dtype=np.int64)
+    seg_len = np.zeros((B, R_alloc), dtype=np.int32)
+    n_rounds = np.array([w.n_rounds(b) for b in range(B)], dtype=np.int32)
+    el = np.uint16 if w.dtype == "bf16" else np.float32
+    seqs = range(B) if seq_range is None else seq_range
+
+    jobs = []
+    if bs == 0:
+        tok = 0
+        for b in range(B):
+            for r in range(w.n_rounds(b)):
+                n = int(w.lens[b][r])
+                seg_off[b, r], seg_len[b, r] = tok, n
+                if b in seqs:
+                    jobs.append((b, r, tok, n))
+                tok += n
+        k = np.zeros(tok * Hkv * d, dtype=el)
+        v = np.zeros(tok * Hkv * d, dtype=el) if with_v else None
+        block_table = None
+
+        def fill(job):
+            b, r, off, n = job
+            if n == 0:
+                return
+            lo, hi = off * Hkv * d, (off + n) * Hkv * d
+            k[lo:hi] = _encode(w.k_round(b, layer, r).transpose(1, 0, 2), w.dtype).reshape(-1)
+            if with_v:
+                v[lo:hi] = _encode(w.v_round(b, layer, r).transpose(1, 0, 2), w.dtype).reshape(-1)
+    else:
+        slots = [int(sum(-(-int(n) // bs) for n in w.lens[b])) for b in range(B)]
+        max_blocks = max(slots + [1])
+        n_blocks = int(sum(slots))
+        perm = w.block_rng(layer).permutation(max(n_blocks, 1)).astype(np.int32)
+        block_table = np.full((B, max_blocks), -1, dtype=np.int32)
+        nxt = 0
+        for b in range(B):
+            slot = 0
+            for r in range(w.n_rounds(b)):
+                n = int(w.lens[b][r])
+                nb = -(-n // bs)
+                seg_off[b, r], seg_len[b, r] = slot, n
+                block_table[b, slot:slot + nb] = perm[nxt:nxt + nb]
+                if b in seqs:
+                    jobs.append((b, r, slot, n))
+                slot += nb
+                nxt += nb
+        k = np.zeros(max(n_blocks, 1) * Hkv * bs * d, dtype=el)
+        v = np.zeros(max(n_blocks, 1) * Hkv * bs * d, dtype=el) if with_v else None
+        k4 = k.reshape(-1, Hkv, bs, d)
+        v4 = v.reshape(-1, Hkv, bs, d) if with_v else None
+
+        def fill(job):
+            b, r, slot, n = job
+            if n == 0:
+                return
+            nb = -(-n // bs)
+            blocks = block_table[b, slot:slot + nb]
+
+            def scatter(dst, src):  # src [len, Hkv, d] -> padded [nb, bs, Hkv, d] -> blocks [nb, Hkv, bs, d]
+                pad = np.zeros((nb * bs, Hkv, d), dtype=el)
+                pad[:n] = _encode(src, w.dtype)
+                dst[blocks] = pad.reshape(nb, bs, Hkv, d).transpose(0, 2, 1, 3)
+
+            scatter(k4, w.k_round(b, layer, r))
+            if with_v:
+                scatter(v4, w.v_round(b, layer, r))
+
+    if threads > 1 and len(jobs) > 1:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(fill, jobs))
+    else:
+        for j in jobs:
+            fill(j)
+    max_tokens = max([w.total_tokens(b) for b in range(B)] + [0])
+    return PackedLayer(k=k, v=v, seg_off=seg_off, seg_len=seg_len, n_rounds=n_rounds,
+                       block_table=block_table, block_size=bs, max_tokens=max_tokens)
