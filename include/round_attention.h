@@ -1,0 +1,237 @@
+/*
+ * round_attention.h -- C ABI of the Round Attention hot path for AMD MI355X (gfx950).
+ *
+ * The library implements the part of the Round Attention inference pipeline (paper Sec. 3.2,
+ * steps 3-5, and Sec. 3.3) that runs on the GPU once the watershed layer L_w has been reached:
+ *
+ *   ra_round_scores               round-level attention distribution of the current question over
+ *                                 the history rounds at the watershed layer (Sec. 3.1, Eq. 1)
+ *   ra_select_rounds              choice of the relevant rounds from that distribution (Sec. 3.3)
+ *   ra_kv_store_*                 round-indexed store of the post-watershed KV ("u_m", Sec. 3.2):
+ *                                 host-resident per round, selected rounds copied to the GPU
+ *   ra_round_sparse_attn_decode   attention of one new token over the selected rounds (step 5)
+ *   ra_round_sparse_attn_prefill  attention of the question's tokens over the selected rounds
+ *                                 and, causally, over the question itself (step 4)
+ *
+ * Conventions
+ * -----------
+ * - Plain C, no exceptions.  Every call returns RA_OK (0) or a negative ra_status; the text of the
+ *   last failure on the calling thread is available from ra_last_error().
+ * - "device" pointers are HIP device memory on the context's GPU; "host" pointers are ordinary or
+ *   pinned host memory as stated.  The caller owns every buffer it passes in.  The library owns its
+ *   context, and the store owns its device pool and its small index tables.
+ * - Compute calls validate their arguments on the host, enqueue kernels on the caller's stream
+ *   (a hipStream_t passed as void*; NULL is the default stream), do not synchronise, and do not
+ *   allocate: scratch memory comes from the workspace given to ra_set_workspace().  Outputs are
+ *   fully overwritten.  Identical inputs give bitwise identical outputs.
+ * - Arguments are checked before anything is launched; on error nothing has been enqueued.
+ * - Head mapping under grouped-query attention: query head h reads KV head h / (Hq / Hkv).
+ *
+ * KV layout (one layer), round-indexed
+ * ------------------------------------
+ * contiguous (block_size == 0): round r of sequence b is a block of Hkv * len * d elements stored
+ *   head-major, [Hkv][len][d].  seg_off[b][r] is the block's start in units of tokens:
+ *   element(g, t, c) = (seg_off * Hkv + g * len + t) * d + c, relative to `k` (keys) and, with
+ *   seg_off_v (or seg_off when seg_off_v is NULL), relative to `v` (values).
+ * paged (block_size == 16): storage is an array of blocks [n_blocks][Hkv][16][d]; a round owns
+ *   ceil(len / 16) consecutive slots of row b of block_table starting at slot seg_off[b][r];
+ *   element(g, t, c) = ((block_table[b][seg_off + t / 16] * Hkv + g) * 16 + t % 16) * d + c.
+ * The current round's own K/V ("cur", the question so far / the tokens generated so far) is passed
+ * separately, token-major: [B][cur_cap][Hkv][d].
+ */
+#ifndef ROUND_ATTENTION_H
+#define ROUND_ATTENTION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ra_status {
+    RA_OK = 0,
+    RA_ERR_INVALID_ARG = -1, /* null pointer, negative size, inconsistent shapes               */
+    RA_ERR_UNSUPPORTED = -2, /* dtype / head_dim / group size / block size not implemented      */
+    RA_ERR_WORKSPACE = -3,   /* no workspace set, or it is too small for this call              */
+    RA_ERR_STATE = -4,       /* call made in the wrong order (e.g. view requested before stage) */
+    RA_ERR_OOM = -5,         /* the store's device pool cannot hold the selected rounds         */
+    RA_ERR_HIP = -6          /* a HIP runtime call failed; see ra_last_error()                  */
+} ra_status;
+
+typedef enum ra_dtype { RA_F32 = 0, RA_BF16 = 1 } ra_dtype;
+
+/* Sec. 3.3: strategy 3 (adaptive), strategy 2 (top fraction), strategy 1 (fixed threshold). */
+typedef enum ra_strategy { RA_SEL_ADAPTIVE = 0, RA_SEL_TOP_FRACTION = 1, RA_SEL_THRESHOLD = 2 } ra_strategy;
+
+typedef struct ra_select_params {
+    int32_t strategy;   /* ra_strategy                                                          */
+    int32_t ddof;       /* ADAPTIVE: variance divisor is R - ddof (0 = population, the default)  */
+    int32_t min_rounds; /* keep at least this many rounds, best score first (default 1)          */
+    int32_t max_rounds; /* keep at most this many rounds; 0 = no cap                             */
+    double lambda;      /* ADAPTIVE: keep score > mean + lambda * std (Sec. 3.3; default 1.0,
+                           0.0 gives the "greater than the average" rule of Sec. 4.4)            */
+    double fraction;    /* TOP_FRACTION: keep the ceil(fraction * R) best rounds (paper: 0.10)   */
+    double threshold;   /* THRESHOLD: keep score > threshold (paper: v = 0.1)                    */
+} ra_select_params;
+
+/* One layer's round-indexed KV cache.  All pointers are device pointers. */
+typedef struct ra_kv_view {
+    const void* k;              /* keys                                                          */
+    const void* v;              /* values; may be NULL for ra_round_scores                       */
+    const int64_t* seg_off;     /* [B][R_max] round start: tokens (contiguous) or slots (paged)  */
+    const int64_t* seg_off_v;   /* [B][R_max] same for values, or NULL to use seg_off            */
+    const int32_t* seg_len;     /* [B][R_max] tokens in each round (0 is legal)                  */
+    const int32_t* n_rounds;    /* [B] number of history rounds of each sequence, 0..R_max       */
+    const int32_t* block_table; /* [B][max_blocks] physical block ids (paged) or NULL            */
+    int32_t block_size;         /* 0 (contiguous) or 16 (paged)                                  */
+    int32_t max_blocks;         /* row length of block_table                                     */
+    int32_t B, R_max, Hkv, d;   /* R_max <= 1024; d is 64 or 128                                 */
+    int32_t dtype;              /* ra_dtype of k, v, q and cur                                   */
+    int32_t reserved;
+    int64_t max_tokens;         /* host-known upper bound on one sequence's history tokens; only
+                                   used to size the launch, never to index memory                */
+} ra_kv_view;
+
+/* Shape envelope used to size the workspace. */
+typedef struct ra_problem {
+    int32_t B, R_max, Hq, Hkv, d, q_len_max;
+    int32_t dtype;
+    int32_t reserved;
+    int64_t max_tokens; /* per sequence, history + current round */
+} ra_problem;
+
+typedef struct ra_ctx ra_ctx;
+
+const char* ra_last_error(void);
+
+/* Create / destroy a context bound to HIP device `device`.  Creation queries the device once. */
+int ra_create(ra_ctx** out, int device);
+int ra_destroy(ra_ctx* ctx);
+
+/* Upper bound of the scratch bytes any compute call needs for problems inside `p`. */
+int ra_workspace_bytes(const ra_problem* p, size_t* bytes_out);
+/* Hand the context a device buffer (256-byte aligned) to use as scratch.  The caller keeps
+ * ownership and must keep it alive, and must not run two calls that use it concurrently. */
+int ra_set_workspace(ra_ctx* ctx, void* device_ptr, size_t bytes);
+
+/*
+ * Round scores at the watershed layer (Sec. 3.1, Eq. 1 and the normalisation after it).
+ * For every sequence b and query head h: softmax of scale * q . k over all history tokens and,
+ * if cur_k is given, over the current round's keys visible to each query token (query token i
+ * sees cur token j iff j <= cur_len - q_len + i); the probabilities are summed per history
+ * round and over the q_len query tokens, then normalised over the history rounds.
+ *   q            device [B][q_len][Hq][d], dtype of the view
+ *   watershed    the watershed layer's view; only keys are read
+ *   cur_k        device [B][cur_len][Hkv][d] or NULL (cur_len = 0)
+ *   scores_head  device float [B][Hq][R_max]: per-head distribution, rows sum to 1 over r < n_rounds[b],
+ *                entries r >= n_rounds[b] are 0; may be NULL
+ *   scores       device float [B][R_max]: arithmetic mean of scores_head over the query heads
+ * Zero-length rounds score 0; a sequence with no history tokens gets all zeros.
+ */
+int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq, const ra_kv_view* watershed,
+                    const void* cur_k, int cur_len, float scale, float* scores_head, float* scores);
+
+/*
+ * Round selection (Sec. 3.3).  Per sequence, from scores[b][0 .. n_rounds[b]):
+ *   ADAPTIVE      keep r with score > mean + lambda * std   (mean/std in double, summed in round order)
+ *   TOP_FRACTION  keep the ceil(fraction * R) highest
+ *   THRESHOLD     keep r with score > threshold
+ * then at least min_rounds and at most max_rounds are kept, preferring higher score, then lower
+ * round index.  Output is ascending.
+ *   scores   device float [B][R_max]      n_rounds  device int32 [B]
+ *   sel_idx  device int32 [B][R_max], unused tail entries set to -1
+ *   n_sel    device int32 [B]
+ * Scores must not be NaN.
+ */
+int ra_select_rounds(ra_ctx* ctx, void* stream, const float* scores, const int32_t* n_rounds, int B, int R_max,
+                     const ra_select_params* params, int32_t* sel_idx, int32_t* n_sel);
+
+/*
+ * Round-sparse decode attention (Sec. 3.2 step 5): one query token per sequence attends over the
+ * tokens of the selected rounds of `layer` plus the first cur_len[b] tokens of the current round.
+ *   q        device [B][Hq][d]
+ *   sel_idx  device int32 [B][R_max] and n_sel device int32 [B]; both NULL = every round of the view
+ *            (entries outside 0..n_rounds[b]-1 are ignored)
+ *   cur_k/v  device [B][cur_cap][Hkv][d] or NULL;  cur_len device int32 [B] (values clamped to cur_cap)
+ *   out      device float [B][Hq][d];  lse device float [B][Hq] or NULL: natural log of the
+ *            softmax normaliser of the scaled logits
+ * A sequence whose key set is empty (nothing selected and no current tokens) gets out = 0, lse = -inf.
+ */
+int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* layer,
+                                const int32_t* sel_idx, const int32_t* n_sel, const void* cur_k,
+                                const void* cur_v, const int32_t* cur_len, int cur_cap, float scale, float* out,
+                                float* lse);
+
+/*
+ * Round-sparse question-prefill attention (Sec. 3.2 step 4): q_len query tokens per sequence, the
+ * last q_len tokens of the current round.  History rounds are fully visible; inside the current
+ * round query i sees token j iff j <= cur_len - q_len + i.
+ *   q        device [B][q_len][Hq][d]
+ *   cur_k/v  device [B][cur_len][Hkv][d] or NULL (then cur_len must be 0); if given, cur_len >= q_len
+ *   out      device float [B][q_len][Hq][d];  lse device float [B][q_len][Hq] or NULL
+ * Only bf16 with d = 128 is implemented (matrix-core path).
+ */
+int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
+                                 const ra_kv_view* layer, const int32_t* sel_idx, const int32_t* n_sel,
+                                 const void* cur_k, const void* cur_v, int cur_len, float scale, float* out,
+                                 float* lse);
+
+/* ------------------------------------------------------------------------------------------
+ * Round-indexed KV store for the post-watershed layers (Sec. 3.2: "u_m" lives in host memory as
+ * one tensor per round and is moved to the GPU in one transfer when the round is selected).
+ *
+ * Host layout of one round's tensor: [n_layers][2 (K then V)][Hkv][len][d], contiguous, in
+ * PINNED host memory (hipHostMalloc or torch pin_memory); the caller keeps it alive and unchanged
+ * while registered.  Staging copies it as is into the device pool, so each (layer, K|V) slice is a
+ * head-major round block as described above; the per-layer views index it through seg_off / seg_off_v.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct ra_kv_store ra_kv_store;
+
+typedef struct ra_store_cfg {
+    int32_t device;
+    int32_t n_layers; /* number of post-watershed layers held per round */
+    int32_t B, R_max, Hkv, d;
+    int32_t dtype;
+    int32_t reserved;
+    size_t device_pool_bytes; /* capacity of the device pool the selected rounds are staged into */
+} ra_store_cfg;
+
+typedef enum ra_stage_order {
+    RA_STAGE_ROUND_MAJOR = 0, /* one copy per selected round (the paper's monolithic transfer)        */
+    RA_STAGE_LAYER_MAJOR = 1  /* one copy per (layer, round), layer by layer, so that the first
+                                 post-watershed layer can start before the last one has arrived  */
+} ra_stage_order;
+
+int ra_kv_store_create(ra_kv_store** out, const ra_store_cfg* cfg);
+int ra_kv_store_destroy(ra_kv_store* store);
+/* Register (or replace) the host tensor of round `round` of sequence `seq`; len >= 0 tokens.
+ * Returns RA_ERR_INVALID_ARG if host_kv is not pinned host memory. */
+int ra_kv_store_register_round(ra_kv_store* store, int seq, int round, const void* host_kv, int len);
+/* Bytes of one registered round's host tensor for a given length. */
+size_t ra_kv_store_round_bytes(const ra_kv_store* store, int len);
+/*
+ * Enqueue on `side_stream` the host-to-device copies of every selected round and of the index
+ * tables of the compact per-layer views, and record one "ready" event per layer.
+ *   sel_idx_host int32 [B][R_max], n_sel_host int32 [B]  (host memory; read before returning)
+ * Returns RA_ERR_STATE if a selected round was never registered, RA_ERR_OOM if the pool is too
+ * small (nothing is enqueued in either case).
+ */
+int ra_kv_store_stage(ra_kv_store* store, const int32_t* sel_idx_host, const int32_t* n_sel_host, int order,
+                      void* side_stream);
+/* Make `compute_stream` wait until `layer` (0-based) has fully arrived. */
+int ra_kv_store_wait_layer(ra_kv_store* store, int layer, void* compute_stream);
+/* Compact view of one staged layer: its rounds are the selected rounds in ascending order, so the
+ * attention calls take it with sel_idx = n_sel = NULL. */
+int ra_kv_store_layer_view(ra_kv_store* store, int layer, ra_kv_view* out);
+/* Byte accounting of the last stage call: bytes copied to the device and bytes of all registered rounds. */
+int ra_kv_store_stats(const ra_kv_store* store, uint64_t* staged_bytes, uint64_t* registered_bytes,
+                      uint64_t* n_copies);
+/* Forget the staged rounds (the pool is reused by the next stage call); registrations are kept.
+ * The caller must have finished all work that reads the staged views. */
+int ra_kv_store_release(ra_kv_store* store);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROUND_ATTENTION_H */

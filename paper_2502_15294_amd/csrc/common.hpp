@@ -1,0 +1,68 @@
+// Internal declarations shared by the translation units of libround_attention (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "round_attention.h"
+
+namespace ra {
+
+// ---- error reporting ------------------------------------------------------------------------
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+#define RA_HIP_CHECK(expr)                                                                      \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess) return ::ra::fail(RA_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+#define RA_REQUIRE(cond, code, ...)                      \
+    do {                                                 \
+        if (!(cond)) return ::ra::fail(code, __VA_ARGS__); \
+    } while (0)
+
+// ---- context ---------------------------------------------------------------------------------
+struct Workspace {
+    char* base = nullptr;
+    size_t bytes = 0;
+};
+
+}  // namespace ra
+
+struct ra_ctx {
+    int device = 0;
+    int num_cu = 256;
+    ra::Workspace ws;
+};
+
+namespace ra {
+
+// View as the kernels see it (passed by value).
+struct DevView {
+    const void* k;
+    const void* v;
+    const int64_t* seg_off;
+    const int64_t* seg_off_v;
+    const int32_t* seg_len;
+    const int32_t* n_rounds;
+    const int32_t* block_table;
+    int32_t block_size, max_blocks, B, R_max, Hkv, d;
+};
+
+int check_view(const ra_kv_view* v, bool need_v, const char* who);
+DevView to_dev(const ra_kv_view* v);
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Number of KV splits the decode / prefill launchers use for a given shape.
+int decode_splits(int num_cu, int B, int Hkv, int64_t max_tokens);
+
+constexpr int kUnitTokens = 16;   // tokens per work unit of the streaming kernels (= one paged block)
+constexpr int kMaxRounds = 1024;  // largest R_max any entry point accepts
+
+// ---- device helpers --------------------------------------------------------------------------
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no score yet" (keeps max/exp free of inf - inf)
+
+}  // namespace ra

@@ -1,0 +1,129 @@
+// Context, workspace and argument checking of libround_attention.
+#include "common.hpp"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <new>
+
+namespace ra {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_view(const ra_kv_view* v, bool need_v, const char* who) {
+    RA_REQUIRE(v != nullptr, RA_ERR_INVALID_ARG, "%s: view is NULL", who);
+    RA_REQUIRE(v->B > 0 && v->R_max >= 0 && v->Hkv > 0 && v->d > 0, RA_ERR_INVALID_ARG,
+               "%s: view needs B > 0, R_max >= 0, Hkv > 0, d > 0 (got %d, %d, %d, %d)", who, v->B, v->R_max, v->Hkv,
+               v->d);
+    RA_REQUIRE(v->R_max <= kMaxRounds, RA_ERR_UNSUPPORTED, "%s: R_max %d exceeds %d", who, v->R_max, kMaxRounds);
+    RA_REQUIRE(v->dtype == RA_F32 || v->dtype == RA_BF16, RA_ERR_UNSUPPORTED, "%s: unknown dtype %d", who, v->dtype);
+    RA_REQUIRE(v->n_rounds != nullptr, RA_ERR_INVALID_ARG, "%s: view.n_rounds is NULL", who);
+    if (v->R_max > 0) {
+        RA_REQUIRE(v->k != nullptr, RA_ERR_INVALID_ARG, "%s: view.k is NULL", who);
+        RA_REQUIRE(!need_v || v->v != nullptr, RA_ERR_INVALID_ARG, "%s: view.v is NULL", who);
+        RA_REQUIRE(v->seg_off != nullptr && v->seg_len != nullptr, RA_ERR_INVALID_ARG,
+                   "%s: view.seg_off / seg_len is NULL", who);
+    }
+    RA_REQUIRE(v->block_size == 0 || v->block_size == kUnitTokens, RA_ERR_UNSUPPORTED,
+               "%s: block_size must be 0 or %d (got %d)", who, kUnitTokens, v->block_size);
+    if (v->block_size != 0 && v->R_max > 0) {
+        RA_REQUIRE(v->block_table != nullptr && v->max_blocks > 0, RA_ERR_INVALID_ARG,
+                   "%s: paged view needs block_table and max_blocks > 0", who);
+    }
+    RA_REQUIRE(v->max_tokens >= 0, RA_ERR_INVALID_ARG, "%s: view.max_tokens is negative", who);
+    return RA_OK;
+}
+
+DevView to_dev(const ra_kv_view* v) {
+    DevView d;
+    d.k = v->k;
+    d.v = v->v;
+    d.seg_off = v->seg_off;
+    d.seg_off_v = v->seg_off_v ? v->seg_off_v : v->seg_off;
+    d.seg_len = v->seg_len;
+    d.n_rounds = v->n_rounds;
+    d.block_table = v->block_table;
+    d.block_size = v->block_size;
+    d.max_blocks = v->max_blocks;
+    d.B = v->B;
+    d.R_max = v->R_max;
+    d.Hkv = v->Hkv;
+    d.d = v->d;
+    return d;
+}
+
+int decode_splits(int num_cu, int B, int Hkv, int64_t max_tokens) {
+    // Aim for about 8 workgroups per compute unit so that uneven selections even out, but never
+    // cut a sequence into pieces of fewer than 128 tokens (two 16-token units per wave).
+    const int64_t target = (int64_t)num_cu * 8;
+    int64_t s = (target + (int64_t)B * Hkv - 1) / ((int64_t)B * Hkv);
+    int64_t cap = max_tokens / 128;
+    if (cap < 1) cap = 1;
+    if (s > cap) s = cap;
+    if (s > 64) s = 64;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+}  // namespace ra
+
+using namespace ra;
+
+extern "C" {
+
+const char* ra_last_error(void) { return g_err; }
+
+int ra_create(ra_ctx** out, int device) {
+    RA_REQUIRE(out != nullptr, RA_ERR_INVALID_ARG, "ra_create: out is NULL");
+    *out = nullptr;
+    int n = 0;
+    RA_HIP_CHECK(hipGetDeviceCount(&n));
+    RA_REQUIRE(device >= 0 && device < n, RA_ERR_INVALID_ARG, "ra_create: device %d out of range (%d devices)", device,
+               n);
+    hipDeviceProp_t prop;
+    RA_HIP_CHECK(hipGetDeviceProperties(&prop, device));
+    ra_ctx* c = new (std::nothrow) ra_ctx();
+    RA_REQUIRE(c != nullptr, RA_ERR_OOM, "ra_create: out of host memory");
+    c->device = device;
+    c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    *out = c;
+    return RA_OK;
+}
+
+int ra_destroy(ra_ctx* ctx) {
+    delete ctx;
+    return RA_OK;
+}
+
+int ra_workspace_bytes(const ra_problem* p, size_t* bytes_out) {
+    RA_REQUIRE(p != nullptr && bytes_out != nullptr, RA_ERR_INVALID_ARG, "ra_workspace_bytes: NULL argument");
+    RA_REQUIRE(p->B > 0 && p->R_max >= 0 && p->Hq > 0 && p->Hkv > 0 && p->d > 0 && p->q_len_max > 0 &&
+                   p->max_tokens >= 0,
+               RA_ERR_INVALID_ARG, "ra_workspace_bytes: non-positive dimension");
+    RA_REQUIRE(p->Hq % p->Hkv == 0, RA_ERR_INVALID_ARG, "ra_workspace_bytes: Hq %% Hkv != 0");
+    const size_t rows = (size_t)p->B * p->q_len_max * p->Hq;
+    // attention partials: up to 64 splits of (d accumulators + running max + running sum) per output row
+    const size_t attn = rows * 64 * ((size_t)p->d + 2) * sizeof(float);
+    // score intermediates: one log-sum-exp per (row, round) plus one for the current round
+    const size_t sc = rows * ((size_t)p->R_max + 1) * sizeof(float);
+    *bytes_out = align_up(attn, 256) + align_up(sc, 256) + 256;
+    return RA_OK;
+}
+
+int ra_set_workspace(ra_ctx* ctx, void* device_ptr, size_t bytes) {
+    RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "ra_set_workspace: ctx is NULL");
+    RA_REQUIRE(device_ptr != nullptr || bytes == 0, RA_ERR_INVALID_ARG, "ra_set_workspace: NULL pointer with bytes > 0");
+    RA_REQUIRE(((uintptr_t)device_ptr & 255u) == 0, RA_ERR_INVALID_ARG, "ra_set_workspace: pointer not 256-byte aligned");
+    ctx->ws.base = (char*)device_ptr;
+    ctx->ws.bytes = bytes;
+    return RA_OK;
+}
+
+}  // extern "C"

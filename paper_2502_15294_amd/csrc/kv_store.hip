@@ -1,0 +1,274 @@
+// Round-indexed KV store for the post-watershed layers (paper Sec. 3.2 and Fig. 1: the "upper half"
+// u_m of every round stays in host memory as one tensor; the tensors of the selected rounds are
+// moved to the GPU, each in one transfer, once the selection is known).
+//
+// Host side only: a registry of pinned per-round tensors, a bump-allocated device pool, the index
+// tables of the compact per-layer views, and the hipMemcpyAsync / event choreography on a side
+// stream.  The copied bytes keep the host layout [n_layers][K|V][Hkv][len][d], so every (layer, K|V)
+// slice is already a head-major round block and no repacking kernel is needed.
+#include "common.hpp"
+
+#include <new>
+#include <vector>
+
+struct ra_kv_store {
+    ra_store_cfg cfg;
+    size_t token_bytes = 0;  // bytes of one token of one layer of K (or V): Hkv * d * elem
+    struct Round {
+        const char* host = nullptr;
+        int len = -1;  // -1 = never registered
+    };
+    std::vector<Round> rounds;  // [B][R_max]
+    char* pool = nullptr;
+    // index tables: host pinned mirror and device copy
+    int64_t* h_off = nullptr;  // [n_layers][2][B][R_max]
+    int32_t* h_len = nullptr;  // [B][R_max]
+    int32_t* h_n = nullptr;    // [B]
+    int64_t* d_off = nullptr;
+    int32_t* d_len = nullptr;
+    int32_t* d_n = nullptr;
+    std::vector<hipEvent_t> ready;
+    bool staged = false;
+    int64_t max_tokens = 0;
+    uint64_t staged_bytes = 0, n_copies = 0;
+};
+
+using namespace ra;
+
+static bool is_pinned_host(const void* p) {
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();  // ordinary pageable memory: not an error of ours, clear the sticky code
+        return false;
+    }
+    return attr.type == hipMemoryTypeHost;
+}
+
+extern "C" {
+
+int ra_kv_store_create(ra_kv_store** out, const ra_store_cfg* cfg) {
+    RA_REQUIRE(out != nullptr && cfg != nullptr, RA_ERR_INVALID_ARG, "kv_store_create: NULL argument");
+    *out = nullptr;
+    RA_REQUIRE(cfg->n_layers > 0 && cfg->B > 0 && cfg->R_max > 0 && cfg->Hkv > 0 && cfg->d > 0, RA_ERR_INVALID_ARG,
+               "kv_store_create: non-positive dimension");
+    RA_REQUIRE(cfg->R_max <= kMaxRounds, RA_ERR_UNSUPPORTED, "kv_store_create: R_max %d exceeds %d", cfg->R_max,
+               kMaxRounds);
+    RA_REQUIRE(cfg->dtype == RA_F32 || cfg->dtype == RA_BF16, RA_ERR_UNSUPPORTED, "kv_store_create: unknown dtype");
+    RA_REQUIRE(cfg->device_pool_bytes > 0, RA_ERR_INVALID_ARG, "kv_store_create: device_pool_bytes is 0");
+    int ndev = 0, prev = 0;
+    RA_HIP_CHECK(hipGetDeviceCount(&ndev));
+    RA_REQUIRE(cfg->device >= 0 && cfg->device < ndev, RA_ERR_INVALID_ARG, "kv_store_create: device out of range");
+    RA_HIP_CHECK(hipGetDevice(&prev));
+    RA_HIP_CHECK(hipSetDevice(cfg->device));
+
+    ra_kv_store* s = new (std::nothrow) ra_kv_store();
+    RA_REQUIRE(s != nullptr, RA_ERR_OOM, "kv_store_create: out of host memory");
+    s->cfg = *cfg;
+    s->token_bytes = (size_t)cfg->Hkv * cfg->d * (cfg->dtype == RA_BF16 ? 2 : 4);
+    s->rounds.resize((size_t)cfg->B * cfg->R_max);
+    const size_t n_off = (size_t)cfg->n_layers * 2 * cfg->B * cfg->R_max;
+    const size_t n_len = (size_t)cfg->B * cfg->R_max;
+    hipError_t e = hipMalloc((void**)&s->pool, cfg->device_pool_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&s->d_off, n_off * sizeof(int64_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&s->d_len, n_len * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&s->d_n, (size_t)cfg->B * sizeof(int32_t));
+    if (e == hipSuccess) e = hipHostMalloc((void**)&s->h_off, n_off * sizeof(int64_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&s->h_len, n_len * sizeof(int32_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&s->h_n, (size_t)cfg->B * sizeof(int32_t), hipHostMallocDefault);
+    if (e == hipSuccess) {
+        s->ready.resize(cfg->n_layers, nullptr);
+        for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l)
+            e = hipEventCreateWithFlags(&s->ready[l], hipEventDisableTiming);
+    }
+    (void)hipSetDevice(prev);
+    if (e != hipSuccess) {
+        const bool oom = e == hipErrorOutOfMemory;
+        (void)hipGetLastError();
+        ra_kv_store_destroy(s);
+        return fail(oom ? RA_ERR_OOM : RA_ERR_HIP, "kv_store_create: %s", hipGetErrorString(e));
+    }
+    *out = s;
+    return RA_OK;
+}
+
+int ra_kv_store_destroy(ra_kv_store* s) {
+    if (!s) return RA_OK;
+    for (hipEvent_t ev : s->ready)
+        if (ev) (void)hipEventDestroy(ev);
+    if (s->pool) (void)hipFree(s->pool);
+    if (s->d_off) (void)hipFree(s->d_off);
+    if (s->d_len) (void)hipFree(s->d_len);
+    if (s->d_n) (void)hipFree(s->d_n);
+    if (s->h_off) (void)hipHostFree(s->h_off);
+    if (s->h_len) (void)hipHostFree(s->h_len);
+    if (s->h_n) (void)hipHostFree(s->h_n);
+    delete s;
+    return RA_OK;
+}
+
+size_t ra_kv_store_round_bytes(const ra_kv_store* s, int len) {
+    if (!s || len < 0) return 0;
+    return (size_t)s->cfg.n_layers * 2 * (size_t)len * s->token_bytes;
+}
+
+int ra_kv_store_register_round(ra_kv_store* s, int seq, int round, const void* host_kv, int len) {
+    RA_REQUIRE(s != nullptr, RA_ERR_INVALID_ARG, "kv_store_register_round: store is NULL");
+    RA_REQUIRE(seq >= 0 && seq < s->cfg.B && round >= 0 && round < s->cfg.R_max, RA_ERR_INVALID_ARG,
+               "kv_store_register_round: (seq %d, round %d) outside [0,%d) x [0,%d)", seq, round, s->cfg.B,
+               s->cfg.R_max);
+    RA_REQUIRE(len >= 0, RA_ERR_INVALID_ARG, "kv_store_register_round: negative length");
+    RA_REQUIRE(len == 0 || host_kv != nullptr, RA_ERR_INVALID_ARG, "kv_store_register_round: host_kv is NULL");
+    RA_REQUIRE(!s->staged, RA_ERR_STATE, "kv_store_register_round: rounds are staged; call ra_kv_store_release first");
+    if (len > 0)
+        RA_REQUIRE(is_pinned_host(host_kv), RA_ERR_INVALID_ARG,
+                   "kv_store_register_round: host_kv is not pinned host memory (use hipHostMalloc / pin_memory)");
+    ra_kv_store::Round& r = s->rounds[(size_t)seq * s->cfg.R_max + round];
+    r.host = static_cast<const char*>(host_kv);
+    r.len = len;
+    return RA_OK;
+}
+
+int ra_kv_store_stage(ra_kv_store* s, const int32_t* sel_idx_host, const int32_t* n_sel_host, int order,
+                      void* side_stream) {
+    RA_REQUIRE(s != nullptr && sel_idx_host != nullptr && n_sel_host != nullptr, RA_ERR_INVALID_ARG,
+               "kv_store_stage: NULL argument");
+    RA_REQUIRE(order == RA_STAGE_ROUND_MAJOR || order == RA_STAGE_LAYER_MAJOR, RA_ERR_INVALID_ARG,
+               "kv_store_stage: unknown order %d", order);
+    RA_REQUIRE(!s->staged, RA_ERR_STATE, "kv_store_stage: already staged; call ra_kv_store_release first");
+    const int B = s->cfg.B, R = s->cfg.R_max, L = s->cfg.n_layers;
+    // ---- validate the selection and place every selected round in the pool ----------------------
+    struct Job { const char* src; size_t dst_tok; int len; };
+    std::vector<Job> jobs;
+    size_t tok = 0;  // pool cursor in units of token_bytes
+    int64_t max_tokens = 0;
+    for (int b = 0; b < B; ++b) {
+        const int n = n_sel_host[b];
+        RA_REQUIRE(n >= 0 && n <= R, RA_ERR_INVALID_ARG, "kv_store_stage: n_sel[%d] = %d outside [0, %d]", b, n, R);
+        int64_t seq_tokens = 0;
+        int prev = -1;
+        for (int i = 0; i < n; ++i) {
+            const int r = sel_idx_host[(size_t)b * R + i];
+            RA_REQUIRE(r > prev && r < R, RA_ERR_INVALID_ARG,
+                       "kv_store_stage: sel_idx[%d][%d] = %d is not an ascending round index below %d", b, i, r, R);
+            prev = r;
+            const ra_kv_store::Round& rd = s->rounds[(size_t)b * R + r];
+            RA_REQUIRE(rd.len >= 0, RA_ERR_STATE, "kv_store_stage: round %d of sequence %d was never registered", r, b);
+            jobs.push_back({rd.host, tok, rd.len});
+            tok += (size_t)L * 2 * rd.len;
+            seq_tokens += rd.len;
+        }
+        if (seq_tokens > max_tokens) max_tokens = seq_tokens;
+    }
+    RA_REQUIRE(tok * s->token_bytes <= s->cfg.device_pool_bytes, RA_ERR_OOM,
+               "kv_store_stage: selected rounds need %zu bytes, the device pool has %zu", tok * s->token_bytes,
+               s->cfg.device_pool_bytes);
+    // ---- index tables of the compact views (round i of the view = i-th selected round) ----------
+    const size_t plane = (size_t)B * R;
+    for (size_t i = 0; i < (size_t)L * 2 * plane; ++i) s->h_off[i] = 0;
+    for (size_t i = 0; i < plane; ++i) s->h_len[i] = 0;
+    size_t j = 0;
+    for (int b = 0; b < B; ++b) {
+        s->h_n[b] = n_sel_host[b];
+        for (int i = 0; i < n_sel_host[b]; ++i, ++j) {
+            const Job& jb = jobs[j];
+            s->h_len[(size_t)b * R + i] = jb.len;
+            for (int l = 0; l < L; ++l) {
+                s->h_off[((size_t)l * 2 + 0) * plane + (size_t)b * R + i] = (int64_t)(jb.dst_tok + (size_t)(2 * l) * jb.len);
+                s->h_off[((size_t)l * 2 + 1) * plane + (size_t)b * R + i] =
+                    (int64_t)(jb.dst_tok + (size_t)(2 * l + 1) * jb.len);
+            }
+        }
+    }
+    // ---- enqueue the copies ------------------------------------------------------------------------
+    hipStream_t st = reinterpret_cast<hipStream_t>(side_stream);
+    RA_HIP_CHECK(hipMemcpyAsync(s->d_off, s->h_off, (size_t)L * 2 * plane * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    RA_HIP_CHECK(hipMemcpyAsync(s->d_len, s->h_len, plane * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    RA_HIP_CHECK(hipMemcpyAsync(s->d_n, s->h_n, (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    s->staged_bytes = 0;
+    s->n_copies = 0;
+    if (order == RA_STAGE_ROUND_MAJOR) {
+        for (const Job& jb : jobs) {
+            if (jb.len == 0) continue;
+            const size_t bytes = (size_t)L * 2 * jb.len * s->token_bytes;
+            RA_HIP_CHECK(hipMemcpyAsync(s->pool + jb.dst_tok * s->token_bytes, jb.src, bytes, hipMemcpyHostToDevice, st));
+            s->staged_bytes += bytes;
+            ++s->n_copies;
+        }
+        for (int l = 0; l < L; ++l) RA_HIP_CHECK(hipEventRecord(s->ready[l], st));
+    } else {
+        for (int l = 0; l < L; ++l) {
+            for (const Job& jb : jobs) {
+                if (jb.len == 0) continue;
+                const size_t bytes = (size_t)2 * jb.len * s->token_bytes;
+                const size_t o = (size_t)(2 * l) * jb.len * s->token_bytes;
+                RA_HIP_CHECK(hipMemcpyAsync(s->pool + jb.dst_tok * s->token_bytes + o, jb.src + o, bytes,
+                                            hipMemcpyHostToDevice, st));
+                s->staged_bytes += bytes;
+                ++s->n_copies;
+            }
+            RA_HIP_CHECK(hipEventRecord(s->ready[l], st));
+        }
+    }
+    s->max_tokens = max_tokens;
+    s->staged = true;
+    return RA_OK;
+}
+
+int ra_kv_store_wait_layer(ra_kv_store* s, int layer, void* compute_stream) {
+    RA_REQUIRE(s != nullptr, RA_ERR_INVALID_ARG, "kv_store_wait_layer: store is NULL");
+    RA_REQUIRE(layer >= 0 && layer < s->cfg.n_layers, RA_ERR_INVALID_ARG, "kv_store_wait_layer: layer out of range");
+    RA_REQUIRE(s->staged, RA_ERR_STATE, "kv_store_wait_layer: nothing is staged");
+    RA_HIP_CHECK(hipStreamWaitEvent(reinterpret_cast<hipStream_t>(compute_stream), s->ready[layer], 0));
+    return RA_OK;
+}
+
+int ra_kv_store_layer_view(ra_kv_store* s, int layer, ra_kv_view* out) {
+    RA_REQUIRE(s != nullptr && out != nullptr, RA_ERR_INVALID_ARG, "kv_store_layer_view: NULL argument");
+    RA_REQUIRE(layer >= 0 && layer < s->cfg.n_layers, RA_ERR_INVALID_ARG, "kv_store_layer_view: layer out of range");
+    RA_REQUIRE(s->staged, RA_ERR_STATE, "kv_store_layer_view: nothing is staged");
+    const size_t plane = (size_t)s->cfg.B * s->cfg.R_max;
+    out->k = s->pool;
+    out->v = s->pool;
+    out->seg_off = s->d_off + ((size_t)layer * 2 + 0) * plane;
+    out->seg_off_v = s->d_off + ((size_t)layer * 2 + 1) * plane;
+    out->seg_len = s->d_len;
+    out->n_rounds = s->d_n;
+    out->block_table = nullptr;
+    out->block_size = 0;
+    out->max_blocks = 0;
+    out->B = s->cfg.B;
+    out->R_max = s->cfg.R_max;
+    out->Hkv = s->cfg.Hkv;
+    out->d = s->cfg.d;
+    out->dtype = s->cfg.dtype;
+    out->reserved = 0;
+    out->max_tokens = s->max_tokens;
+    return RA_OK;
+}
+
+int ra_kv_store_stats(const ra_kv_store* s, uint64_t* staged_bytes, uint64_t* registered_bytes, uint64_t* n_copies) {
+    RA_REQUIRE(s != nullptr, RA_ERR_INVALID_ARG, "kv_store_stats: store is NULL");
+    if (staged_bytes) *staged_bytes = s->staged_bytes;
+    if (n_copies) *n_copies = s->n_copies;
+    if (registered_bytes) {
+        uint64_t t = 0;
+        for (const auto& r : s->rounds)
+            if (r.len > 0) t += (uint64_t)s->cfg.n_layers * 2 * r.len * s->token_bytes;
+        *registered_bytes = t;
+    }
+    return RA_OK;
+}
+
+int ra_kv_store_release(ra_kv_store* s) {
+    RA_REQUIRE(s != nullptr, RA_ERR_INVALID_ARG, "kv_store_release: store is NULL");
+    if (s->staged) {
+        // the pinned mirrors of the index tables are rewritten by the next stage call: make sure the
+        // copies that read them have finished
+        RA_HIP_CHECK(hipEventSynchronize(s->ready[s->cfg.n_layers - 1]));
+        s->staged = false;
+    }
+    return RA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,161 @@
+// Device-side building blocks of the bandwidth-bound streaming kernels (decode attention and
+// decode-shape round scores): the per-workgroup table of round segments, the lane layout that
+// reads K/V rows with full 16-byte-per-lane coalescing, and the wavefront-level reductions.
+//
+// Lane layout inside a 64-wide wavefront: the wave is four rows of 16 lanes.  Row `grp` works on
+// one token at a time and lane `sub` of the row owns d/16 consecutive channels of that token, so
+// one load instruction of the wave covers four consecutive token rows (1 KB for bf16, d = 128).
+// A dot product is finished with four DPP adds inside the 16-lane row; nothing goes through LDS.
+#pragma once
+
+#include "common.hpp"
+
+namespace ra {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float as_f32(uint32_t x) { return __builtin_bit_cast(float, x); }
+__device__ __forceinline__ uint32_t as_u32(float x) { return __builtin_bit_cast(uint32_t, x); }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+    return as_f32((uint32_t)__builtin_amdgcn_update_dpp(0, (int)as_u32(v), CTRL, 0xf, 0xf, false));
+}
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
+__device__ __forceinline__ float row16_sum(float v) {
+    v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_mov<0x141>(v);  // row_half_mirror
+    v += dpp_mov<0x140>(v);  // row_mirror
+    return v;
+}
+__device__ __forceinline__ float xrow_get(float v, int xor_mask) { return __shfl_xor(v, xor_mask, 64); }
+
+// Element-type specific pieces.  A lane's share of one K or V row is WORDS 32-bit words.
+struct F32 {};
+struct BF16 {};
+template <typename T, int EPL>
+struct RowOps;
+
+template <int EPL>
+struct RowOps<F32, EPL> {
+    static constexpr int WORDS = EPL;
+    static constexpr int ELEM_BYTES = 4;
+    __device__ static __forceinline__ float dot(const uint32_t* k, const uint32_t* q) {
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < WORDS; ++e) acc = __builtin_fmaf(as_f32(k[e]), as_f32(q[e]), acc);
+        return acc;
+    }
+    __device__ static __forceinline__ void widen(const uint32_t* w, float* f) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) f[e] = as_f32(w[e]);
+    }
+};
+
+template <int EPL>
+struct RowOps<BF16, EPL> {
+    static constexpr int WORDS = EPL / 2;
+    static constexpr int ELEM_BYTES = 2;
+    // Both operands are bf16, so every product is exact in fp32; accumulation is fp32.
+    __device__ static __forceinline__ float dot(const uint32_t* k, const uint32_t* q) {
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < WORDS; ++e)
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k[e]), __builtin_bit_cast(bf16x2_t, q[e]),
+                                                  acc, false);
+        return acc;
+    }
+    __device__ static __forceinline__ void widen(const uint32_t* w, float* f) {
+#pragma unroll
+        for (int e = 0; e < WORDS; ++e) {
+            f[2 * e] = as_f32(w[e] << 16);
+            f[2 * e + 1] = as_f32(w[e] & 0xffff0000u);
+        }
+    }
+};
+
+template <int WORDS>
+struct Frag {
+    uint32_t w[WORDS];
+};
+
+template <int WORDS>
+__device__ __forceinline__ Frag<WORDS> load_frag(const char* p) {
+    Frag<WORDS> f;
+    if constexpr (WORDS == 2) {
+        uint2 t = *reinterpret_cast<const uint2*>(p);
+        f.w[0] = t.x;
+        f.w[1] = t.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < WORDS / 4; ++i) {
+            uint4 t = reinterpret_cast<const uint4*>(p)[i];
+            f.w[4 * i + 0] = t.x;
+            f.w[4 * i + 1] = t.y;
+            f.w[4 * i + 2] = t.z;
+            f.w[4 * i + 3] = t.w;
+        }
+    }
+    return f;
+}
+
+// ---- per-workgroup table of the round segments it may touch ------------------------------------
+// slot i < n_hist is a history round, slot n_hist (if present) is the current round.  `cum` is the
+// exclusive prefix sum of the segments' unit counts (a unit = 16 tokens, never crossing a segment).
+struct SlotTable {
+    long long* off_k;  // [cap]   segment start: tokens (contiguous) or block-table slots (paged)
+    long long* off_v;  // [cap]
+    int* len;          // [cap]
+    int* cum;          // [cap + 1]
+    __host__ __device__ static size_t bytes(int cap) { return (size_t)cap * 24 + 4; }
+    __device__ void carve(char* smem, int cap) {
+        off_k = reinterpret_cast<long long*>(smem);
+        off_v = off_k + cap;
+        len = reinterpret_cast<int*>(off_v + cap);
+        cum = len + cap;
+    }
+};
+
+// Exclusive prefix sum, in place, of cum[0..n) by the first wavefront; cum[n] receives the total.
+// Must be called by all threads of the workgroup (it synchronises).
+__device__ inline void exclusive_scan_units(int* cum, int n) {
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        const int per = (n + 63) >> 6;
+        const int base = lane * per;
+        int sum = 0;
+        for (int j = 0; j < per; ++j)
+            if (base + j < n) sum += cum[base + j];
+        int incl = sum;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int t = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += t;
+        }
+        int excl = incl - sum;
+        for (int j = 0; j < per; ++j)
+            if (base + j < n) {
+                int u = cum[base + j];
+                cum[base + j] = excl;
+                excl += u;
+            }
+        if (lane == 63) cum[n] = incl;
+    }
+    __syncthreads();
+}
+
+// Largest slot with cum[slot] <= u, for 0 <= u < cum[n].
+__device__ __forceinline__ int find_slot(const int* cum, int n, int u) {
+    int lo = 0, hi = n;  // invariant: cum[lo] <= u < cum[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (cum[mid] <= u) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+}  // namespace ra

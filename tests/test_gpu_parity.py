@@ -1,0 +1,262 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Bars: selected indices bit-exact; attention outputs within 2e-3 (max over rows of
+max|err| / max|ref|), and, for the fp32-accumulating streaming kernels, within the much tighter
+bound their arithmetic implies; round scores within 1e-5 absolute."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_15294_amd as ra
+from oracle import pipeline
+from oracle import round_attention as ora
+from synth import make_workload
+from synth.device import Engine, device_view, sel_to_device, to_device
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL = 2e-3        # the contract
+STREAM_TOL = 5e-5     # fp32 accumulation of exact bf16 products over <= 2^17 terms, exp2 to ~2 ulp
+SCORE_TOL = 1e-5
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _oracle_attention(w, layer, sels):
+    outs, lses = [], []
+    for b in range(w.B):
+        o, l = pipeline.attention_for_sequence(w, b, layer, sels[b])
+        outs.append(o)
+        lses.append(l)
+    return np.stack(outs), np.stack(lses)
+
+
+def _gpu_decode(eng, w, layer, sels, view=None, cur_len_dev=None, use_sel=True):
+    view = view or device_view(w, layer)
+    q = to_device(w.q(layer)[:, 0], w.dtype)
+    sel_idx, n_sel = sel_to_device(sels, view.R_max) if use_sel else (None, None)
+    ck = cv = cl = None
+    if w.cur_len:
+        ck, cv = to_device(w.cur_k(layer), w.dtype), to_device(w.cur_v(layer), w.dtype)
+        cl = cur_len_dev if cur_len_dev is not None else torch.full((w.B,), w.cur_len, dtype=torch.int32, device="cuda")
+    out, lse = ra.ra_round_sparse_attn_decode(eng.ctx, q, view, sel_idx, n_sel, ck, cv, cl, scale=w.scale)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), lse.cpu().numpy()
+
+
+DECODE_CASES = {
+    # name: (config, overrides, selections or None for "all rounds")
+    "f32_d64_g2_tiny": ("cfg1", dict(), [[1, 3]]),
+    "f32_d64_g2_all": ("cfg1", dict(), None),
+    "bf16_g4_ragged": ("cfg2", dict(B=3, R=7, lens=[[5, 16, 17, 0, 33, 1, 250], [64, 3, 0, 0, 15, 48, 31],
+                                                   [700, 1, 1, 1, 1, 1, 1]]),
+                       [[0, 2, 4, 6], [1, 4], [0, 3, 6]]),
+    "bf16_g4_cur": ("cfg2", dict(B=2, R=4, cur_len=37, lens=[[40, 9, 130, 77], [3, 300, 20, 5]]), [[2], [0, 1, 3]]),
+    "bf16_g4_cur_only": ("cfg2", dict(B=2, R=3, cur_len=21, lens=[[40, 9, 13], [3, 30, 20]]), [[], []]),
+    "bf16_g8_paged": ("cfg5", dict(B=3, R=6, lens=[[300, 17, 16, 1, 999, 50], [31, 32, 33, 0, 64, 5],
+                                                  [450, 450, 450, 450, 450, 450]]),
+                      [[0, 1, 4], [0, 1, 2, 3, 4, 5], [1, 5]]),
+    "bf16_g8_contig": ("cfg5", dict(B=2, R=5, block_size=0, length=("uniform", 30, 400)), [[0, 4], [1, 2, 3]]),
+    "bf16_g1_mha": ("cfg2", dict(B=2, R=5, Hq=8, Hkv=8, length=("uniform", 10, 200)), [[0, 1, 4], [2]]),
+    "bf16_g2": ("cfg2", dict(B=2, R=5, Hq=16, Hkv=8, length=("uniform", 10, 200)), [[3], [0, 2, 4]]),
+    "bf16_d64": ("cfg2", dict(B=2, R=5, d=64, length=("uniform", 10, 200)), [[0, 3], [1, 2, 4]]),
+    "f32_d128_g4": ("cfg2", dict(B=2, R=4, dtype="f32", length=("uniform", 10, 120)), [[0, 3], [1, 2]]),
+    "bf16_g4_many_rounds": ("cfg4", dict(B=2, R=200, length=("lognormal", 40.0, 0.8, 9000), n_post_layers=1),
+                            [list(range(0, 200, 7)), list(range(3, 200, 11))]),
+}
+
+
+@pytest.mark.parametrize("name", list(DECODE_CASES))
+def test_decode_matches_oracle(name):
+    cfg, over, sels = DECODE_CASES[name]
+    w = make_workload(cfg, **over)
+    if sels is None:
+        sels = [list(range(w.n_rounds(b))) for b in range(w.B)]
+    _say(f"decode case {name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} d={w.d} dtype={w.dtype} block={w.block_size}")
+    eng = Engine(w)
+    ref_o, ref_l = _oracle_attention(w, 1, sels)
+    out, lse = _gpu_decode(eng, w, 1, sels)
+    err = ora.row_error(out, ref_o[:, 0])
+    _say(f"  row error {err:.3e}, lse error {np.abs(lse - ref_l[:, 0]).max():.3e}")
+    assert err < OUT_TOL and err < STREAM_TOL
+    assert np.allclose(lse, ref_l[:, 0], rtol=0, atol=2e-5 * max(1.0, np.abs(ref_l).max()))
+    eng.close()
+
+
+def test_decode_identity_selection_equals_explicit_all_and_is_deterministic():
+    w = make_workload("cfg2", B=2, R=6, length=("uniform", 20, 300))
+    eng = Engine(w)
+    view = device_view(w, 1)
+    all_sel = [list(range(6)), list(range(6))]
+    a, la = _gpu_decode(eng, w, 1, all_sel, view=view)
+    b, lb = _gpu_decode(eng, w, 1, all_sel, view=view, use_sel=False)
+    c, lc = _gpu_decode(eng, w, 1, all_sel, view=view)
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
+    assert np.array_equal(a, c) and np.array_equal(la, lc)
+    # order of the selected list does not matter for the result beyond rounding
+    d, _ = _gpu_decode(eng, w, 1, [[5, 3, 4, 0, 2, 1], [1, 0, 3, 2, 5, 4]], view=view)
+    assert ora.row_error(d, a) < STREAM_TOL
+    eng.close()
+
+
+def test_decode_per_sequence_cur_len_and_empty_key_set():
+    w = make_workload("cfg2", B=3, R=3, cur_len=40, lens=[[20, 30, 40]] * 3)
+    eng = Engine(w)
+    cur_len = torch.tensor([40, 7, 0], dtype=torch.int32, device="cuda")
+    sels = [[1], [0, 2], []]
+    out, lse = _gpu_decode(eng, w, 1, sels, cur_len_dev=cur_len)
+    for b, n_cur in enumerate([40, 7, 0]):
+        if b == 2:
+            assert np.all(out[b] == 0) and np.all(np.isneginf(lse[b]))      # empty key set: zeros, lse = -inf
+            continue
+        q = w.q(1)[b]
+        ks = [w.k_round(b, 1, r) for r in range(3)]
+        vs = [w.v_round(b, 1, r) for r in range(3)]
+        ro, rl = ora.sparse_attention(q, ks, vs, sels[b], w.scale, w.cur_k(1)[b, :n_cur], w.cur_v(1)[b, :n_cur])
+        assert ora.row_error(out[b], ro[0]) < STREAM_TOL
+    eng.close()
+
+
+SCORE_CASES = {
+    "f32_cfg1": ("cfg1", dict()),
+    "bf16_g4_ragged": ("cfg2", dict(B=3, R=7, lens=[[5, 16, 17, 0, 33, 1, 250], [64, 3, 0, 0, 15, 48, 31],
+                                                   [700, 1, 1, 1, 1, 1, 1]])),
+    "bf16_g8_paged": ("cfg5", dict(B=2, R=6, lens=[[300, 17, 16, 1, 999, 50], [31, 32, 33, 0, 64, 5]])),
+    "bf16_uneven_round_counts": ("cfg2", dict(B=3, lens=[[30, 40], [10, 20, 30, 40, 50], []])),
+    "bf16_qlen3_cur": ("cfg2", dict(B=2, R=5, q_len=3, cur_len=9, length=("uniform", 10, 150))),
+    "bf16_qlen4_nocur": ("cfg2", dict(B=2, R=5, q_len=4, cur_len=0, length=("uniform", 10, 150))),
+    "bf16_qlen1_cur_cancels": ("cfg2", dict(B=2, R=5, q_len=1, cur_len=6, length=("uniform", 10, 150))),
+}
+
+
+@pytest.mark.parametrize("name", list(SCORE_CASES))
+def test_round_scores_match_oracle(name):
+    cfg, over = SCORE_CASES[name]
+    w = make_workload(cfg, **over)
+    _say(f"scores case {name}: B={w.B} R_max={w.R_max} q_len={w.q_len} cur_len={w.cur_len}")
+    eng = Engine(w)
+    view = device_view(w, 0, with_v=False)
+    q = to_device(w.q(0), w.dtype)
+    ck = to_device(w.cur_k(0), w.dtype) if w.cur_len else None
+    P, S = ra.ra_round_scores(eng.ctx, q, view, ck, scale=w.scale)
+    torch.cuda.synchronize()
+    P, S = P.cpu().numpy(), S.cpu().numpy()
+    for b in range(w.B):
+        rP, rS = pipeline.scores_for_sequence(w, b)
+        R = w.n_rounds(b)
+        if R:
+            assert np.abs(P[b, :, :R] - rP).max() < SCORE_TOL and np.abs(S[b, :R] - rS).max() < SCORE_TOL
+        assert np.all(P[b, :, R:] == 0) and np.all(S[b, R:] == 0)
+        if R and w.total_tokens(b):
+            assert np.abs(P[b].sum(axis=1) - 1).max() < SCORE_TOL       # per-head scores sum to one
+    eng.close()
+
+
+def _oracle_select_on(S_row, R, params):
+    return ora.select_rounds([float(x) for x in S_row[:R]], **params)[0]
+
+
+SELECT_PARAMS = [
+    dict(strategy=ora.ADAPTIVE),
+    dict(strategy=ora.ADAPTIVE, lam=0.0),
+    dict(strategy=ora.ADAPTIVE, lam=0.5, ddof=1),
+    dict(strategy=ora.ADAPTIVE, lam=3.0, min_rounds=2),
+    dict(strategy=ora.ADAPTIVE, lam=-1.0, max_rounds=5),
+    dict(strategy=ora.TOP_FRACTION),
+    dict(strategy=ora.TOP_FRACTION, fraction=0.33),
+    dict(strategy=ora.THRESHOLD),
+    dict(strategy=ora.THRESHOLD, threshold=0.02, min_rounds=0),
+]
+
+
+@pytest.mark.parametrize("pi", range(len(SELECT_PARAMS)))
+def test_select_function_parity_is_bit_exact(pi):
+    params = SELECT_PARAMS[pi]
+    rng = np.random.default_rng(100 + pi)
+    B, R_max = 12, 300
+    n_rounds = np.array([300, 1, 2, 0, 64, 65, 256, 257, 10, 20, 200, 299], dtype=np.int32)
+    S = np.zeros((B, R_max), dtype=np.float32)
+    for b in range(B):
+        R = n_rounds[b]
+        if R == 0:
+            continue
+        x = rng.random(R) ** (1 + b)
+        if b % 3 == 0:
+            x = np.round(x, 2)              # exact ties
+        if b == 4:
+            x[:] = 1.0                      # uniform
+        S[b, :R] = (x / max(x.sum(), 1e-30)).astype(np.float32)
+    w = make_workload("cfg1")
+    eng = Engine(w)
+    p = ra.make_select_params(strategy=params["strategy"], lam=params.get("lam", 1.0),
+                              fraction=params.get("fraction", 0.10), threshold=params.get("threshold", 0.10),
+                              ddof=params.get("ddof", 0), min_rounds=params.get("min_rounds", 1),
+                              max_rounds=params.get("max_rounds", 0))
+    sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, torch.from_numpy(S).cuda(), torch.from_numpy(n_rounds).cuda(), p)
+    torch.cuda.synchronize()
+    sel_idx, n_sel = sel_idx.cpu().numpy(), n_sel.cpu().numpy()
+    for b in range(B):
+        expect = _oracle_select_on(S[b], n_rounds[b], params)
+        got = sel_idx[b, :n_sel[b]].tolist()
+        assert got == expect, (b, params)
+        assert np.all(sel_idx[b, n_sel[b]:] == -1)
+    eng.close()
+
+
+def _run_gpu_pipeline(eng, w, select_params=None, block_size=None):
+    wview = device_view(w, 0, with_v=False, block_size=block_size)
+    q0 = to_device(w.q(0), w.dtype)
+    ck0 = to_device(w.cur_k(0), w.dtype) if w.cur_len else None
+    P, S = ra.ra_round_scores(eng.ctx, q0, wview, ck0, scale=w.scale)
+    sp = select_params or {}
+    p = ra.make_select_params(strategy=sp.get("strategy", 0), lam=sp.get("lam", 1.0))
+    sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, wview.n_rounds, p)
+    lview = device_view(w, 1, block_size=block_size)
+    q1 = to_device(w.q(1)[:, 0], w.dtype)
+    out, lse = ra.ra_round_sparse_attn_decode(eng.ctx, q1, lview, sel_idx, n_sel, scale=w.scale)
+    torch.cuda.synchronize()
+    return P.cpu().numpy(), S.cpu().numpy(), sel_idx.cpu().numpy(), n_sel.cpu().numpy(), out.cpu().numpy()
+
+
+@pytest.mark.parametrize("cfg,over", [("cfg1", {}), ("cfg2", {}), ("cfg5", dict(B=4)), ("cfg4", dict(B=2, n_post_layers=1, length=("lognormal", 400.0, 0.8, 16384)))])
+def test_decode_pipeline_end_to_end(cfg, over):
+    """scores -> selection -> sparse decode on the GPU against the oracle's own pipeline."""
+    w = make_workload(cfg, **over)
+    _say(f"pipeline {cfg} {over}")
+    eng = Engine(w)
+    P, S, sel_idx, n_sel, out = _run_gpu_pipeline(eng, w)
+    ref = pipeline.run(w)
+    for b, r in enumerate(ref):
+        R = w.n_rounds(b)
+        assert np.abs(S[b, :R] - r.S).max() < SCORE_TOL
+        assert r.info["margin"] > 1e-4, "ill-conditioned seed: a score sits on the cut"
+        assert sel_idx[b, :n_sel[b]].tolist() == r.sel                       # bit-exact indices
+        # function parity: the oracle's rule applied to the GPU's own fp32 scores
+        assert sel_idx[b, :n_sel[b]].tolist() == ora.select_rounds([float(x) for x in S[b, :R]])[0]
+        err = ora.row_error(out[b], r.out[1][0])
+        assert err < OUT_TOL and err < STREAM_TOL
+    eng.close()
+
+
+def test_workspace_and_argument_errors():
+    w = make_workload("cfg2", B=2, R=3, length=("uniform", 10, 50))
+    eng = Engine(w)
+    view = device_view(w, 1)
+    q = to_device(w.q(1)[:, 0], w.dtype)
+    ra.ra_set_workspace(eng.ctx, eng.workspace[:256])
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_round_sparse_attn_decode(eng.ctx, q, view, scale=w.scale)
+    assert e.value.code == ra.RA_ERR_WORKSPACE
+    ra.ra_set_workspace(eng.ctx, eng.workspace)
+    with pytest.raises(ra.RaError) as e:                                       # Hq not a multiple of Hkv
+        ra.ra_round_sparse_attn_decode(eng.ctx, q[:, :30].contiguous(), view, scale=w.scale)
+    assert e.value.code == ra.RA_ERR_INVALID_ARG
+    with pytest.raises(ra.RaError) as e:                                       # group size 3 is not built
+        ra.ra_round_sparse_attn_decode(eng.ctx, q[:, :24].contiguous(), view, scale=w.scale)
+    assert e.value.code == ra.RA_ERR_UNSUPPORTED
+    sel_idx, n_sel = sel_to_device([[0], [1]], 3)
+    with pytest.raises(ra.RaError) as e:                                       # sel_idx without n_sel
+        ra.ra_round_sparse_attn_decode(eng.ctx, q, view, sel_idx, None, scale=w.scale)
+    assert e.value.code == ra.RA_ERR_INVALID_ARG
+    eng.close()
