@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--lam", type=float, default=1.0, help="multiplier of the adaptive selection rule")
     ap.add_argument("--alpha", type=float, default=None, help="override the key bias strength of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--replicas", type=int, default=0, help="input replicas rotated through (0 = enough to defeat the Infinity Cache)")
     ap.add_argument("--cpu-baseline-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     return ap.parse_args()
 
@@ -138,7 +139,7 @@ def main():
     sel_h = sel_idx.cpu().numpy()
     sel_tokens = int(sum(int(w.lens[b][sel_h[b, :n_sel_h[b]]].sum()) for b in range(w.B)))
     step_bytes = hist_tokens * k_bytes_tok + sel_tokens * 2 * k_bytes_tok
-    n_rep = int(max(1, min(8, -(-CACHE_DEFEAT_BYTES // max(step_bytes, 1)))))
+    n_rep = args.replicas or int(max(1, min(8, -(-CACHE_DEFEAT_BYTES // max(step_bytes, 1)))))
 
     def clone_view(v):
         k, vv, seg_off, seg_len, n_rounds, bt, seg_off_v = v.tensors

@@ -59,6 +59,9 @@ int decode_splits(int num_cu, int B, int Hkv, int64_t max_tokens);
 
 constexpr int kUnitTokens = 16;   // tokens per work unit of the streaming kernels (= one paged block)
 constexpr int kMaxRounds = 1024;  // largest R_max any entry point accepts
+// Head of the workspace kept for small integer state (arrival counters) that must read zero at the
+// start of every launch: ra_set_workspace clears it once and the kernels restore it.
+constexpr size_t kWsReserved = 16384;
 
 // ---- device helpers --------------------------------------------------------------------------
 constexpr float kLog2e = 1.4426950408889634f;

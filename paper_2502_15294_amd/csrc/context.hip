@@ -111,9 +111,11 @@ int ra_workspace_bytes(const ra_problem* p, size_t* bytes_out) {
     const size_t rows = (size_t)p->B * p->q_len_max * p->Hq;
     // attention partials: up to 64 splits of (d accumulators + running max + running sum) per output row
     const size_t attn = rows * 64 * ((size_t)p->d + 2) * sizeof(float);
-    // score intermediates: one log-sum-exp per (row, round) plus one for the current round
-    const size_t sc = rows * ((size_t)p->R_max + 1) * sizeof(float);
-    *bytes_out = align_up(attn, 256) + align_up(sc, 256) + 256;
+    // score intermediates: one log-sum-exp per (row, 256-token chunk), plus a per-head score buffer
+    const size_t chunks = (size_t)(p->max_tokens / 256) + p->R_max + 2;
+    const size_t sc = rows * chunks * sizeof(float) + (size_t)p->B * p->Hq * p->R_max * sizeof(float);
+    const size_t both = align_up(attn, 256) > align_up(sc, 256) + 256 ? align_up(attn, 256) : align_up(sc, 256) + 256;
+    *bytes_out = kWsReserved + both + 3 * 256;
     return RA_OK;
 }
 
@@ -121,6 +123,9 @@ int ra_set_workspace(ra_ctx* ctx, void* device_ptr, size_t bytes) {
     RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "ra_set_workspace: ctx is NULL");
     RA_REQUIRE(device_ptr != nullptr || bytes == 0, RA_ERR_INVALID_ARG, "ra_set_workspace: NULL pointer with bytes > 0");
     RA_REQUIRE(((uintptr_t)device_ptr & 255u) == 0, RA_ERR_INVALID_ARG, "ra_set_workspace: pointer not 256-byte aligned");
+    RA_REQUIRE(bytes == 0 || bytes >= kWsReserved, RA_ERR_WORKSPACE,
+               "ra_set_workspace: a workspace must have at least %zu bytes", kWsReserved);
+    if (bytes) RA_HIP_CHECK(hipMemset(device_ptr, 0, kWsReserved));  // arrival counters start at zero
     ctx->ws.base = (char*)device_ptr;
     ctx->ws.bytes = bytes;
     return RA_OK;

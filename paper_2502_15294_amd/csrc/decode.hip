@@ -6,8 +6,11 @@
 // Work decomposition: grid (S, Hkv, B).  A workgroup (4 wavefronts) owns KV head g of sequence b and
 // the s-th of S equal shares of that sequence's 16-token units; its waves take units round-robin,
 // keep an online-softmax state per 16-lane row in registers, and merge rows, then waves (LDS), into
-// one partial (max, sum, d accumulators) per query head.  A second small kernel merges the S partials.
+// one partial (max, sum, d accumulators) per query head.  A sequence with a short selection is not
+// split and its output is written directly; otherwise a second small kernel merges the pieces.
 #include "stream_kv.hpp"
+
+#include <stdlib.h>
 
 namespace ra {
 
@@ -22,11 +25,28 @@ struct DecodeArgs {
     int cur_cap;
     int Hq;
     int S;
-    float c;  // scale * log2(e)
+    int min_units;  // a sequence is never cut into pieces of fewer 16-token units than this
+    float c;      // scale * log2(e)
+    float scale;
     float* part_acc;  // [B][Hq][S][D]
     float* part_m;    // [B][Hq][S]  running max of the raw (unscaled) logits
     float* part_l;    // [B][Hq][S]  sum of 2^((logit - max) * c)
+    int* n_parts;     // [B]         number of pieces sequence b was really cut into
+    float* out;       // [B][Hq][D]
+    float* lse;       // [B][Hq] or null
 };
+
+// A sequence is cut into at most S pieces, but never into pieces of fewer units than this: short
+// selections would otherwise pay the per-workgroup set-up for a handful of tokens.
+constexpr int kMinUnitsPerWorkgroup = 8;
+static int min_units_per_workgroup() {
+    static const int v = [] {
+        const char* e = getenv("RA_DECODE_MIN_UNITS");  // tuning knob for experiments
+        const int x = e ? atoi(e) : kMinUnitsPerWorkgroup;
+        return x > 0 ? x : kMinUnitsPerWorkgroup;
+    }();
+    return v;
+}
 
 template <typename T, int D, int G, bool PAGED>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
@@ -74,8 +94,10 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     }
     exclusive_scan_units(tab.cum, n_slots);
     const int U = n_slots > 0 ? tab.cum[n_slots] : 0;
-    const int u_lo = (int)(((long long)U * s) / a.S);
-    const int u_hi = (int)(((long long)U * (s + 1)) / a.S);
+    const int S_eff = min(a.S, max(1, U / a.min_units));  // pieces this sequence is really cut into
+    if (s >= S_eff) return;
+    const int u_lo = (int)(((long long)U * s) / S_eff);
+    const int u_hi = (int)(((long long)U * (s + 1)) / S_eff);
 
     // ---- this lane's share of the G queries ----------------------------------------------------
     uint32_t qw[G][WORDS];
@@ -246,38 +268,73 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         }
     }
     __syncthreads();
-    for (int idx = tid; idx < G * D; idx += 256) {
-        const int h = idx / D, dim = idx - h * D;
-        float M = fmaxf(fmaxf(sm[h], sm[G + h]), fmaxf(sm[2 * G + h], sm[3 * G + h]));
-        float num = 0.f, den = 0.f;
+    if (s == 0 && g == 0 && tid == 0) a.n_parts[b] = S_eff;
+    const size_t row0 = (size_t)b * a.Hq + (size_t)g * G;
+    if (S_eff > 1) {
+        for (int idx = tid; idx < G * D; idx += 256) {
+            const int h = idx / D, dim = idx - h * D;
+            float M = fmaxf(fmaxf(sm[h], sm[G + h]), fmaxf(sm[2 * G + h], sm[3 * G + h]));
+            float num = 0.f, den = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float f = fast_exp2((sm[w * G + h] - M) * a.c);
-            num = __builtin_fmaf(sacc[(w * G + h) * D + dim], f, num);
-            den = __builtin_fmaf(sl[w * G + h], f, den);
+            for (int w = 0; w < 4; ++w) {
+                const float f = fast_exp2((sm[w * G + h] - M) * a.c);
+                num = __builtin_fmaf(sacc[(w * G + h) * D + dim], f, num);
+                den = __builtin_fmaf(sl[w * G + h], f, den);
+            }
+            const size_t slot_row = (row0 + h) * a.S + s;
+            a.part_acc[slot_row * D + dim] = num;
+            if (dim == 0) {
+                a.part_m[slot_row] = M;
+                a.part_l[slot_row] = den;
+            }
         }
-        const size_t row = ((size_t)b * a.Hq + (size_t)g * G + h) * a.S + s;
-        a.part_acc[row * D + dim] = num;
-        if (dim == 0) {
-            a.part_m[row] = M;
-            a.part_l[row] = den;
+    } else {
+        for (int idx = tid; idx < G * D; idx += 256) {
+            const int h = idx / D, dim = idx - h * D;
+            float M = fmaxf(fmaxf(sm[h], sm[G + h]), fmaxf(sm[2 * G + h], sm[3 * G + h]));
+            float num = 0.f, den = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float f = fast_exp2((sm[w * G + h] - M) * a.c);
+                num = __builtin_fmaf(sacc[(w * G + h) * D + dim], f, num);
+                den = __builtin_fmaf(sl[w * G + h], f, den);
+            }
+            a.out[(row0 + h) * D + dim] = den > 0.f ? num / den : 0.f;
+            if (a.lse && dim == 0)
+                a.lse[row0 + h] = den > 0.f ? __builtin_fmaf(M, a.scale, __builtin_logf(den)) : -__builtin_inff();
         }
     }
 }
 
-// Merge the S partials of every (sequence, query head) row; grid (B * Hq), block D.
+// Merge the pieces of every (sequence, query head) row that was split; grid (B * Hq), block D.
 template <int D>
 __global__ __launch_bounds__(D) void combine_kernel(const float* part_acc, const float* part_m, const float* part_l,
-                                                   int S, float c, float scale, float* out, float* lse) {
+                                                   const int* n_parts, int S, int Hq, float c, float scale,
+                                                   float* out, float* lse) {
     const size_t row = blockIdx.x;
+    const int n = n_parts[row / Hq];
+    if (n <= 1) return;  // written directly by the streaming kernel
     const int dim = threadIdx.x;
+    const float* pm = part_m + row * S;
+    const float* pl = part_l + row * S;
+    const float* pa = part_acc + row * S * D + dim;
     float M = kNegBig;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, part_m[row * S + s]);
+    for (int p = 0; p < n; ++p) M = fmaxf(M, pm[p]);
     float num = 0.f, den = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const float f = fast_exp2((part_m[row * S + s] - M) * c);
-        num = __builtin_fmaf(part_acc[(row * S + s) * D + dim], f, num);
-        den = __builtin_fmaf(part_l[row * S + s], f, den);
+    int p = 0;
+    for (; p + 4 <= n; p += 4) {
+        float a0 = pa[(size_t)p * D], a1 = pa[(size_t)(p + 1) * D], a2 = pa[(size_t)(p + 2) * D], a3 = pa[(size_t)(p + 3) * D];
+        float f0 = fast_exp2((pm[p] - M) * c), f1 = fast_exp2((pm[p + 1] - M) * c);
+        float f2 = fast_exp2((pm[p + 2] - M) * c), f3 = fast_exp2((pm[p + 3] - M) * c);
+        num = __builtin_fmaf(a0, f0, num); den = __builtin_fmaf(pl[p], f0, den);
+        num = __builtin_fmaf(a1, f1, num); den = __builtin_fmaf(pl[p + 1], f1, den);
+        num = __builtin_fmaf(a2, f2, num); den = __builtin_fmaf(pl[p + 2], f2, den);
+        num = __builtin_fmaf(a3, f3, num); den = __builtin_fmaf(pl[p + 3], f3, den);
+    }
+    for (; p < n; ++p) {
+        const float f = fast_exp2((pm[p] - M) * c);
+        num = __builtin_fmaf(pa[(size_t)p * D], f, num);
+        den = __builtin_fmaf(pl[p], f, den);
     }
     out[row * D + dim] = den > 0.f ? num / den : 0.f;
     if (lse && dim == 0) lse[row] = den > 0.f ? __builtin_fmaf(M, scale, __builtin_logf(den)) : -__builtin_inff();
@@ -335,7 +392,10 @@ extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void
     int64_t max_tok = layer->max_tokens + (has_cur ? cur_cap : 0);
     const int S = decode_splits(ctx->num_cu, B, layer->Hkv, max_tok);
     const size_t rows = (size_t)B * Hq;
-    const size_t need = align_up(rows * S * D * sizeof(float), 256) + 2 * align_up(rows * S * sizeof(float), 256);
+    RA_REQUIRE((size_t)B * sizeof(int) <= kWsReserved, RA_ERR_UNSUPPORTED, "decode: B = %d exceeds %zu", B,
+               kWsReserved / sizeof(int));
+    const size_t need = kWsReserved + align_up(rows * S * D * sizeof(float), 256) +
+                        2 * align_up(rows * S * sizeof(float), 256);
     RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= need, RA_ERR_WORKSPACE,
                "decode: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, need);
 
@@ -350,9 +410,14 @@ extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void
     a.cur_cap = has_cur ? cur_cap : 0;
     a.Hq = Hq;
     a.S = S;
+    a.min_units = min_units_per_workgroup();
     a.c = scale * kLog2e;
-    a.part_acc = reinterpret_cast<float*>(ctx->ws.base);
-    a.part_m = reinterpret_cast<float*>(ctx->ws.base + align_up(rows * S * D * sizeof(float), 256));
+    a.scale = scale;
+    a.out = out;
+    a.lse = lse;
+    a.n_parts = reinterpret_cast<int*>(ctx->ws.base);
+    a.part_acc = reinterpret_cast<float*>(ctx->ws.base + kWsReserved);
+    a.part_m = reinterpret_cast<float*>(ctx->ws.base + kWsReserved + align_up(rows * S * D * sizeof(float), 256));
     a.part_l = reinterpret_cast<float*>(reinterpret_cast<char*>(a.part_m) + align_up(rows * S * sizeof(float), 256));
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -368,12 +433,14 @@ extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void
                       : dispatch_g<F32, 64>(G, paged, grid, 0, st, a, tab_bytes);
     }
     if (rc) return rc;
-    if (D == 128)
-        hipLaunchKernelGGL((combine_kernel<128>), dim3((unsigned)rows), dim3(128), 0, st, a.part_acc, a.part_m, a.part_l,
-                           S, a.c, scale, out, lse);
-    else
-        hipLaunchKernelGGL((combine_kernel<64>), dim3((unsigned)rows), dim3(64), 0, st, a.part_acc, a.part_m, a.part_l, S,
-                           a.c, scale, out, lse);
+    if (S > 1) {
+        if (D == 128)
+            hipLaunchKernelGGL((combine_kernel<128>), dim3((unsigned)rows), dim3(128), 0, st, a.part_acc, a.part_m,
+                               a.part_l, a.n_parts, S, Hq, a.c, scale, out, lse);
+        else
+            hipLaunchKernelGGL((combine_kernel<64>), dim3((unsigned)rows), dim3(64), 0, st, a.part_acc, a.part_m,
+                               a.part_l, a.n_parts, S, Hq, a.c, scale, out, lse);
+    }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
 }

@@ -1,23 +1,38 @@
 // Round scores at the watershed layer (paper Sec. 3.1, Eq. 1 and the normalisation after it).
 //
-// Two kernels.  (1) A streaming pass over the watershed layer's keys, bandwidth bound like decode
-// attention but without values: workgroup (r, g, b*q_len+i) reduces the logits of query token i
-// against the tokens of round r (or of the visible part of the current round) to one log-sum-exp
-// per query head.  (2) A small finishing kernel turns the log-sum-exps into Eq. 1: per query token
-// the softmax normaliser over all rounds and the current round, the probability mass of every
-// history round summed over query tokens, normalisation over history rounds, mean over heads.
+// Two kernels.
+// (1) A streaming pass over the watershed layer's keys, HBM-bandwidth bound like decode attention but
+//     without values.  Every round is cut into chunks of 256 tokens; workgroup (c, g, b*q_len+i) owns
+//     chunk c of sequence b for KV head g and query token i.  Each of its four waves issues the loads
+//     of its four 16-token units up front (16 KB in flight per workgroup), then reduces the logits of
+//     the chunk to one log-sum-exp per query head.  Equal-sized work items keep long rounds from
+//     becoming the tail of the launch.
+// (2) A small finishing kernel turns the per-chunk log-sum-exps into Eq. 1: per round the
+//     log-sum-exp over its chunks, per query token the softmax normaliser over all rounds and the
+//     visible part of the current round, the probability mass of every history round summed over the
+//     query tokens, normalisation over history rounds, mean over query heads.
 #include "stream_kv.hpp"
 
 namespace ra {
+
+constexpr int kChunkUnits = 16;                          // units per chunk
+constexpr int kChunkTokens = kChunkUnits * kUnitTokens;  // 256
 
 struct ScoreArgs {
     DevView view;
     const void* q;      // [B][q_len][Hq][D]
     const void* cur_k;  // [B][cur_len][Hkv][D] or null
     int cur_len, q_len, Hq;
+    int n_chunks_max;   // row length of `part`
     float c;            // scale * log2(e)
-    float* lse;         // [B][Hq][q_len][R_max + 1] natural-log sum-exp of the scaled logits; last = current round
+    float* part;        // [B][Hq][q_len][n_chunks_max] natural-log sum-exp of the scaled logits of one chunk
 };
+
+__device__ __forceinline__ int chunks_of(int len) { return (len + kChunkTokens - 1) / kChunkTokens; }
+// Tokens of the current round visible to query token i (causal, aligned to the round's end).
+__device__ __forceinline__ int cur_visible(int cur_len, int q_len, int i) {
+    return min(max(cur_len - q_len + i + 1, 0), cur_len);
+}
 
 template <typename T, int D, int G, bool PAGED>
 __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
@@ -26,28 +41,43 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
     constexpr int WORDS = Ops::WORDS;
     constexpr int EB = Ops::ELEM_BYTES;
     __shared__ float sm[4][G], sl[4][G];
+    extern __shared__ __align__(16) char smem[];
 
     const DevView& vw = a.view;
-    const int r = blockIdx.x, g = blockIdx.y;
+    const int c = blockIdx.x, g = blockIdx.y;
     const int b = blockIdx.z / a.q_len, i = blockIdx.z - b * a.q_len;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, grp = lane >> 4, sub = lane & 15;
     const int Hkv = vw.Hkv;
-    const bool is_cur = r >= vw.R_max;
 
-    int len = 0;
-    long long off = 0;
-    if (is_cur) {
-        len = min(max(a.cur_len - a.q_len + i + 1, 0), a.cur_len);  // causal: tokens 0 .. cur_len - q_len + i
-    } else {
-        const int n_rounds = min(max(vw.n_rounds[b], 0), vw.R_max);
-        if (r < n_rounds) {
-            len = max(vw.seg_len[(size_t)b * vw.R_max + r], 0);
-            off = vw.seg_off[(size_t)b * vw.R_max + r];
+    // ---- which round does chunk c belong to? -------------------------------------------------------
+    const int n_hist = min(max(vw.n_rounds[b], 0), vw.R_max);
+    const int cur_vis = a.cur_k ? cur_visible(a.cur_len, a.q_len, i) : 0;
+    const int n_slots = n_hist + (cur_vis > 0 ? 1 : 0);
+    const int cap = vw.R_max + 1;
+    long long* t_off = reinterpret_cast<long long*>(smem);
+    int* t_len = reinterpret_cast<int*>(t_off + cap);
+    int* t_cum = t_len + cap;
+    for (int s = tid; s < n_slots; s += 256) {
+        int len = cur_vis;
+        long long off = 0;
+        if (s < n_hist) {
+            len = max(vw.seg_len[(size_t)b * vw.R_max + s], 0);
+            off = vw.seg_off[(size_t)b * vw.R_max + s];
         }
+        t_len[s] = len;
+        t_off[s] = off;
+        t_cum[s] = chunks_of(len);
     }
-    const int units = (len + kUnitTokens - 1) / kUnitTokens;
+    exclusive_scan_units(t_cum, n_slots);
+    const int total = n_slots > 0 ? t_cum[n_slots] : 0;
+    if (c >= total) return;
+    const int slot = find_slot(t_cum, n_slots, c);
+    const int len = t_len[slot];
+    const long long off = t_off[slot];
+    const bool is_cur = slot >= n_hist;
+    const int chunk_tok0 = (c - t_cum[slot]) * kChunkTokens;
 
     uint32_t qw[G][WORDS];
     {
@@ -60,85 +90,75 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
             for (int e = 0; e < WORDS; ++e) qw[h][e] = f.w[e];
         }
     }
+
+    // ---- issue every load of this wave's four units, then do the arithmetic ---------------------------
+    const char* kbase = reinterpret_cast<const char*>(vw.k);
+    Frag<WORDS> kf[4][4];
+    int ntok[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int tok0 = chunk_tok0 + (j * 4 + wave) * kUnitTokens;  // the four waves read adjacent units
+        ntok[j] = min(kUnitTokens, len - tok0);
+        if (ntok[j] > 0) {
+            const char* kp;
+            size_t stride;
+            if (is_cur) {
+                kp = reinterpret_cast<const char*>(a.cur_k) + ((((size_t)b * a.cur_len + tok0) * Hkv + g) * D) * EB;
+                stride = (size_t)Hkv * D * EB;
+            } else if (PAGED) {
+                long long si = off + tok0 / kUnitTokens;
+                si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
+                int blk = vw.block_table[(size_t)b * vw.max_blocks + si];
+                if (blk < 0) { blk = 0; ntok[j] = 0; }
+                kp = kbase + ((((size_t)blk * Hkv + g) * kUnitTokens) * D) * EB;
+                stride = (size_t)D * EB;
+            } else {
+                kp = kbase + (((size_t)off * Hkv + (size_t)g * len + tok0) * D) * EB;
+                stride = (size_t)D * EB;
+            }
+            const int last = max(ntok[j] - 1, 0);
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
+                const int t = min(t4 * 4 + grp, last);  // rows past the round's end re-read its last row
+                kf[j][t4] = load_frag<WORDS>(kp + (size_t)t * stride + (size_t)sub * EPL * EB);
+            }
+        }
+    }
+
     float m[G], l[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
         m[h] = kNegBig;
         l[h] = 0.f;
     }
-
-    const char* kbase = reinterpret_cast<const char*>(vw.k);
-    auto issue = [&](int u, Frag<WORDS>* kf, int& ntok) {
-        const int tok0 = u * kUnitTokens;
-        ntok = min(kUnitTokens, len - tok0);
-        const char* kp;
-        size_t stride;
-        if (is_cur) {
-            kp = reinterpret_cast<const char*>(a.cur_k) + ((((size_t)b * a.cur_len + tok0) * Hkv + g) * D) * EB;
-            stride = (size_t)Hkv * D * EB;
-        } else if (PAGED) {
-            long long si = off + u;
-            si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
-            int blk = vw.block_table[(size_t)b * vw.max_blocks + si];
-            if (blk < 0) { blk = 0; ntok = 0; }
-            kp = kbase + ((((size_t)blk * Hkv + g) * kUnitTokens) * D) * EB;
-            stride = (size_t)D * EB;
-        } else {
-            kp = kbase + (((size_t)off * Hkv + (size_t)g * len + tok0) * D) * EB;
-            stride = (size_t)D * EB;
-        }
-        const int last = max(ntok - 1, 0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int t = min(j * 4 + grp, last);
-            kf[j] = load_frag<WORDS>(kp + (size_t)t * stride + (size_t)sub * EPL * EB);
-        }
-    };
-    auto consume = [&](const Frag<WORDS>* kf, int ntok) {
-        float sc[4][G];
+    for (int j = 0; j < 4; ++j) {
+        if (ntok[j] > 0) {
+            float sc[4][G];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool valid = (j * 4 + grp) < ntok;
+            for (int t4 = 0; t4 < 4; ++t4) {
+                const bool valid = (t4 * 4 + grp) < ntok[j];
+#pragma unroll
+                for (int h = 0; h < G; ++h) {
+                    float d = row16_sum(Ops::dot(kf[j][t4].w, qw[h]));
+                    sc[t4][h] = valid ? d : -__builtin_inff();
+                }
+            }
 #pragma unroll
             for (int h = 0; h < G; ++h) {
-                float d = row16_sum(Ops::dot(kf[j].w, qw[h]));
-                sc[j][h] = valid ? d : -__builtin_inff();
+                const float mx = fmaxf(fmaxf(sc[0][h], sc[1][h]), fmaxf(sc[2][h], sc[3][h]));
+                const float m_new = fmaxf(m[h], mx);
+                const float mc = m_new * a.c;
+                float ps = 0.f;
+#pragma unroll
+                for (int t4 = 0; t4 < 4; ++t4) ps += fast_exp2(__builtin_fmaf(sc[t4][h], a.c, -mc));
+                l[h] = __builtin_fmaf(l[h], fast_exp2(__builtin_fmaf(m[h], a.c, -mc)), ps);
+                m[h] = m_new;
             }
-        }
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            const float mx = fmaxf(fmaxf(sc[0][h], sc[1][h]), fmaxf(sc[2][h], sc[3][h]));
-            const float m_new = fmaxf(m[h], mx);
-            const float mc = m_new * a.c;
-            float ps = 0.f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) ps += fast_exp2(__builtin_fmaf(sc[j][h], a.c, -mc));
-            l[h] = __builtin_fmaf(l[h], fast_exp2(__builtin_fmaf(m[h], a.c, -mc)), ps);
-            m[h] = m_new;
-        }
-    };
-
-    {
-        int u = wave;
-        Frag<WORDS> kf[4];
-        int ntok = 0;
-        bool have = u < units;
-        if (have) issue(u, kf, ntok);
-        while (have) {
-            const int un = u + 4;
-            const bool have_n = un < units;
-            Frag<WORDS> kn[4];
-            int ntok_n = 0;
-            if (have_n) issue(un, kn, ntok_n);
-            consume(kf, ntok);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) kf[j] = kn[j];
-            ntok = ntok_n;
-            u = un;
-            have = have_n;
         }
     }
 
+    // ---- merge the four 16-lane rows of the wave, then the four waves ------------------------------------
 #pragma unroll
     for (int h = 0; h < G; ++h) {
         float M = fmaxf(m[h], xrow_get(m[h], 16));
@@ -158,9 +178,9 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
         float den = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) den = __builtin_fmaf(sl[w][h], fast_exp2((sm[w][h] - M) * a.c), den);
-        const size_t idx = ((((size_t)b * a.Hq + (size_t)g * G + h) * a.q_len) + i) * (vw.R_max + 1) + r;
+        const size_t idx = ((((size_t)b * a.Hq + (size_t)g * G + h) * a.q_len) + i) * a.n_chunks_max + c;
         // natural log of sum_j exp(scale * logit_j) = ln2 * (M * c + log2(den))
-        a.lse[idx] = den > 0.f ? kLn2 * __builtin_fmaf(M, a.c, fast_log2(den)) : -__builtin_inff();
+        a.part[idx] = den > 0.f ? kLn2 * __builtin_fmaf(M, a.c, fast_log2(den)) : -__builtin_inff();
     }
 }
 
@@ -174,81 +194,119 @@ __device__ __forceinline__ float wave_sum(float v) {
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
 }
+// log-sum-exp of x[lo .. hi)
+__device__ __forceinline__ float lse_range(const float* x, int lo, int hi) {
+    float mx = -__builtin_inff();
+    for (int k = lo; k < hi; ++k) mx = fmaxf(mx, x[k]);
+    if (hi - lo <= 1 || mx == -__builtin_inff()) return mx;
+    float s = 0.f;
+    for (int k = lo; k < hi; ++k) s += __expf(x[k] - mx);
+    return mx + __logf(s);
+}
 
-// grid (B), block 256.  Wave w finishes heads w, w + 4, ...; lane j owns rounds j, j + 64, ...
-// P is written to p_out [B][Hq][R_max]; afterwards the whole workgroup averages over heads.
-constexpr int kRoundsPerLane = kMaxRounds / 64;
-__global__ __launch_bounds__(256) void scores_finish_kernel(const float* lse, const int32_t* n_rounds_arr, int R_max,
-                                                           int Hq, int q_len, bool has_cur, float* p_out,
-                                                           float* s_out) {
+// grid (B), block 512.  Wave w finishes heads w, w + 8, ...; lane j owns rounds j, j + 64, ...
+// (KPL rounds per lane).  P goes to p_out [B][Hq][R_max] if wanted; the head mean is accumulated per
+// wave in registers and reduced over the eight waves through LDS in a fixed order.
+struct FinishArgs {
+    const float* part;
+    const int32_t* n_rounds;
+    const int32_t* seg_len;
+    int R_max, Hq, q_len, cur_len, n_chunks_max;
+    bool has_cur;
+    float* p_out;  // may be null
+    float* s_out;
+};
+constexpr int kFinishWaves = 8;
+
+template <int KPL>
+__global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_kernel(FinishArgs a) {
+    extern __shared__ __align__(16) char smem[];
+    int* cum = reinterpret_cast<int*>(smem);                       // [R_max + 2] chunk prefix of the history rounds
+    float* hs = reinterpret_cast<float*>(smem) + (a.R_max + 2);    // [kFinishWaves][R_max] per-wave head sums
     const int b = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int R = min(max(n_rounds_arr[b], 0), R_max);
-    const int W = R_max + 1;
-    for (int h = wave; h < Hq; h += 4) {
-        float qatt[kRoundsPerLane];
+    const int R = min(max(a.n_rounds[b], 0), a.R_max);
+    for (int r = tid; r < R; r += kFinishWaves * 64) cum[r] = chunks_of(max(a.seg_len[(size_t)b * a.R_max + r], 0));
+    exclusive_scan_units(cum, R);
+    const int hist_chunks = R > 0 ? cum[R] : 0;
+    const bool overflow = hist_chunks + (a.has_cur ? chunks_of(a.cur_len) : 0) > a.n_chunks_max;
+
+    float hsum[KPL];
 #pragma unroll
-        for (int k = 0; k < kRoundsPerLane; ++k) qatt[k] = 0.f;
-        for (int i = 0; i < q_len; ++i) {
-            const float* row = lse + (((size_t)b * Hq + h) * q_len + i) * W;
-            float lv[kRoundsPerLane];
+    for (int k = 0; k < KPL; ++k) hsum[k] = 0.f;
+    for (int h = wave; h < a.Hq; h += kFinishWaves) {
+        float qatt[KPL];
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) qatt[k] = 0.f;
+        for (int i = 0; i < a.q_len && !overflow; ++i) {
+            const float* row = a.part + (((size_t)b * a.Hq + h) * a.q_len + i) * a.n_chunks_max;
+            float lv[KPL];
             float mx = -__builtin_inff();
 #pragma unroll
-            for (int k = 0; k < kRoundsPerLane; ++k) {
+            for (int k = 0; k < KPL; ++k) {
                 const int r = lane + 64 * k;
-                lv[k] = r < R ? row[r] : -__builtin_inff();
+                lv[k] = r < R ? lse_range(row, cum[r], cum[r + 1]) : -__builtin_inff();
                 mx = fmaxf(mx, lv[k]);
             }
-            const float lc = has_cur ? row[R_max] : -__builtin_inff();
+            float lc = -__builtin_inff();
+            if (a.has_cur) lc = lse_range(row, hist_chunks, hist_chunks + chunks_of(cur_visible(a.cur_len, a.q_len, i)));
             mx = fmaxf(wave_max(mx), lc);
             if (mx == -__builtin_inff()) continue;  // this query token sees no key at all
-            float e[kRoundsPerLane], sum = 0.f;
+            float e[KPL], sum = 0.f;
 #pragma unroll
-            for (int k = 0; k < kRoundsPerLane; ++k) {
+            for (int k = 0; k < KPL; ++k) {
                 e[k] = __expf(lv[k] - mx);
                 sum += e[k];
             }
             const float z = wave_sum(sum) + __expf(lc - mx);
             const float inv = 1.f / z;
 #pragma unroll
-            for (int k = 0; k < kRoundsPerLane; ++k) qatt[k] = __builtin_fmaf(e[k], inv, qatt[k]);
+            for (int k = 0; k < KPL; ++k) qatt[k] = __builtin_fmaf(e[k], inv, qatt[k]);
         }
         float tot = 0.f;
 #pragma unroll
-        for (int k = 0; k < kRoundsPerLane; ++k) tot += qatt[k];
+        for (int k = 0; k < KPL; ++k) tot += qatt[k];
         tot = wave_sum(tot);
         const float inv = tot > 0.f ? 1.f / tot : 0.f;
 #pragma unroll
-        for (int k = 0; k < kRoundsPerLane; ++k) {
+        for (int k = 0; k < KPL; ++k) {
             const int r = lane + 64 * k;
-            if (r < R_max) p_out[((size_t)b * Hq + h) * R_max + r] = r < R ? qatt[k] * inv : 0.f;
+            // a max_tokens that understates the cache would leave chunks unscored: make that loud
+            const float val = overflow ? __builtin_nanf("") : (r < R ? qatt[k] * inv : 0.f);
+            hsum[k] += val;
+            if (a.p_out && r < a.R_max) a.p_out[((size_t)b * a.Hq + h) * a.R_max + r] = val;
         }
     }
-    __threadfence_block();
+#pragma unroll
+    for (int k = 0; k < KPL; ++k) {
+        const int r = lane + 64 * k;
+        if (r < a.R_max) hs[wave * a.R_max + r] = hsum[k];
+    }
     __syncthreads();
-    const float inv_h = 1.f / (float)Hq;
-    for (int r = tid; r < R_max; r += 256) {
+    const float inv_h = 1.f / (float)a.Hq;
+    for (int r = tid; r < a.R_max; r += kFinishWaves * 64) {
         float s = 0.f;
-        for (int h = 0; h < Hq; ++h) s += p_out[((size_t)b * Hq + h) * R_max + r];
-        s_out[(size_t)b * R_max + r] = s * inv_h;
+#pragma unroll
+        for (int w = 0; w < kFinishWaves; ++w) s += hs[w * a.R_max + r];
+        a.s_out[(size_t)b * a.R_max + r] = s * inv_h;
     }
 }
 
 template <typename T, int D, int G>
-static void launch_scores(bool paged, dim3 grid, hipStream_t st, const ScoreArgs& a) {
+static void launch_scores(bool paged, dim3 grid, size_t smem, hipStream_t st, const ScoreArgs& a) {
     if (paged)
-        hipLaunchKernelGGL((scores_stream_kernel<T, D, G, true>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((scores_stream_kernel<T, D, G, true>), grid, dim3(256), smem, st, a);
     else
-        hipLaunchKernelGGL((scores_stream_kernel<T, D, G, false>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((scores_stream_kernel<T, D, G, false>), grid, dim3(256), smem, st, a);
 }
 
 template <typename T, int D>
-static int dispatch_scores(int G, bool paged, dim3 grid, hipStream_t st, const ScoreArgs& a) {
+static int dispatch_scores(int G, bool paged, dim3 grid, size_t smem, hipStream_t st, const ScoreArgs& a) {
     switch (G) {
-        case 1: launch_scores<T, D, 1>(paged, grid, st, a); return RA_OK;
-        case 2: launch_scores<T, D, 2>(paged, grid, st, a); return RA_OK;
-        case 4: launch_scores<T, D, 4>(paged, grid, st, a); return RA_OK;
-        case 8: launch_scores<T, D, 8>(paged, grid, st, a); return RA_OK;
+        case 1: launch_scores<T, D, 1>(paged, grid, smem, st, a); return RA_OK;
+        case 2: launch_scores<T, D, 2>(paged, grid, smem, st, a); return RA_OK;
+        case 4: launch_scores<T, D, 4>(paged, grid, smem, st, a); return RA_OK;
+        case 8: launch_scores<T, D, 8>(paged, grid, smem, st, a); return RA_OK;
         default: return fail(RA_ERR_UNSUPPORTED, "round_scores: Hq / Hkv = %d not in {1, 2, 4, 8}", G);
     }
 }
@@ -279,11 +337,15 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     // With a single query token the current round's share of the softmax cancels in the
     // normalisation over history rounds, so its keys need not be read at all.
     const bool use_cur = cur_k != nullptr && q_len > 1;
+    const int64_t nc64 = watershed->max_tokens / kChunkTokens + R_max + (use_cur ? (cur_len + kChunkTokens - 1) / kChunkTokens : 0);
+    RA_REQUIRE(nc64 <= (int64_t)1 << 24, RA_ERR_UNSUPPORTED, "round_scores: max_tokens too large");
+    const int n_chunks_max = (int)(nc64 < 1 ? 1 : nc64);
     const size_t rows = (size_t)B * Hq * q_len;
-    const size_t lse_bytes = align_up(rows * (R_max + 1) * sizeof(float), 256);
-    const size_t p_bytes = scores_head ? 0 : align_up((size_t)B * Hq * R_max * sizeof(float), 256);
-    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= lse_bytes + p_bytes, RA_ERR_WORKSPACE,
-               "round_scores: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, lse_bytes + p_bytes);
+    const size_t part_bytes = align_up(rows * n_chunks_max * sizeof(float), 256);
+    const size_t p_bytes = 0;
+    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= kWsReserved + part_bytes + p_bytes, RA_ERR_WORKSPACE,
+               "round_scores: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes,
+               kWsReserved + part_bytes + p_bytes);
 
     ScoreArgs a;
     a.view = to_dev(watershed);
@@ -292,21 +354,43 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     a.cur_len = use_cur ? cur_len : 0;
     a.q_len = q_len;
     a.Hq = Hq;
+    a.n_chunks_max = n_chunks_max;
     a.c = scale * kLog2e;
-    a.lse = reinterpret_cast<float*>(ctx->ws.base);
-    float* p_out = scores_head ? scores_head : reinterpret_cast<float*>(ctx->ws.base + lse_bytes);
+    a.part = reinterpret_cast<float*>(ctx->ws.base + kWsReserved);
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const dim3 grid(R_max + (use_cur ? 1 : 0), watershed->Hkv, B * q_len);
+    const dim3 grid(n_chunks_max, watershed->Hkv, B * q_len);
+    const size_t tab_bytes = (size_t)(R_max + 1) * 16 + 16;
     const bool paged = watershed->block_size != 0;
     int rc;
     if (watershed->dtype == RA_BF16)
-        rc = D == 128 ? dispatch_scores<BF16, 128>(G, paged, grid, st, a) : dispatch_scores<BF16, 64>(G, paged, grid, st, a);
+        rc = D == 128 ? dispatch_scores<BF16, 128>(G, paged, grid, tab_bytes, st, a)
+                      : dispatch_scores<BF16, 64>(G, paged, grid, tab_bytes, st, a);
     else
-        rc = D == 128 ? dispatch_scores<F32, 128>(G, paged, grid, st, a) : dispatch_scores<F32, 64>(G, paged, grid, st, a);
+        rc = D == 128 ? dispatch_scores<F32, 128>(G, paged, grid, tab_bytes, st, a)
+                      : dispatch_scores<F32, 64>(G, paged, grid, tab_bytes, st, a);
     if (rc) return rc;
-    hipLaunchKernelGGL(scores_finish_kernel, dim3(B), dim3(256), 0, st, a.lse, watershed->n_rounds, R_max, Hq, q_len,
-                       use_cur, p_out, scores);
+
+    FinishArgs f;
+    f.part = a.part;
+    f.n_rounds = watershed->n_rounds;
+    f.seg_len = watershed->seg_len;
+    f.R_max = R_max;
+    f.Hq = Hq;
+    f.q_len = q_len;
+    f.cur_len = a.cur_len;
+    f.n_chunks_max = n_chunks_max;
+    f.has_cur = use_cur;
+    f.p_out = scores_head;
+    f.s_out = scores;
+    const size_t fin_smem = (size_t)(R_max + 2) * sizeof(int) + (size_t)kFinishWaves * R_max * sizeof(float);
+    const dim3 fin_block(kFinishWaves * 64);
+    if (R_max <= 64)
+        hipLaunchKernelGGL((scores_finish_kernel<1>), dim3(B), fin_block, fin_smem, st, f);
+    else if (R_max <= 256)
+        hipLaunchKernelGGL((scores_finish_kernel<4>), dim3(B), fin_block, fin_smem, st, f);
+    else
+        hipLaunchKernelGGL((scores_finish_kernel<kMaxRounds / 64>), dim3(B), fin_block, fin_smem, st, f);
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
 }

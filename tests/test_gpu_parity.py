@@ -244,7 +244,7 @@ def test_workspace_and_argument_errors():
     eng = Engine(w)
     view = device_view(w, 1)
     q = to_device(w.q(1)[:, 0], w.dtype)
-    ra.ra_set_workspace(eng.ctx, eng.workspace[:256])
+    ra.ra_set_workspace(eng.ctx, eng.workspace[:16384])
     with pytest.raises(ra.RaError) as e:
         ra.ra_round_sparse_attn_decode(eng.ctx, q, view, scale=w.scale)
     assert e.value.code == ra.RA_ERR_WORKSPACE
