@@ -15,7 +15,8 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libround_attention.so")
+# RA_LIBRARY overrides the path (e.g. to load an instrumented build of the same sources)
+LIB_PATH = os.environ.get("RA_LIBRARY") or os.path.join(_HERE, "libround_attention.so")
 
 RA_F32, RA_BF16 = 0, 1
 RA_SEL_ADAPTIVE, RA_SEL_TOP_FRACTION, RA_SEL_THRESHOLD = 0, 1, 2

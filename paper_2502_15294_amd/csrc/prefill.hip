@@ -1,5 +1,8 @@
-// Round-sparse question-prefill attention (paper Sec. 3.2 step 4).
-#include "common.hpp"
+// Round-sparse question-prefill attention (paper Sec. 3.2 step 4): the q_len tokens of the current
+// question attend over the selected rounds' KV (fully visible) and, causally, over the question's own
+// KV.  Entry point only; the arithmetic is the matrix-core kernel shared with decode, run with the
+// query rows split over the waves of a workgroup.
+#include "attn_common.hpp"
 
 using namespace ra;
 
@@ -7,7 +10,63 @@ extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const voi
                                             const ra_kv_view* layer, const int32_t* sel_idx, const int32_t* n_sel,
                                             const void* cur_k, const void* cur_v, int cur_len, float scale, float* out,
                                             float* lse) {
-    (void)ctx; (void)stream; (void)q; (void)q_len; (void)Hq; (void)layer; (void)sel_idx; (void)n_sel;
-    (void)cur_k; (void)cur_v; (void)cur_len; (void)scale; (void)out; (void)lse;
-    return fail(RA_ERR_UNSUPPORTED, "prefill: not implemented yet");
+    RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "prefill: ctx is NULL");
+    RA_REQUIRE(q != nullptr && out != nullptr, RA_ERR_INVALID_ARG, "prefill: q or out is NULL");
+    if (int rc = check_view(layer, true, "prefill")) return rc;
+    RA_REQUIRE(q_len > 0, RA_ERR_INVALID_ARG, "prefill: q_len must be positive");
+    RA_REQUIRE(Hq > 0 && Hq % layer->Hkv == 0, RA_ERR_INVALID_ARG, "prefill: Hq %d is not a multiple of Hkv %d", Hq,
+               layer->Hkv);
+    RA_REQUIRE((sel_idx == nullptr) == (n_sel == nullptr), RA_ERR_INVALID_ARG,
+               "prefill: sel_idx and n_sel must both be given or both be NULL");
+    RA_REQUIRE(cur_len >= 0 && (cur_k != nullptr) == (cur_len > 0) && (cur_v != nullptr) == (cur_len > 0),
+               RA_ERR_INVALID_ARG, "prefill: cur_k, cur_v and cur_len > 0 must be given together");
+    RA_REQUIRE(cur_len == 0 || cur_len >= q_len, RA_ERR_INVALID_ARG,
+               "prefill: the q_len query tokens are the tail of the current round, so cur_len >= q_len");
+    RA_REQUIRE(layer->R_max > 0 || cur_len > 0, RA_ERR_INVALID_ARG,
+               "prefill: no history rounds and no current round: the key set is empty");
+    RA_REQUIRE(scale > 0.f && scale == scale, RA_ERR_INVALID_ARG, "prefill: scale must be positive");
+    RA_REQUIRE(layer->dtype == RA_BF16 && layer->d == 128, RA_ERR_UNSUPPORTED,
+               "prefill: only bf16 with head_dim 128 is implemented");
+    const int G = Hq / layer->Hkv, B = layer->B, D = 128;
+    RA_REQUIRE(G <= 16, RA_ERR_UNSUPPORTED, "prefill: Hq / Hkv = %d exceeds 16", G);
+    RA_REQUIRE((size_t)B * sizeof(int) <= kWsReserved, RA_ERR_UNSUPPORTED, "prefill: B = %d exceeds %zu", B,
+               kWsReserved / sizeof(int));
+
+    const int S = mfma_max_pieces(layer->max_tokens + cur_len, attn_min_units(), q_len == 1 ? 64 : 8);
+    const size_t rows = (size_t)B * q_len * Hq;
+    const AttnWorkspace w = attn_workspace(rows, S, D, B, layer->R_max);
+    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total, RA_ERR_WORKSPACE,
+               "prefill: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total);
+
+    AttnArgs a;
+    a.view = to_dev(layer);
+    a.q = q;
+    a.sel_idx = sel_idx;
+    a.n_sel = n_sel;
+    a.cur_k = cur_len ? cur_k : nullptr;
+    a.cur_v = cur_len ? cur_v : nullptr;
+    a.cur_len_dev = nullptr;
+    a.cur_len_host = cur_len;
+    a.cur_cap = cur_len;
+    a.max_tokens = layer->max_tokens;
+    a.q_len = q_len;
+    a.Hq = Hq;
+    a.G = G;
+    a.S = S;
+    a.min_units = attn_min_units();
+    a.c = scale * kLog2e;
+    a.scale = scale;
+    a.part_acc = reinterpret_cast<float*>(ctx->ws.base + w.acc_off);
+    a.part_m = reinterpret_cast<float*>(ctx->ws.base + w.m_off);
+    a.part_l = reinterpret_cast<float*>(ctx->ws.base + w.l_off);
+    a.n_parts = reinterpret_cast<int*>(ctx->ws.base);
+    a.plan = ctx->ws.base + w.plan_off;
+    a.out = out;
+    a.lse = lse;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    launch_plan(a, 32, st);
+    if (int rc = launch_attn_mfma(a, layer->block_size != 0, ctx->num_cu, st)) return rc;
+    if (S > 1) launch_combine(a, D, rows, st);
+    RA_HIP_CHECK(hipGetLastError());
+    return RA_OK;
 }

@@ -11,28 +11,10 @@
 //     log-sum-exp over its chunks, per query token the softmax normaliser over all rounds and the
 //     visible part of the current round, the probability mass of every history round summed over the
 //     query tokens, normalisation over history rounds, mean over query heads.
+#include "scores_common.hpp"
 #include "stream_kv.hpp"
 
 namespace ra {
-
-constexpr int kChunkUnits = 16;                          // units per chunk
-constexpr int kChunkTokens = kChunkUnits * kUnitTokens;  // 256
-
-struct ScoreArgs {
-    DevView view;
-    const void* q;      // [B][q_len][Hq][D]
-    const void* cur_k;  // [B][cur_len][Hkv][D] or null
-    int cur_len, q_len, Hq;
-    int n_chunks_max;   // row length of `part`
-    float c;            // scale * log2(e)
-    float* part;        // [B][Hq][q_len][n_chunks_max] natural-log sum-exp of the scaled logits of one chunk
-};
-
-__device__ __forceinline__ int chunks_of(int len) { return (len + kChunkTokens - 1) / kChunkTokens; }
-// Tokens of the current round visible to query token i (causal, aligned to the round's end).
-__device__ __forceinline__ int cur_visible(int cur_len, int q_len, int i) {
-    return min(max(cur_len - q_len + i + 1, 0), cur_len);
-}
 
 template <typename T, int D, int G, bool PAGED>
 __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
@@ -54,13 +36,15 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
     // ---- which round does chunk c belong to? -------------------------------------------------------
     const int n_hist = min(max(vw.n_rounds[b], 0), vw.R_max);
     const int cur_vis = a.cur_k ? cur_visible(a.cur_len, a.q_len, i) : 0;
-    const int n_slots = n_hist + (cur_vis > 0 ? 1 : 0);
+    // the current round is chunked by its full length (the same for every query token); what a query
+    // token may see of it is applied as a mask
+    const int n_slots = n_hist + (a.cur_k && a.cur_len > 0 ? 1 : 0);
     const int cap = vw.R_max + 1;
     long long* t_off = reinterpret_cast<long long*>(smem);
     int* t_len = reinterpret_cast<int*>(t_off + cap);
     int* t_cum = t_len + cap;
     for (int s = tid; s < n_slots; s += 256) {
-        int len = cur_vis;
+        int len = a.cur_len;
         long long off = 0;
         if (s < n_hist) {
             len = max(vw.seg_len[(size_t)b * vw.R_max + s], 0);
@@ -77,6 +61,7 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
     const int len = t_len[slot];
     const long long off = t_off[slot];
     const bool is_cur = slot >= n_hist;
+    const int vis = is_cur ? cur_vis : len;  // tokens of this segment the query token may see
     const int chunk_tok0 = (c - t_cum[slot]) * kChunkTokens;
 
     uint32_t qw[G][WORDS];
@@ -98,7 +83,7 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int tok0 = chunk_tok0 + (j * 4 + wave) * kUnitTokens;  // the four waves read adjacent units
-        ntok[j] = min(kUnitTokens, len - tok0);
+        ntok[j] = min(kUnitTokens, vis - tok0);
         if (ntok[j] > 0) {
             const char* kp;
             size_t stride;
@@ -249,7 +234,7 @@ __global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_kernel(Finish
                 mx = fmaxf(mx, lv[k]);
             }
             float lc = -__builtin_inff();
-            if (a.has_cur) lc = lse_range(row, hist_chunks, hist_chunks + chunks_of(cur_visible(a.cur_len, a.q_len, i)));
+            if (a.has_cur) lc = lse_range(row, hist_chunks, hist_chunks + chunks_of(a.cur_len));
             mx = fmaxf(wave_max(mx), lc);
             if (mx == -__builtin_inff()) continue;  // this query token sees no key at all
             float e[KPL], sum = 0.f;
@@ -363,9 +348,10 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     const size_t tab_bytes = (size_t)(R_max + 1) * 16 + 16;
     const bool paged = watershed->block_size != 0;
     int rc;
-    if (watershed->dtype == RA_BF16)
-        rc = D == 128 ? dispatch_scores<BF16, 128>(G, paged, grid, tab_bytes, st, a)
-                      : dispatch_scores<BF16, 64>(G, paged, grid, tab_bytes, st, a);
+    if (watershed->dtype == RA_BF16 && D == 128)
+        rc = launch_scores_mfma(a, paged, st);
+    else if (watershed->dtype == RA_BF16)
+        rc = dispatch_scores<BF16, 64>(G, paged, grid, tab_bytes, st, a);
     else
         rc = D == 128 ? dispatch_scores<F32, 128>(G, paged, grid, tab_bytes, st, a)
                       : dispatch_scores<F32, 64>(G, paged, grid, tab_bytes, st, a);

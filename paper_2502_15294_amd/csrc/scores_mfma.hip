@@ -1,0 +1,238 @@
+// Round scores (paper Sec. 3.1, Eq. 1), streaming pass over the watershed layer's keys for bf16 /
+// head_dim 128 on the matrix cores.  Same roles as in the attention kernel: the query rows of a KV
+// head (query token i, head h of the group; row = i * G + h) are handled in tiles of 16, keys in
+// tiles of 32 tokens, S^T[16 tokens x 16 rows] = K . Q^T with four mfma 16x16x32 per 16 tokens, and
+// lane%16 is the query row, so the running (max, sum-exp) of a row stays in its lane.
+//
+// Work item: (chunk c of 256 tokens, KV head g, row block, sequence b) -> one log-sum-exp per row.
+//   decode shape (rows <= 16, token split): the four waves take two key tiles each, all loads issued
+//     up front, and are merged through LDS;
+//   prefill shape (row split): the four waves take NT row tiles each and walk the chunk's eight key
+//     tiles together, so a key tile is fetched from HBM once and then served from L1/L2.
+#include "scores_common.hpp"
+#include "stream_kv.hpp"
+
+namespace ra {
+
+typedef __bf16 bf16x8s_t __attribute__((ext_vector_type(8)));
+typedef float floatx4s_t __attribute__((ext_vector_type(4)));
+constexpr int kTileS = 32;
+
+__device__ __forceinline__ floatx4s_t mfma16s(uint4 a, uint4 b, floatx4s_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8s_t, a), __builtin_bit_cast(bf16x8s_t, b),
+                                                   c, 0, 0, 0);
+}
+
+struct KTile {
+    uint4 k[2][4];  // [half][kk]: 8 channels kk*32 + 8*(lane/16) .. of token half*16 + lane%16
+};
+
+template <bool PAGED, int NT, bool ROW_SPLIT>
+__global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
+    extern __shared__ __align__(16) char smem[];
+    __shared__ float sm[4][16], sl[4][16];
+    const DevView& vw = a.view;
+    const int Hkv = vw.Hkv;
+    const int c = blockIdx.x, b = blockIdx.z;
+    const int g = blockIdx.y % Hkv, rowblock = blockIdx.y / Hkv;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, n = lane & 15, q4 = lane >> 4;
+    const int G = a.Hq / Hkv, q_len = a.q_len;
+    const int rows_total = q_len * G;
+    constexpr int RB = (ROW_SPLIT ? 4 : 1) * NT * 16;
+
+    // ---- which round does chunk c belong to? -------------------------------------------------------
+    const int n_hist = min(max(vw.n_rounds[b], 0), vw.R_max);
+    const int n_slots = n_hist + (a.cur_k && a.cur_len > 0 ? 1 : 0);
+    const int cap = vw.R_max + 1;
+    long long* t_off = reinterpret_cast<long long*>(smem);
+    int* t_len = reinterpret_cast<int*>(t_off + cap);
+    int* t_cum = t_len + cap;
+    for (int s = tid; s < n_slots; s += 256) {
+        int len = a.cur_len;
+        long long off = 0;
+        if (s < n_hist) {
+            len = max(vw.seg_len[(size_t)b * vw.R_max + s], 0);
+            off = vw.seg_off[(size_t)b * vw.R_max + s];
+        }
+        t_len[s] = len;
+        t_off[s] = off;
+        t_cum[s] = chunks_of(len);
+    }
+    exclusive_scan_units(t_cum, n_slots);
+    const int total = n_slots > 0 ? t_cum[n_slots] : 0;
+    if (c >= total) return;
+    const int slot = find_slot(t_cum, n_slots, c);
+    const int len = t_len[slot];
+    const long long off = t_off[slot];
+    const bool is_cur = slot >= n_hist;
+    const int chunk_tok0 = (c - t_cum[slot]) * kChunkTokens;
+    const int nblk = (len + 15) >> 4;
+
+    // ---- this wave's query rows -----------------------------------------------------------------------
+    int lim[NT];
+    bool row_ok[NT];
+    size_t rowid[NT];
+    uint4 qf[NT][4];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int row = rowblock * RB + (ROW_SPLIT ? wave * NT * 16 : 0) + nt * 16 + n;
+        row_ok[nt] = row < rows_total;
+        const int rr = row_ok[nt] ? row : 0;
+        const int qtok = rr / G;
+        rowid[nt] = ((size_t)b * a.Hq + (size_t)g * G + (rr - qtok * G)) * q_len + qtok;  // [B][Hq][q_len]
+        const size_t qrow = ((size_t)b * q_len + qtok) * a.Hq + (size_t)g * G + (rr - qtok * G);
+        const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.q) + qrow * 256);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) qf[nt][kk] = row_ok[nt] ? qp[kk * 4 + q4] : make_uint4(0, 0, 0, 0);
+        // tokens of this segment the row may see (causal inside the current round)
+        lim[nt] = is_cur ? cur_visible(len, q_len, qtok) : len;
+        if (!row_ok[nt]) lim[nt] = 0;
+    }
+    float m[NT], l[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        m[nt] = kNegBig;
+        l[nt] = 0.f;
+    }
+
+    const char* kbase = reinterpret_cast<const char*>(vw.k);
+    auto issue = [&](int tok0, KTile& t) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int blk = min((tok0 >> 4) + h, nblk - 1);   // halves past the end re-read the last block
+            const int rin = min(n, len - 1 - blk * 16);
+            const char* kp;
+            if (is_cur) {
+                kp = reinterpret_cast<const char*>(a.cur_k) + ((((size_t)b * a.cur_len + blk * 16 + rin) * Hkv + g) * 128) * 2;
+            } else if (PAGED) {
+                long long si = off + blk;
+                si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
+                const int pb = max(vw.block_table[(size_t)b * vw.max_blocks + si], 0);
+                kp = kbase + ((((size_t)pb * Hkv + g) * 16 + rin) * 128) * 2;
+            } else {
+                kp = kbase + ((((size_t)off * Hkv + (size_t)g * len + blk * 16 + rin) * 128)) * 2;
+            }
+            const uint4* kq = reinterpret_cast<const uint4*>(kp);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) t.k[h][kk] = kq[kk * 4 + q4];
+        }
+    };
+    auto consume = [&](const KTile& t, int tok0) {
+        const bool full = !is_cur && (len - tok0 >= kTileS);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            floatx4s_t sc[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                sc[h] = floatx4s_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) sc[h] = mfma16s(t.k[h][kk], qf[nt][kk], sc[h]);
+            }
+            if (!full) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (tok0 + h * 16 + q4 * 4 + i >= lim[nt]) sc[h][i] = -__builtin_inff();
+            }
+            const float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                                   fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+            // each lane keeps its own running max: the four lane groups of a row are merged at the end
+            const float m_new = fmaxf(m[nt], mx);
+            const float mc = m_new * a.c;
+            float ps = 0.f;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ps += fast_exp2(__builtin_fmaf(sc[h][i], a.c, -mc));
+            l[nt] = __builtin_fmaf(l[nt], fast_exp2(__builtin_fmaf(m[nt], a.c, -mc)), ps);
+            m[nt] = m_new;
+        }
+    };
+
+    if constexpr (ROW_SPLIT) {
+        for (int j = 0; j < kChunkTokens / kTileS; ++j) {
+            const int tok0 = chunk_tok0 + j * kTileS;
+            if (tok0 >= len) break;
+            KTile t;
+            issue(tok0, t);
+            consume(t, tok0);
+        }
+    } else {
+        KTile t[2];
+        int tok0[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            tok0[j] = chunk_tok0 + (j * 4 + wave) * kTileS;  // the four waves read adjacent tiles
+            if (tok0[j] < len) issue(tok0[j], t[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (tok0[j] < len) consume(t[j], tok0[j]);
+    }
+
+    // ---- merge the four lane groups of every row -----------------------------------------------------------
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        float M = fmaxf(m[nt], xrow_get(m[nt], 16));
+        M = fmaxf(M, xrow_get(M, 32));
+        float lv = l[nt] * fast_exp2((m[nt] - M) * a.c);
+        lv += xrow_get(lv, 16);
+        lv += xrow_get(lv, 32);
+        m[nt] = M;
+        l[nt] = lv;
+    }
+    if constexpr (ROW_SPLIT) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            if (row_ok[nt] && q4 == 0)
+                a.part[rowid[nt] * a.n_chunks_max + c] =
+                    l[nt] > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(l[nt])) : -__builtin_inff();
+    } else {
+        if (q4 == 0) {
+            sm[wave][n] = m[0];
+            sl[wave][n] = l[0];
+        }
+        __syncthreads();
+        if (tid < 16 && rowblock * RB + tid < rows_total) {
+            const int r = tid;
+            const float M = fmaxf(fmaxf(sm[0][r], sm[1][r]), fmaxf(sm[2][r], sm[3][r]));
+            float den = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) den = __builtin_fmaf(sl[w][r], fast_exp2((sm[w][r] - M) * a.c), den);
+            // wave 0's lanes 0..15 have q4 == 0 and n == tid, so rowid[0] is this row's index
+            a.part[rowid[0] * a.n_chunks_max + c] =
+                den > 0.f ? kLn2 * __builtin_fmaf(M, a.c, fast_log2(den)) : -__builtin_inff();
+        }
+    }
+}
+
+int launch_scores_mfma(const ScoreArgs& a, bool paged, hipStream_t st) {
+    const int G = a.Hq / a.view.Hkv;
+    if (G > 16) return fail(RA_ERR_UNSUPPORTED, "round_scores: Hq / Hkv = %d exceeds 16", G);
+    const int rows_total = a.q_len * G;
+    const size_t tab_bytes = (size_t)(a.view.R_max + 1) * 16 + 16;
+    if (rows_total <= 16) {
+        const dim3 grid(a.n_chunks_max, a.view.Hkv, a.view.B);
+        if (paged)
+            hipLaunchKernelGGL((scores_mfma_kernel<true, 1, false>), grid, dim3(256), tab_bytes, st, a);
+        else
+            hipLaunchKernelGGL((scores_mfma_kernel<false, 1, false>), grid, dim3(256), tab_bytes, st, a);
+    } else {
+        constexpr int NT = 4;
+        const int rb = 4 * NT * 16;
+        const int n_rowblocks = (rows_total + rb - 1) / rb;
+        if ((long long)a.view.Hkv * n_rowblocks > 65535)
+            return fail(RA_ERR_UNSUPPORTED, "round_scores: too many row blocks (q_len * Hq too large)");
+        const dim3 grid(a.n_chunks_max, a.view.Hkv * n_rowblocks, a.view.B);
+        if (paged)
+            hipLaunchKernelGGL((scores_mfma_kernel<true, NT, true>), grid, dim3(256), tab_bytes, st, a);
+        else
+            hipLaunchKernelGGL((scores_mfma_kernel<false, NT, true>), grid, dim3(256), tab_bytes, st, a);
+    }
+    return RA_OK;
+}
+
+}  // namespace ra

@@ -119,6 +119,30 @@ struct SlotTable {
     }
 };
 
+// The table is built once per call and sequence by a small planning kernel and kept in global memory
+// (header, then the four arrays with `cap` entries each, cum with cap + 1); the streaming kernels
+// copy it to LDS with independent loads, so their workgroups start after a single memory round trip.
+struct PlanHeader {
+    int n_slots, n_hist, U, S_eff;  // U = total work units, S_eff = pieces the sequence is cut into
+};
+__host__ __device__ inline size_t plan_stride(int cap) { return (sizeof(PlanHeader) + SlotTable::bytes(cap) + 15) & ~(size_t)15; }
+
+__device__ __forceinline__ PlanHeader load_plan(const char* plan_b, int cap, SlotTable& tab) {
+    const PlanHeader hdr = *reinterpret_cast<const PlanHeader*>(plan_b);
+    const long long* g_off_k = reinterpret_cast<const long long*>(plan_b + sizeof(PlanHeader));
+    const long long* g_off_v = g_off_k + cap;
+    const int* g_len = reinterpret_cast<const int*>(g_off_v + cap);
+    const int* g_cum = g_len + cap;
+    for (int i = threadIdx.x; i < cap; i += blockDim.x) {  // entries past n_slots are zero and unused
+        tab.off_k[i] = g_off_k[i];
+        tab.off_v[i] = g_off_v[i];
+        tab.len[i] = g_len[i];
+        tab.cum[i] = g_cum[i];
+    }
+    if (threadIdx.x == 0) tab.cum[cap] = g_cum[cap];
+    return hdr;
+}
+
 // Exclusive prefix sum, in place, of cum[0..n) by the first wavefront; cum[n] receives the total.
 // Must be called by all threads of the workgroup (it synchronises).
 __device__ inline void exclusive_scan_units(int* cum, int n) {
@@ -146,6 +170,35 @@ __device__ inline void exclusive_scan_units(int* cum, int n) {
         if (lane == 63) cum[n] = incl;
     }
     __syncthreads();
+}
+
+// ---- balanced schedule of a whole batch ------------------------------------------------------------
+// Every workgroup of a persistent attention launch derives the same schedule from the per-sequence
+// unit counts U_b the planning kernel left in the plan headers: sequence b is cut into
+//   n_b = clamp(ceil(U_b / T), 1, S)   pieces,   T = max(min_units, ceil(sum_b U_b / slots)),
+// so that pieces have about equal size whatever the selection sizes are, and the batch has about
+// `slots` pieces in total.  sU[b] = U_b, sps = exclusive prefix of n_b (sps[B] = number of pieces).
+// Must be called by all threads of the workgroup.
+constexpr int kMaxBatch = 1024;
+__device__ inline int build_schedule(const char* plan, int cap, int B, int S, int min_units, long long slots,
+                                     int* sU, int* sps) {
+    const size_t stride = plan_stride(cap);
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const int U = reinterpret_cast<const PlanHeader*>(plan + (size_t)b * stride)->U;
+        sU[b] = U;
+        sps[b] = U;
+    }
+    exclusive_scan_units(sps, B);
+    const long long total = sps[B];
+    long long T = (total + slots - 1) / (slots > 0 ? slots : 1);
+    if (T < min_units) T = min_units;
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        long long nb = (sU[b] + T - 1) / T;
+        sps[b] = (int)(nb < 1 ? 1 : (nb > S ? S : nb));
+    }
+    exclusive_scan_units(sps, B);
+    return sps[B];
 }
 
 // Largest slot with cum[slot] <= u, for 0 <= u < cum[n].

@@ -34,7 +34,8 @@ def view_from_packed(p: PackedLayer, Hkv: int, d: int, device="cuda") -> ra.KVVi
     bt = torch.from_numpy(p.block_table).to(device) if p.block_table is not None else None
     return ra.KVView(k, v, torch.from_numpy(p.seg_off).to(device), torch.from_numpy(p.seg_len).to(device),
                      torch.from_numpy(p.n_rounds).to(device), Hkv, d, p.max_tokens, block_table=bt,
-                     block_size=p.block_size)
+                     block_size=p.block_size,
+                     seg_off_v=None if p.seg_off_v is None else torch.from_numpy(p.seg_off_v).to(device))
 
 
 def device_view(w: Workload, layer: int, with_v: bool = True, block_size: Optional[int] = None, threads: int = 8,

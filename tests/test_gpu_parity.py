@@ -60,6 +60,8 @@ DECODE_CASES = {
     "bf16_g8_contig": ("cfg5", dict(B=2, R=5, block_size=0, length=("uniform", 30, 400)), [[0, 4], [1, 2, 3]]),
     "bf16_g1_mha": ("cfg2", dict(B=2, R=5, Hq=8, Hkv=8, length=("uniform", 10, 200)), [[0, 1, 4], [2]]),
     "bf16_g2": ("cfg2", dict(B=2, R=5, Hq=16, Hkv=8, length=("uniform", 10, 200)), [[3], [0, 2, 4]]),
+    "bf16_g3": ("cfg2", dict(B=2, R=5, Hq=24, Hkv=8, length=("uniform", 10, 200)), [[0, 3], [1, 2, 4]]),
+    "bf16_g16_cur": ("cfg2", dict(B=2, R=4, Hq=32, Hkv=2, cur_len=19, length=("uniform", 10, 200)), [[0, 3], [1]]),
     "bf16_d64": ("cfg2", dict(B=2, R=5, d=64, length=("uniform", 10, 200)), [[0, 3], [1, 2, 4]]),
     "f32_d128_g4": ("cfg2", dict(B=2, R=4, dtype="f32", length=("uniform", 10, 120)), [[0, 3], [1, 2]]),
     "bf16_g4_many_rounds": ("cfg4", dict(B=2, R=200, length=("lognormal", 40.0, 0.8, 9000), n_post_layers=1),
@@ -252,8 +254,9 @@ def test_workspace_and_argument_errors():
     with pytest.raises(ra.RaError) as e:                                       # Hq not a multiple of Hkv
         ra.ra_round_sparse_attn_decode(eng.ctx, q[:, :30].contiguous(), view, scale=w.scale)
     assert e.value.code == ra.RA_ERR_INVALID_ARG
-    with pytest.raises(ra.RaError) as e:                                       # group size 3 is not built
-        ra.ra_round_sparse_attn_decode(eng.ctx, q[:, :24].contiguous(), view, scale=w.scale)
+    w64 = make_workload("cfg2", B=2, R=3, d=64, Hq=24, length=("uniform", 10, 50))
+    with pytest.raises(ra.RaError) as e:                # group size 3 is not built for the head_dim 64 path
+        ra.ra_round_sparse_attn_decode(eng.ctx, to_device(w64.q(1)[:, 0], "bf16"), device_view(w64, 1), scale=0.125)
     assert e.value.code == ra.RA_ERR_UNSUPPORTED
     sel_idx, n_sel = sel_to_device([[0], [1]], 3)
     with pytest.raises(ra.RaError) as e:                                       # sel_idx without n_sel

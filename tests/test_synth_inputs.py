@@ -48,7 +48,7 @@ def test_contiguous_and_paged_packing_hold_the_same_values():
     pc = pack_layer(w, 1, block_size=0, threads=1)
     pp = pack_layer(w, 1, block_size=16, threads=2)
     Hkv, d = w.Hkv, w.d
-    kc, vp = pc.k.reshape(-1, d), pp.v.reshape(-1, Hkv, 16, d)
+    kc, vc, vp = pc.k.reshape(-1, d), pc.v, pp.v.reshape(-1, Hkv, d, 16)
     for b in range(2):
         for r in range(5):
             n = int(w.lens[b][r])
@@ -59,6 +59,9 @@ def test_contiguous_and_paged_packing_hold_the_same_values():
                     row = (pc.seg_off[b, r] * Hkv + g * n + t)
                     assert np.array_equal(kc[row], kr[t, g])
                     blk = pp.block_table[b, pp.seg_off[b, r] + t // 16]
-                    assert np.array_equal(vp[blk, g, t % 16], vr[t, g])
+                    assert np.array_equal(vp[blk, g, :, t % 16], vr[t, g])
+                    L16 = 16 * (-(-n // 16))
+                    base = (pc.seg_off_v[b, r] * Hkv + g * L16 + (t // 16) * 16) * d + t % 16
+                    assert np.array_equal(vc[base + 16 * np.arange(d)], vr[t, g])
     used = pp.block_table[pp.block_table >= 0]
     assert len(set(used.tolist())) == len(used)                    # no physical block is shared
