@@ -29,15 +29,22 @@
  *
  * KV layout (one layer), round-indexed
  * ------------------------------------
- * contiguous (block_size == 0): round r of sequence b is a block of Hkv * len * d elements stored
- *   head-major, [Hkv][len][d].  seg_off[b][r] is the block's start in units of tokens:
- *   element(g, t, c) = (seg_off * Hkv + g * len + t) * d + c, relative to `k` (keys) and, with
- *   seg_off_v (or seg_off when seg_off_v is NULL), relative to `v` (values).
- * paged (block_size == 16): storage is an array of blocks [n_blocks][Hkv][16][d]; a round owns
- *   ceil(len / 16) consecutive slots of row b of block_table starting at slot seg_off[b][r];
- *   element(g, t, c) = ((block_table[b][seg_off + t / 16] * Hkv + g) * 16 + t % 16) * d + c.
+ * Keys are stored token-major (one row of d channels per token).  Values are stored TRANSPOSED in
+ * tiles of 16 tokens, [d][16] per tile, the last tile of a round padded (the padding must hold finite
+ * numbers, e.g. zeros), so that the matrix-core kernels read several consecutive tokens of a channel
+ * with one load.
+ * contiguous (block_size == 0): the keys of round r of sequence b are a block of Hkv * len * d
+ *   elements, [Hkv][len][d]; seg_off[b][r] is its start in units of tokens:
+ *     K(g, t, c) = (seg_off * Hkv + g * len + t) * d + c                         relative to `k`.
+ *   The values are a block of Hkv * L16 * d elements, [Hkv][L16 / 16][d][16], L16 = 16 * ceil(len / 16);
+ *   seg_off_v[b][r] (seg_off if seg_off_v is NULL) is its start in units of tokens:
+ *     V(g, t, c) = (seg_off_v * Hkv + g * L16 + (t / 16) * 16) * d + c * 16 + t % 16   relative to `v`.
+ * paged (block_size == 16): storage is an array of physical blocks, [n_blocks][Hkv][16][d] for keys and
+ *   [n_blocks][Hkv][d][16] for values; a round owns ceil(len / 16) consecutive slots of row b of
+ *   block_table starting at slot seg_off[b][r].  With blk = block_table[b][seg_off + t / 16]:
+ *     K(g, t, c) = ((blk * Hkv + g) * 16 + t % 16) * d + c,   V(g, t, c) = ((blk * Hkv + g) * d + c) * 16 + t % 16.
  * The current round's own K/V ("cur", the question so far / the tokens generated so far) is passed
- * separately, token-major: [B][cur_cap][Hkv][d].
+ * separately, token-major for both keys and values: [B][cur_cap][Hkv][d].
  */
 #ifndef ROUND_ATTENTION_H
 #define ROUND_ATTENTION_H
@@ -89,8 +96,9 @@ typedef struct ra_kv_view {
     int32_t B, R_max, Hkv, d;   /* R_max <= 1024; d is 64 or 128                                 */
     int32_t dtype;              /* ra_dtype of k, v, q and cur                                   */
     int32_t reserved;
-    int64_t max_tokens;         /* host-known upper bound on one sequence's history tokens; only
-                                   used to size the launch, never to index memory                */
+    int64_t max_tokens;         /* host-known upper bound on one sequence's history tokens.  It sizes
+                                   launches and scratch, never indexes memory; if it understates the
+                                   cache, ra_round_scores returns NaN scores for that sequence      */
 } ra_kv_view;
 
 /* Shape envelope used to size the workspace. */
@@ -181,10 +189,12 @@ int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const void* q, int q
  * Round-indexed KV store for the post-watershed layers (Sec. 3.2: "u_m" lives in host memory as
  * one tensor per round and is moved to the GPU in one transfer when the round is selected).
  *
- * Host layout of one round's tensor: [n_layers][2 (K then V)][Hkv][len][d], contiguous, in
- * PINNED host memory (hipHostMalloc or torch pin_memory); the caller keeps it alive and unchanged
- * while registered.  Staging copies it as is into the device pool, so each (layer, K|V) slice is a
- * head-major round block as described above; the per-layer views index it through seg_off / seg_off_v.
+ * Host layout of one round's tensor: for each of the n_layers layers in turn, the keys [Hkv][len][d]
+ * followed by the values in transposed 16-token tiles [Hkv][ceil(len/16)][d][16] (padding zeroed);
+ * ra_kv_store_round_bytes() gives the size.  It lives in PINNED host memory (hipHostMalloc or torch
+ * pin_memory); the caller keeps it alive and unchanged while registered.  Staging copies it as is into
+ * the device pool, so each slice already is a round block of the contiguous layout described above;
+ * the per-layer views index it through seg_off / seg_off_v.
  * ------------------------------------------------------------------------------------------ */
 typedef struct ra_kv_store ra_kv_store;
 

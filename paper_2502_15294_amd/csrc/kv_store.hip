@@ -4,8 +4,9 @@
 //
 // Host side only: a registry of pinned per-round tensors, a bump-allocated device pool, the index
 // tables of the compact per-layer views, and the hipMemcpyAsync / event choreography on a side
-// stream.  The copied bytes keep the host layout [n_layers][K|V][Hkv][len][d], so every (layer, K|V)
-// slice is already a head-major round block and no repacking kernel is needed.
+// stream.  The copied bytes keep the host layout: per layer the keys [Hkv][len][d] followed by the
+// values in transposed 16-token tiles [Hkv][ceil(len/16)][d][16].  Every slice is therefore already a
+// round block in the device layout and no repacking kernel is needed.
 #include "common.hpp"
 
 #include <new>
@@ -34,6 +35,10 @@ struct ra_kv_store {
 };
 
 using namespace ra;
+
+// Tokens' worth of storage of one layer of one round: len rows of keys plus the values padded to
+// whole 16-token tiles.
+static inline size_t layer_tokens(int len) { return (size_t)len + (size_t)((len + 15) / 16) * 16; }
 
 static bool is_pinned_host(const void* p) {
     hipPointerAttribute_t attr;
@@ -109,7 +114,7 @@ int ra_kv_store_destroy(ra_kv_store* s) {
 
 size_t ra_kv_store_round_bytes(const ra_kv_store* s, int len) {
     if (!s || len < 0) return 0;
-    return (size_t)s->cfg.n_layers * 2 * (size_t)len * s->token_bytes;
+    return (size_t)s->cfg.n_layers * layer_tokens(len) * s->token_bytes;
 }
 
 int ra_kv_store_register_round(ra_kv_store* s, int seq, int round, const void* host_kv, int len) {
@@ -155,7 +160,7 @@ int ra_kv_store_stage(ra_kv_store* s, const int32_t* sel_idx_host, const int32_t
             const ra_kv_store::Round& rd = s->rounds[(size_t)b * R + r];
             RA_REQUIRE(rd.len >= 0, RA_ERR_STATE, "kv_store_stage: round %d of sequence %d was never registered", r, b);
             jobs.push_back({rd.host, tok, rd.len});
-            tok += (size_t)L * 2 * rd.len;
+            tok += (size_t)L * layer_tokens(rd.len);
             seq_tokens += rd.len;
         }
         if (seq_tokens > max_tokens) max_tokens = seq_tokens;
@@ -174,9 +179,9 @@ int ra_kv_store_stage(ra_kv_store* s, const int32_t* sel_idx_host, const int32_t
             const Job& jb = jobs[j];
             s->h_len[(size_t)b * R + i] = jb.len;
             for (int l = 0; l < L; ++l) {
-                s->h_off[((size_t)l * 2 + 0) * plane + (size_t)b * R + i] = (int64_t)(jb.dst_tok + (size_t)(2 * l) * jb.len);
+                s->h_off[((size_t)l * 2 + 0) * plane + (size_t)b * R + i] = (int64_t)(jb.dst_tok + (size_t)l * layer_tokens(jb.len));
                 s->h_off[((size_t)l * 2 + 1) * plane + (size_t)b * R + i] =
-                    (int64_t)(jb.dst_tok + (size_t)(2 * l + 1) * jb.len);
+                    (int64_t)(jb.dst_tok + (size_t)l * layer_tokens(jb.len) + jb.len);
             }
         }
     }
@@ -190,7 +195,7 @@ int ra_kv_store_stage(ra_kv_store* s, const int32_t* sel_idx_host, const int32_t
     if (order == RA_STAGE_ROUND_MAJOR) {
         for (const Job& jb : jobs) {
             if (jb.len == 0) continue;
-            const size_t bytes = (size_t)L * 2 * jb.len * s->token_bytes;
+            const size_t bytes = (size_t)L * layer_tokens(jb.len) * s->token_bytes;
             RA_HIP_CHECK(hipMemcpyAsync(s->pool + jb.dst_tok * s->token_bytes, jb.src, bytes, hipMemcpyHostToDevice, st));
             s->staged_bytes += bytes;
             ++s->n_copies;
@@ -200,8 +205,8 @@ int ra_kv_store_stage(ra_kv_store* s, const int32_t* sel_idx_host, const int32_t
         for (int l = 0; l < L; ++l) {
             for (const Job& jb : jobs) {
                 if (jb.len == 0) continue;
-                const size_t bytes = (size_t)2 * jb.len * s->token_bytes;
-                const size_t o = (size_t)(2 * l) * jb.len * s->token_bytes;
+                const size_t bytes = layer_tokens(jb.len) * s->token_bytes;
+                const size_t o = (size_t)l * layer_tokens(jb.len) * s->token_bytes;
                 RA_HIP_CHECK(hipMemcpyAsync(s->pool + jb.dst_tok * s->token_bytes + o, jb.src + o, bytes,
                                             hipMemcpyHostToDevice, st));
                 s->staged_bytes += bytes;
@@ -254,7 +259,7 @@ int ra_kv_store_stats(const ra_kv_store* s, uint64_t* staged_bytes, uint64_t* re
     if (registered_bytes) {
         uint64_t t = 0;
         for (const auto& r : s->rounds)
-            if (r.len > 0) t += (uint64_t)s->cfg.n_layers * 2 * r.len * s->token_bytes;
+            if (r.len > 0) t += (uint64_t)s->cfg.n_layers * layer_tokens(r.len) * s->token_bytes;
         *registered_bytes = t;
     }
     return RA_OK;

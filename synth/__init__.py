@@ -6,4 +6,4 @@ buffers.  None of the method's arithmetic (logits, softmax, round scores, select
 attention) lives here.
 """
 from .workloads import Workload, make_workload, CONFIGS, to_bf16_bits, bf16_bits_to_f32  # noqa: F401
-from .layout import pack_layer, PackedLayer  # noqa: F401
+from .layout import pack_layer, pack_round_host, round_host_elems, PackedLayer  # noqa: F401

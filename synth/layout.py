@@ -52,6 +52,35 @@ def _encode(x: np.ndarray, dtype: str) -> np.ndarray:
     return to_bf16_bits(x) if dtype == "bf16" else np.ascontiguousarray(x, dtype=np.float32)
 
 
+def _packed(**kw) -> "PackedLayer":
+    return PackedLayer(**kw)
+
+
+def round_host_elems(w: Workload, n: int, n_layers: int) -> int:
+    """Elements of one round's host tensor: per layer, keys [Hkv][len][d] then values
+    [Hkv][ceil(len/16)][d][16]."""
+    return n_layers * (n + 16 * (-(-n // 16))) * w.Hkv * w.d
+
+
+def pack_round_host(w: Workload, b: int, r: int, layers, out: Optional[np.ndarray] = None) -> np.ndarray:
+    """One round's post-watershed KV as the monolithic host tensor the KV store registers:
+    for each layer in `layers`, keys head-major then values in transposed, zero-padded 16-token tiles."""
+    n = int(w.lens[b][r])
+    nb = -(-n // 16)
+    Hkv, d = w.Hkv, w.d
+    el = np.uint16 if w.dtype == "bf16" else np.float32
+    per_layer = (n + nb * 16) * Hkv * d
+    buf = out if out is not None else np.zeros(len(layers) * per_layer, dtype=el)
+    assert buf.size == len(layers) * per_layer
+    for i, layer in enumerate(layers):
+        base = i * per_layer
+        buf[base:base + n * Hkv * d] = _encode(w.k_round(b, layer, r).transpose(1, 0, 2), w.dtype).reshape(-1)
+        pad = np.zeros((nb * 16, Hkv, d), dtype=el)
+        pad[:n] = _encode(w.v_round(b, layer, r), w.dtype)
+        buf[base + n * Hkv * d:base + per_layer] = pad.reshape(nb, 16, Hkv, d).transpose(2, 0, 3, 1).reshape(-1)
+    return buf
+
+
 def pack_layer(w: Workload, layer: int, with_v: bool = True, block_size: Optional[int] = None,
                threads: int = 8, seq_range: Optional[range] = None) -> PackedLayer:
     """Generate one layer's history K (and V) for every sequence and pack it for the device."""
@@ -140,6 +169,6 @@ def pack_layer(w: Workload, layer: int, with_v: bool = True, block_size: Optiona
         for j in jobs:
             fill(j)
     max_tokens = max([w.total_tokens(b) for b in range(B)] + [0])
-    return PackedLayer(k=k, v=v, seg_off=seg_off, seg_off_v=seg_off_v if bs == 0 else None, seg_len=seg_len,
+    return _packed(k=k, v=v, seg_off=seg_off, seg_off_v=seg_off_v if bs == 0 else None, seg_len=seg_len,
                        n_rounds=n_rounds,
                        block_table=block_table, block_size=bs, max_tokens=max_tokens)

@@ -263,3 +263,102 @@ def test_workspace_and_argument_errors():
         ra.ra_round_sparse_attn_decode(eng.ctx, q, view, sel_idx, None, scale=w.scale)
     assert e.value.code == ra.RA_ERR_INVALID_ARG
     eng.close()
+
+
+# --------------------------------------------------------------------------- question prefill (matrix cores)
+PREFILL_CASES = {
+    # name: (overrides on cfg3, selections)
+    "q8_cur8": (dict(B=2, R=5, q_len=8, cur_len=8, length=("uniform", 10, 150)), [[0, 3], [1, 2, 4]]),
+    "q5_cur12": (dict(B=2, R=4, q_len=5, cur_len=12, length=("uniform", 10, 150)), [[1], [0, 2, 3]]),
+    "q6_history_only": (dict(B=2, R=4, q_len=6, cur_len=0, length=("uniform", 10, 150)), [[1, 2], [3]]),
+    "q40_two_rowblocks": (dict(B=2, R=6, q_len=40, cur_len=45, length=("uniform", 20, 300)), [[0, 5], [1, 2, 3, 4]]),
+    "q16_cur_only": (dict(B=1, R=3, q_len=16, cur_len=16, length=("uniform", 10, 50)), [[]]),
+    "q33_paged_g8": (dict(B=2, R=5, q_len=33, cur_len=40, Hq=64, block_size=16, length=("uniform", 5, 200)),
+                     [[0, 1, 4], [2]]),
+    "q128_long": (dict(B=1, R=12, q_len=128, cur_len=128, length=("lognormal", 400.0, 0.8, 6000)), [[1, 4, 7, 8, 11]]),
+}
+
+
+@pytest.mark.parametrize("name", list(PREFILL_CASES))
+def test_prefill_matches_oracle(name):
+    over, sels = PREFILL_CASES[name]
+    w = make_workload("cfg3", **over)
+    _say(f"prefill case {name}: B={w.B} q_len={w.q_len} cur_len={w.cur_len} Hq={w.Hq} block={w.block_size}")
+    eng = Engine(w)
+    view = device_view(w, 1)
+    q = to_device(w.q(1), w.dtype)
+    ck = to_device(w.cur_k(1), w.dtype) if w.cur_len else None
+    cv = to_device(w.cur_v(1), w.dtype) if w.cur_len else None
+    sel_idx, n_sel = sel_to_device(sels, view.R_max)
+    out, lse = ra.ra_round_sparse_attn_prefill(eng.ctx, q, view, sel_idx, n_sel, ck, cv, scale=w.scale)
+    torch.cuda.synchronize()
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    ref_o, ref_l = _oracle_attention(w, 1, sels)
+    err = ora.row_error(out, ref_o)
+    _say(f"  row error {err:.3e}, lse error {np.abs(lse - ref_l).max():.3e}")
+    assert err < OUT_TOL and err < STREAM_TOL
+    assert np.allclose(lse, ref_l, rtol=0, atol=2e-5 * max(1.0, np.abs(ref_l).max()))
+    eng.close()
+
+
+def test_prefill_with_one_query_token_equals_decode():
+    w = make_workload("cfg2", B=2, R=5, cur_len=9, length=("uniform", 10, 200))
+    eng = Engine(w)
+    view = device_view(w, 1)
+    sels = [[0, 2], [1, 3, 4]]
+    d_out, d_lse = _gpu_decode(eng, w, 1, sels, view=view)
+    sel_idx, n_sel = sel_to_device(sels, view.R_max)
+    p_out, p_lse = ra.ra_round_sparse_attn_prefill(eng.ctx, to_device(w.q(1), w.dtype), view, sel_idx, n_sel,
+                                                   to_device(w.cur_k(1), w.dtype), to_device(w.cur_v(1), w.dtype),
+                                                   scale=w.scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(p_out.cpu().numpy()[:, 0], d_out) and np.array_equal(p_lse.cpu().numpy()[:, 0], d_lse)
+    eng.close()
+
+
+SCORE_PREFILL_CASES = {
+    "q8_cur8": dict(B=2, R=5, q_len=8, cur_len=8, length=("uniform", 10, 150)),
+    "q40_cur64": dict(B=2, R=6, q_len=40, cur_len=64, length=("uniform", 20, 600)),
+    "q100_two_rowblocks": dict(B=1, R=7, q_len=100, cur_len=100, length=("uniform", 20, 400)),
+    "q24_history_only_paged_g8": dict(B=2, R=5, q_len=24, cur_len=0, Hq=64, block_size=16, length=("uniform", 5, 300)),
+    "q300_long_question": dict(B=1, R=4, q_len=300, cur_len=300, length=("uniform", 100, 700)),
+}
+
+
+@pytest.mark.parametrize("name", list(SCORE_PREFILL_CASES))
+def test_round_scores_prefill_shape_match_oracle(name):
+    w = make_workload("cfg3", **SCORE_PREFILL_CASES[name])
+    _say(f"scores (prefill shape) case {name}: B={w.B} q_len={w.q_len} cur_len={w.cur_len} Hq={w.Hq}")
+    eng = Engine(w)
+    view = device_view(w, 0, with_v=False)
+    ck = to_device(w.cur_k(0), w.dtype) if w.cur_len else None
+    P, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), view, ck, scale=w.scale)
+    torch.cuda.synchronize()
+    P, S = P.cpu().numpy(), S.cpu().numpy()
+    for b in range(w.B):
+        rP, rS = pipeline.scores_for_sequence(w, b)
+        assert np.abs(P[b] - rP).max() < SCORE_TOL and np.abs(S[b] - rS).max() < SCORE_TOL
+        assert np.abs(P[b].sum(axis=1) - 1).max() < SCORE_TOL
+    eng.close()
+
+
+def test_prefill_pipeline_end_to_end_reduced_config3():
+    """scores (q_len 128, causal current round) -> selection -> prefill attention, config 3 at reduced batch / context."""
+    w = make_workload("cfg3", B=2, length=("lognormal", 400.0, 0.8, 8192))
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0, with_v=False), device_view(w, 1)
+    P, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, to_device(w.cur_k(0), w.dtype), scale=w.scale)
+    sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, v0.n_rounds)
+    out, _ = ra.ra_round_sparse_attn_prefill(eng.ctx, to_device(w.q(1), w.dtype), v1, sel_idx, n_sel,
+                                             to_device(w.cur_k(1), w.dtype), to_device(w.cur_v(1), w.dtype),
+                                             scale=w.scale)
+    torch.cuda.synchronize()
+    S, sel_idx, n_sel, out = S.cpu().numpy(), sel_idx.cpu().numpy(), n_sel.cpu().numpy(), out.cpu().numpy()
+    for b, r in enumerate(pipeline.run(w)):
+        assert np.abs(S[b] - r.S).max() < SCORE_TOL
+        assert r.info["margin"] > 1e-4
+        assert sel_idx[b, :n_sel[b]].tolist() == r.sel
+        err = ora.row_error(out[b], r.out[1])
+        _say(f"  seq {b}: {len(r.sel)} rounds selected, row error {err:.3e}")
+        assert err < OUT_TOL and err < STREAM_TOL
+    eng.close()
