@@ -1,0 +1,26 @@
+// Optional phase timestamps for kernel tuning.  Compiled out unless the library is built with
+// -DRA_DEBUG_TS.  Each translation unit that uses RA_TS gets its own buffer and exports a reader
+// through RA_TS_DEFINE_READER(name): int name(long long* host, int n).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#ifdef RA_DEBUG_TS
+namespace ra {
+constexpr int kDbgWorkgroups = 8192, kDbgSlots = 8;
+static __device__ long long dbg_ts[kDbgWorkgroups * kDbgSlots];
+}  // namespace ra
+#define RA_TS(k)                                                                                        \
+    do {                                                                                                \
+        const int wg_ = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;                 \
+        if (threadIdx.x == 0 && wg_ < ::ra::kDbgWorkgroups)                                             \
+            ::ra::dbg_ts[wg_ * ::ra::kDbgSlots + (k)] = wall_clock64();                                 \
+    } while (0)
+#define RA_TS_DEFINE_READER(name)                                                                       \
+    extern "C" int name(long long* host, int n) {                                                       \
+        return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(::ra::dbg_ts), (size_t)n * sizeof(long long)); \
+    }
+#else
+#define RA_TS(k)
+#define RA_TS_DEFINE_READER(name)
+#endif

@@ -11,6 +11,7 @@
 //     tiles together, so a key tile is fetched from HBM once and then served from L1/L2.
 #include "scores_common.hpp"
 #include "stream_kv.hpp"
+#include "debug_ts.hpp"
 
 namespace ra {
 
@@ -31,6 +32,7 @@ template <bool PAGED, int NT, bool ROW_SPLIT>
 __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     extern __shared__ __align__(16) char smem[];
     __shared__ float sm[4][16], sl[4][16];
+    RA_TS(0);
     const DevView& vw = a.view;
     const int Hkv = vw.Hkv;
     const int c = blockIdx.x, b = blockIdx.z;
@@ -62,6 +64,7 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     }
     exclusive_scan_units(t_cum, n_slots);
     const int total = n_slots > 0 ? t_cum[n_slots] : 0;
+    RA_TS(1);
     if (c >= total) return;
     const int slot = find_slot(t_cum, n_slots, c);
     const int len = t_len[slot];
@@ -173,7 +176,8 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
             if (tok0[j] < len) consume(t[j], tok0[j]);
     }
 
-    // ---- merge the four lane groups of every row -----------------------------------------------------------
+    RA_TS(3);
+    // ---- merge the four lane groups of every row
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         float M = fmaxf(m[nt], xrow_get(m[nt], 16));
@@ -207,7 +211,10 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
                 den > 0.f ? kLn2 * __builtin_fmaf(M, a.c, fast_log2(den)) : -__builtin_inff();
         }
     }
+    RA_TS(4);
 }
+
+RA_TS_DEFINE_READER(ra_debug_read_ts_scores)
 
 int launch_scores_mfma(const ScoreArgs& a, bool paged, hipStream_t st) {
     const int G = a.Hq / a.view.Hkv;
