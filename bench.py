@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--replicas", type=int, default=0, help="input replicas rotated through (0 = enough to defeat the Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large", action="store_true", help="skip the extra measurement on the large paged decode workload")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three device-to-device copies of 1 GiB, so that a hardware-counter run of this "
+                         "command contains a copy kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--cpu-baseline-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     ap.add_argument("--stage-order", default="round", choices=["round", "layer"], help="cfg4: order of the host-to-device copies")
     return ap.parse_args()
@@ -370,6 +373,13 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.pmc_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if args.workload == "cfg4":
         res, w = bench_long_context(args.steps, args.warmup, args.lam, args.stage_order)
