@@ -1,0 +1,121 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+`bench.py` times.  The GPU runs the whole batch; the fp64 oracle computes a sample of the sequences one by
+one (scores, selection, attention) and those rows are compared to the same bars as everywhere else:
+indices bit-exact, attention within 2e-3 (and within the arithmetic bound 5e-5), scores within 1e-5."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_15294_amd as ra
+from oracle import pipeline
+from oracle import round_attention as ora
+from synth import make_workload, pack_round_host, round_host_elems
+from synth.device import Engine, device_view, to_device
+
+pytestmark = pytest.mark.gpu
+OUT_TOL, STREAM_TOL, SCORE_TOL = 2e-3, 5e-5, 1e-5
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _check_sequence(w, b, S, sel_idx, n_sel, out, lam=1.0, layer=1):
+    r = pipeline.run_sequence(w, b, select_params=dict(lam=lam), layers=[layer])
+    R = w.n_rounds(b)
+    assert np.abs(S[b, :R] - r.S).max() < SCORE_TOL
+    assert r.info["margin"] > 1e-4, "ill-conditioned seed: a score sits on the cut"
+    assert sel_idx[b, :n_sel[b]].tolist() == r.sel
+    err = ora.row_error(out[b], r.out[layer] if out[b].ndim == 3 else r.out[layer][0])
+    _say(f"  seq {b}: {len(r.sel)} of {R} rounds kept, margin {r.info['margin']:.3f}, row error {err:.2e}")
+    assert err < OUT_TOL and err < STREAM_TOL
+
+
+def test_config5_full_size_paged_decode_sampled_sequences():
+    w = make_workload("cfg5")
+    _say(f"cfg5 full: B={w.B} Hq={w.Hq} tokens/seq~{w.total_tokens(0)} paged")
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0, with_v=False, threads=16), device_view(w, 1, threads=16)
+    _, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, scale=w.scale)
+    sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, v0.n_rounds)
+    out, _ = ra.ra_round_sparse_attn_decode(eng.ctx, to_device(w.q(1)[:, 0], w.dtype), v1, sel_idx, n_sel, scale=w.scale)
+    torch.cuda.synchronize()
+    S, sel_idx, n_sel, out = S.cpu().numpy(), sel_idx.cpu().numpy(), n_sel.cpu().numpy(), out.cpu().numpy()
+    for b in (0, 17, 40, 63):
+        _check_sequence(w, b, S, sel_idx, n_sel, out)
+    assert np.isfinite(out).all() and (n_sel >= 1).all()
+    eng.close()
+
+
+@pytest.mark.parametrize("alpha", [0.5, 1.0, 4.0])
+def test_config5_bias_sweep_reduced_batch(alpha):
+    """The kept fraction is swept by the bias strength (and by lambda); every point must match the oracle."""
+    w = make_workload("cfg5", B=3, alpha=alpha)
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0, with_v=False), device_view(w, 1)
+    for lam in (0.0, 1.0):
+        _, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, scale=w.scale)
+        sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, v0.n_rounds, ra.make_select_params(lam=lam))
+        out, _ = ra.ra_round_sparse_attn_decode(eng.ctx, to_device(w.q(1)[:, 0], w.dtype), v1, sel_idx, n_sel,
+                                                scale=w.scale)
+        torch.cuda.synchronize()
+        for b in range(w.B):
+            _check_sequence(w, b, S.cpu().numpy(), sel_idx.cpu().numpy(), n_sel.cpu().numpy(), out.cpu().numpy(), lam=lam)
+    eng.close()
+
+
+def test_config3_full_size_prefill():
+    w = make_workload("cfg3")
+    _say(f"cfg3 full: B={w.B} q_len={w.q_len} tokens/seq={w.total_tokens(0)}")
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0, with_v=False, threads=16), device_view(w, 1, threads=16)
+    _, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, to_device(w.cur_k(0), w.dtype), scale=w.scale)
+    sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, v0.n_rounds)
+    out, _ = ra.ra_round_sparse_attn_prefill(eng.ctx, to_device(w.q(1), w.dtype), v1, sel_idx, n_sel,
+                                             to_device(w.cur_k(1), w.dtype), to_device(w.cur_v(1), w.dtype),
+                                             scale=w.scale)
+    torch.cuda.synchronize()
+    S, sel_idx, n_sel, out = S.cpu().numpy(), sel_idx.cpu().numpy(), n_sel.cpu().numpy(), out.cpu().numpy()
+    for b in (0, 3):
+        _check_sequence(w, b, S, sel_idx, n_sel, out)
+    eng.close()
+
+
+def test_config4_full_size_staged_decode_sampled():
+    """128K-token contexts, 200 rounds, batch 16: scores and selection on the full batch, the selected rounds of
+    the first and the last post-watershed layer staged from pinned host memory, decode on the staged views."""
+    w = make_workload("cfg4")
+    layers = [1, w.n_post_layers]
+    _say(f"cfg4 full: B={w.B} R={w.R_max} tokens/seq={w.total_tokens(0)} staged layers {layers}")
+    eng = Engine(w)
+    v0 = device_view(w, 0, with_v=False, threads=16)
+    _, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, scale=w.scale)
+    sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, v0.n_rounds)
+    sel_h, n_h = sel_idx.cpu(), n_sel.cpu()
+    jobs = [(b, int(r)) for b in range(w.B) for r in sel_h[b, :n_h[b]].tolist()]
+    host = {j: torch.empty(round_host_elems(w, int(w.lens[j[0]][j[1]]), 2), dtype=torch.int16, pin_memory=True)
+            for j in jobs}
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=16) as ex:
+        list(ex.map(lambda j: pack_round_host(w, j[0], j[1], layers, out=host[j].numpy().view(np.uint16)), jobs))
+    store = ra.ra_kv_store_create(0, 2, w.B, w.R_max, w.Hkv, w.d, ra.RA_BF16, sum(t.numel() * 2 for t in host.values()) + 4096)
+    dummy = torch.zeros(round_host_elems(w, int(max(l.max() for l in w.lens)), 2), dtype=torch.int16, pin_memory=True)
+    for b in range(w.B):
+        for r in range(w.n_rounds(b)):
+            ra.ra_kv_store_register_round(store, b, r, host.get((b, r), dummy), int(w.lens[b][r]))
+    side = torch.cuda.Stream()
+    ra.ra_kv_store_stage(store, sel_h, n_h, ra.RA_STAGE_LAYER_MAJOR, side)
+    outs = []
+    for li, layer in enumerate(layers):
+        ra.ra_kv_store_wait_layer(store, li)
+        o, _ = ra.ra_round_sparse_attn_decode(eng.ctx, to_device(w.q(layer)[:, 0], w.dtype),
+                                              ra.ra_kv_store_layer_view(store, li), scale=w.scale)
+        outs.append(o)
+    torch.cuda.synchronize()
+    S, sel_np, n_np = S.cpu().numpy(), sel_h.numpy(), n_h.numpy()
+    for li, layer in enumerate(layers):
+        for b in ((0, 11) if li == 0 else (5,)):
+            _check_sequence(w, b, S, sel_np, n_np, outs[li].cpu().numpy(), layer=layer)
+    ra.ra_kv_store_release(store)
+    ra.ra_kv_store_destroy(store)
+    eng.close()
