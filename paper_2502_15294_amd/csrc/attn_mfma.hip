@@ -27,6 +27,7 @@
 //            L1/L2 after the first wave), each writing its own result.
 #include "attn_common.hpp"
 #include "stream_kv.hpp"
+#include "debug_ts.hpp"
 
 namespace ra {
 
@@ -54,6 +55,7 @@ template <bool PAGED, int NT, bool ROW_SPLIT>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
+    RA_TS(0);
     const DevView& vw = a.view;
     const int Hkv = vw.Hkv;
     const int tid = threadIdx.x;
@@ -80,6 +82,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
     const char* ck = reinterpret_cast<const char*>(a.cur_k);
     const char* cv = reinterpret_cast<const char*>(a.cur_v);
     const long long n_items = (long long)P * inner;
+    RA_TS(1);
 
     for (long long item = blockIdx.x; item < n_items; item += gridDim.x) {
         const int piece = (int)(item / inner);
@@ -97,6 +100,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
         const int n_slots = hdr.n_slots, n_hist = hdr.n_hist;
         __syncthreads();
 
+        RA_TS(2);
         // ---- this wave's query rows -------------------------------------------------------------------
         int qtok[NT];
         bool row_ok[NT];
@@ -290,6 +294,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             }
         }
 
+        RA_TS(3);
         // ---- the four lane groups hold partial sums of the same rows ---------------------------------------
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -363,8 +368,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                 }
             }
         }
+        RA_TS(4);
     }
+    RA_TS(5);
 }
+
+RA_TS_DEFINE_READER(ra_debug_read_ts_attn)
 
 int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) {
     const int rows_total = a.q_len * a.G;

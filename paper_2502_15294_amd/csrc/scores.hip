@@ -196,35 +196,45 @@ struct FinishArgs {
     const float* part;
     const int32_t* n_rounds;
     const int32_t* seg_len;
-    int R_max, Hq, q_len, cur_len, n_chunks_max;
+    int R_max, Hq, q_len, cur_len, n_chunks_max, chunk_tokens;
     bool has_cur;
     float* p_out;  // may be null
     float* s_out;
 };
 constexpr int kFinishWaves = 8;
+constexpr int kRowBufMax = 2048;  // chunk values a wave can stage in LDS (8 waves x 8 KB)
 
-template <int KPL>
-__global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_kernel(FinishArgs a) {
+template <int KPL, int W>
+__global__ __launch_bounds__(W * 64) void scores_finish_kernel(FinishArgs a, bool stage_rows) {
     extern __shared__ __align__(16) char smem[];
     int* cum = reinterpret_cast<int*>(smem);                       // [R_max + 2] chunk prefix of the history rounds
-    float* hs = reinterpret_cast<float*>(smem) + (a.R_max + 2);    // [kFinishWaves][R_max] per-wave head sums
+    float* hs = reinterpret_cast<float*>(smem) + (a.R_max + 2);    // [W][R_max] per-wave head sums
+    float* rowbuf = hs + W * a.R_max;                   // [W][n_chunks_max] if staged
     const int b = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int R = min(max(a.n_rounds[b], 0), a.R_max);
-    for (int r = tid; r < R; r += kFinishWaves * 64) cum[r] = chunks_of(max(a.seg_len[(size_t)b * a.R_max + r], 0));
+    for (int r = tid; r < R; r += W * 64) cum[r] = chunks_of(max(a.seg_len[(size_t)b * a.R_max + r], 0), a.chunk_tokens);
     exclusive_scan_units(cum, R);
     const int hist_chunks = R > 0 ? cum[R] : 0;
-    const bool overflow = hist_chunks + (a.has_cur ? chunks_of(a.cur_len) : 0) > a.n_chunks_max;
+    const bool overflow = hist_chunks + (a.has_cur ? chunks_of(a.cur_len, a.chunk_tokens) : 0) > a.n_chunks_max;
 
     float hsum[KPL];
 #pragma unroll
     for (int k = 0; k < KPL; ++k) hsum[k] = 0.f;
-    for (int h = wave; h < a.Hq; h += kFinishWaves) {
+    for (int h = wave; h < a.Hq; h += W) {
         float qatt[KPL];
 #pragma unroll
         for (int k = 0; k < KPL; ++k) qatt[k] = 0.f;
         for (int i = 0; i < a.q_len && !overflow; ++i) {
             const float* row = a.part + (((size_t)b * a.Hq + h) * a.q_len + i) * a.n_chunks_max;
+            if (stage_rows) {  // one coalesced pass over the row instead of dependent loads per round
+                float* mybuf = rowbuf + (size_t)(tid >> 6) * a.n_chunks_max;
+                __builtin_amdgcn_wave_barrier();
+                for (int c = lane; c < hist_chunks + (a.has_cur ? chunks_of(a.cur_len, a.chunk_tokens) : 0); c += 64)
+                    mybuf[c] = row[c];
+                __builtin_amdgcn_wave_barrier();  // same wave: LDS operations complete in program order
+                row = mybuf;
+            }
             float lv[KPL];
             float mx = -__builtin_inff();
 #pragma unroll
@@ -234,7 +244,7 @@ __global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_kernel(Finish
                 mx = fmaxf(mx, lv[k]);
             }
             float lc = -__builtin_inff();
-            if (a.has_cur) lc = lse_range(row, hist_chunks, hist_chunks + chunks_of(a.cur_len));
+            if (a.has_cur) lc = lse_range(row, hist_chunks, hist_chunks + chunks_of(a.cur_len, a.chunk_tokens));
             mx = fmaxf(wave_max(mx), lc);
             if (mx == -__builtin_inff()) continue;  // this query token sees no key at all
             float e[KPL], sum = 0.f;
@@ -269,11 +279,105 @@ __global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_kernel(Finish
     }
     __syncthreads();
     const float inv_h = 1.f / (float)a.Hq;
-    for (int r = tid; r < a.R_max; r += kFinishWaves * 64) {
+    for (int r = tid; r < a.R_max; r += W * 64) {
         float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < kFinishWaves; ++w) s += hs[w * a.R_max + r];
+        for (int w = 0; w < W; ++w) s += hs[w * a.R_max + r];
         a.s_out[(size_t)b * a.R_max + r] = s * inv_h;
+    }
+}
+
+// Finishing kernel for several query tokens: grid (B, Hq), block 512.  One workgroup per (sequence, head);
+// its eight waves take the query tokens i = wave, wave + 8, ...  A wave first copies token i's row of chunk
+// log-sum-exps into its own LDS strip with coalesced loads (when it fits), then every lane folds the
+// chunks of its rounds.  The per-wave round masses are summed over the waves in LDS in a fixed order,
+// normalised, and written to p_buf [B][Hq][R_max]; the head mean is taken by scores_head_mean_kernel.
+
+template <int KPL>
+__global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_rows_kernel(FinishArgs a, float* p_buf,
+                                                                                bool stage_rows) {
+    extern __shared__ __align__(16) char smem[];
+    int* cum = reinterpret_cast<int*>(smem);                        // [R_max + 2]
+    float* hs = reinterpret_cast<float*>(smem) + (a.R_max + 2);     // [kFinishWaves][R_max]
+    float* rowbuf = hs + kFinishWaves * a.R_max;                    // [kFinishWaves][n_chunks_max] if staged
+    const int b = blockIdx.x, h = blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int R = min(max(a.n_rounds[b], 0), a.R_max);
+    for (int r = tid; r < R; r += kFinishWaves * 64) cum[r] = chunks_of(max(a.seg_len[(size_t)b * a.R_max + r], 0), a.chunk_tokens);
+    exclusive_scan_units(cum, R);
+    const int hist_chunks = R > 0 ? cum[R] : 0;
+    const int all_chunks = hist_chunks + (a.has_cur ? chunks_of(a.cur_len, a.chunk_tokens) : 0);
+    const bool overflow = all_chunks > a.n_chunks_max;
+
+    float qatt[KPL];
+#pragma unroll
+    for (int k = 0; k < KPL; ++k) qatt[k] = 0.f;
+    float* mybuf = rowbuf + (size_t)wave * a.n_chunks_max;
+    for (int i = wave; i < a.q_len && !overflow; i += kFinishWaves) {
+        const float* row = a.part + (((size_t)b * a.Hq + h) * a.q_len + i) * a.n_chunks_max;
+        if (stage_rows) {
+            for (int c = lane; c < all_chunks; c += 64) mybuf[c] = row[c];
+            __builtin_amdgcn_wave_barrier();  // same wave: LDS operations complete in program order
+            row = mybuf;
+        }
+        float lv[KPL];
+        float mx = -__builtin_inff();
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            const int r = lane + 64 * k;
+            lv[k] = r < R ? lse_range(row, cum[r], cum[r + 1]) : -__builtin_inff();
+            mx = fmaxf(mx, lv[k]);
+        }
+        float lc = -__builtin_inff();
+        if (a.has_cur) lc = lse_range(row, hist_chunks, all_chunks);
+        __builtin_amdgcn_wave_barrier();
+        mx = fmaxf(wave_max(mx), lc);
+        if (mx == -__builtin_inff()) continue;  // this query token sees no key at all
+        float e[KPL], sum = 0.f;
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            e[k] = __expf(lv[k] - mx);
+            sum += e[k];
+        }
+        const float inv = 1.f / (wave_sum(sum) + __expf(lc - mx));
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) qatt[k] = __builtin_fmaf(e[k], inv, qatt[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < KPL; ++k) {
+        const int r = lane + 64 * k;
+        if (r < a.R_max) hs[wave * a.R_max + r] = qatt[k];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        float tot[KPL], all = 0.f;
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            const int r = lane + 64 * k;
+            tot[k] = 0.f;
+            if (r < R)
+                for (int w = 0; w < kFinishWaves; ++w) tot[k] += hs[w * a.R_max + r];
+            all += tot[k];
+        }
+        all = wave_sum(all);
+        const float inv = all > 0.f ? 1.f / all : 0.f;
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            const int r = lane + 64 * k;
+            if (r < a.R_max)
+                p_buf[((size_t)b * a.Hq + h) * a.R_max + r] = overflow ? __builtin_nanf("") : (r < R ? tot[k] * inv : 0.f);
+        }
+    }
+}
+
+// grid (B), block 256: scores[b][r] = mean over heads of p_buf[b][h][r], heads added in order.
+__global__ __launch_bounds__(256) void scores_head_mean_kernel(const float* p_buf, int R_max, int Hq, float* s_out) {
+    const int b = blockIdx.x;
+    const float inv_h = 1.f / (float)Hq;
+    for (int r = threadIdx.x; r < R_max; r += 256) {
+        float s = 0.f;
+        for (int h = 0; h < Hq; ++h) s += p_buf[((size_t)b * Hq + h) * R_max + r];
+        s_out[(size_t)b * R_max + r] = s * inv_h;
     }
 }
 
@@ -322,12 +426,15 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     // With a single query token the current round's share of the softmax cancels in the
     // normalisation over history rounds, so its keys need not be read at all.
     const bool use_cur = cur_k != nullptr && q_len > 1;
-    const int64_t nc64 = watershed->max_tokens / kChunkTokens + R_max + (use_cur ? (cur_len + kChunkTokens - 1) / kChunkTokens : 0);
+    const bool mfma = watershed->dtype == RA_BF16 && D == 128;
+    const int chunk_tokens = kChunkTokens;
+    const int64_t nc64 = watershed->max_tokens / chunk_tokens + R_max + (use_cur ? (cur_len + chunk_tokens - 1) / chunk_tokens : 0);
     RA_REQUIRE(nc64 <= (int64_t)1 << 24, RA_ERR_UNSUPPORTED, "round_scores: max_tokens too large");
     const int n_chunks_max = (int)(nc64 < 1 ? 1 : nc64);
     const size_t rows = (size_t)B * Hq * q_len;
     const size_t part_bytes = align_up(rows * n_chunks_max * sizeof(float), 256);
-    const size_t p_bytes = 0;
+    // several query tokens: per-head distributions are finished by one workgroup per head and need a buffer
+    const size_t p_bytes = (q_len > 1 && !scores_head) ? align_up((size_t)B * Hq * R_max * sizeof(float), 256) : 0;
     RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= kWsReserved + part_bytes + p_bytes, RA_ERR_WORKSPACE,
                "round_scores: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes,
                kWsReserved + part_bytes + p_bytes);
@@ -340,6 +447,7 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     a.q_len = q_len;
     a.Hq = Hq;
     a.n_chunks_max = n_chunks_max;
+    a.chunk_tokens = chunk_tokens;
     a.c = scale * kLog2e;
     a.part = reinterpret_cast<float*>(ctx->ws.base + kWsReserved);
 
@@ -348,8 +456,8 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     const size_t tab_bytes = (size_t)(R_max + 1) * 16 + 16;
     const bool paged = watershed->block_size != 0;
     int rc;
-    if (watershed->dtype == RA_BF16 && D == 128)
-        rc = launch_scores_mfma(a, paged, st);
+    if (mfma)
+        rc = launch_scores_mfma(a, paged, ctx->num_cu, st);
     else if (watershed->dtype == RA_BF16)
         rc = dispatch_scores<BF16, 64>(G, paged, grid, tab_bytes, st, a);
     else
@@ -366,17 +474,45 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     f.q_len = q_len;
     f.cur_len = a.cur_len;
     f.n_chunks_max = n_chunks_max;
+    f.chunk_tokens = chunk_tokens;
     f.has_cur = use_cur;
     f.p_out = scores_head;
     f.s_out = scores;
     const size_t fin_smem = (size_t)(R_max + 2) * sizeof(int) + (size_t)kFinishWaves * R_max * sizeof(float);
     const dim3 fin_block(kFinishWaves * 64);
-    if (R_max <= 64)
-        hipLaunchKernelGGL((scores_finish_kernel<1>), dim3(B), fin_block, fin_smem, st, f);
-    else if (R_max <= 256)
-        hipLaunchKernelGGL((scores_finish_kernel<4>), dim3(B), fin_block, fin_smem, st, f);
-    else
-        hipLaunchKernelGGL((scores_finish_kernel<kMaxRounds / 64>), dim3(B), fin_block, fin_smem, st, f);
+    if (q_len > 1) {
+        float* p_buf = scores_head ? scores_head : reinterpret_cast<float*>(ctx->ws.base + kWsReserved + part_bytes);
+        const bool stage_rows =
+            n_chunks_max <= kRowBufMax && fin_smem + (size_t)kFinishWaves * n_chunks_max * sizeof(float) <= 60 * 1024;
+        const size_t smem = fin_smem + (stage_rows ? (size_t)kFinishWaves * n_chunks_max * sizeof(float) : 0);
+        const dim3 fgrid(B, Hq);
+        if (R_max <= 64)
+            hipLaunchKernelGGL((scores_finish_rows_kernel<1>), fgrid, fin_block, smem, st, f, p_buf, stage_rows);
+        else if (R_max <= 256)
+            hipLaunchKernelGGL((scores_finish_rows_kernel<4>), fgrid, fin_block, smem, st, f, p_buf, stage_rows);
+        else
+            hipLaunchKernelGGL((scores_finish_rows_kernel<kMaxRounds / 64>), fgrid, fin_block, smem, st, f, p_buf,
+                               stage_rows);
+        hipLaunchKernelGGL(scores_head_mean_kernel, dim3(B), dim3(256), 0, st, p_buf, R_max, Hq, scores);
+    } else {
+        const bool stage_rows =
+            n_chunks_max <= kRowBufMax && fin_smem + (size_t)kFinishWaves * n_chunks_max * sizeof(float) <= 60 * 1024;
+        const size_t smem = fin_smem + (stage_rows ? (size_t)kFinishWaves * n_chunks_max * sizeof(float) : 0);
+        // sixteen waves (two heads each at Hq = 32) when the per-wave LDS strips still fit
+        const size_t smem16 = (size_t)(R_max + 2) * sizeof(int) + (size_t)16 * R_max * sizeof(float) +
+                              (stage_rows ? (size_t)16 * n_chunks_max * sizeof(float) : 0);
+        if (R_max <= 64 && Hq > 8 && smem16 <= 60 * 1024)
+            hipLaunchKernelGGL((scores_finish_kernel<1, 16>), dim3(B), dim3(1024), smem16, st, f, stage_rows);
+        else if (R_max <= 64)
+            hipLaunchKernelGGL((scores_finish_kernel<1, kFinishWaves>), dim3(B), fin_block, smem, st, f, stage_rows);
+        else if (R_max <= 256 && Hq > 8 && smem16 <= 60 * 1024)
+            hipLaunchKernelGGL((scores_finish_kernel<4, 16>), dim3(B), dim3(1024), smem16, st, f, stage_rows);
+        else if (R_max <= 256)
+            hipLaunchKernelGGL((scores_finish_kernel<4, kFinishWaves>), dim3(B), fin_block, smem, st, f, stage_rows);
+        else
+            hipLaunchKernelGGL((scores_finish_kernel<kMaxRounds / 64, kFinishWaves>), dim3(B), fin_block, smem, st, f,
+                               stage_rows);
+    }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
 }

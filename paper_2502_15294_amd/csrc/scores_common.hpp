@@ -6,7 +6,7 @@
 namespace ra {
 
 constexpr int kChunkUnits = 16;                          // units per chunk
-constexpr int kChunkTokens = kChunkUnits * kUnitTokens;  // 256
+constexpr int kChunkTokens = kChunkUnits * kUnitTokens;  // 256: chunk of the workgroup-per-chunk kernels
 
 struct ScoreArgs {
     DevView view;
@@ -14,17 +14,20 @@ struct ScoreArgs {
     const void* cur_k;  // [B][cur_len][Hkv][D] or null
     int cur_len, q_len, Hq;
     int n_chunks_max;   // row length of `part`
+    int chunk_tokens;   // tokens per chunk (a chunk never crosses a round)
     float c;            // scale * log2(e)
     float* part;        // [B][Hq][q_len][n_chunks_max] natural-log sum-exp of the scaled logits of one chunk
 };
 
-__device__ __forceinline__ int chunks_of(int len) { return (len + kChunkTokens - 1) / kChunkTokens; }
+__device__ __forceinline__ int chunks_of(int len, int chunk_tokens = kChunkTokens) {
+    return (len + chunk_tokens - 1) / chunk_tokens;
+}
 // Tokens of the current round visible to query token i (causal, aligned to the round's end).
 __device__ __forceinline__ int cur_visible(int cur_len, int q_len, int i) {
     return min(max(cur_len - q_len + i + 1, 0), cur_len);
 }
 
 // bf16, d = 128, Hq/Hkv <= 16: matrix-core streaming kernel for any q_len.
-int launch_scores_mfma(const ScoreArgs& a, bool paged, hipStream_t st);
+int launch_scores_mfma(const ScoreArgs& a, bool paged, int num_cu, hipStream_t st);
 
 }  // namespace ra

@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
 
 RA_TS_DEFINE_READER(ra_debug_read_ts_scores)
 
-int launch_scores_mfma(const ScoreArgs& a, bool paged, hipStream_t st) {
+int launch_scores_mfma(const ScoreArgs& a, bool paged, int /*num_cu*/, hipStream_t st) {
     const int G = a.Hq / a.view.Hkv;
     if (G > 16) return fail(RA_ERR_UNSUPPORTED, "round_scores: Hq / Hkv = %d exceeds 16", G);
     const int rows_total = a.q_len * G;

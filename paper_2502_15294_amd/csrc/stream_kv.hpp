@@ -180,14 +180,20 @@ __device__ inline void exclusive_scan_units(int* cum, int n) {
 // `slots` pieces in total.  sU[b] = U_b, sps = exclusive prefix of n_b (sps[B] = number of pieces).
 // Must be called by all threads of the workgroup.
 constexpr int kMaxBatch = 1024;
+// Same, from unit counts already in sU[0..B) (written by all threads before the call, no barrier needed).
+__device__ inline int schedule_from_counts(int B, int S, int min_units, long long slots, int* sU, int* sps);
+
 __device__ inline int build_schedule(const char* plan, int cap, int B, int S, int min_units, long long slots,
                                      int* sU, int* sps) {
     const size_t stride = plan_stride(cap);
-    for (int b = threadIdx.x; b < B; b += blockDim.x) {
-        const int U = reinterpret_cast<const PlanHeader*>(plan + (size_t)b * stride)->U;
-        sU[b] = U;
-        sps[b] = U;
-    }
+    for (int b = threadIdx.x; b < B; b += blockDim.x)
+        sU[b] = reinterpret_cast<const PlanHeader*>(plan + (size_t)b * stride)->U;
+    return schedule_from_counts(B, S, min_units, slots, sU, sps);
+}
+
+__device__ inline int schedule_from_counts(int B, int S, int min_units, long long slots, int* sU, int* sps) {
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += blockDim.x) sps[b] = sU[b];
     exclusive_scan_units(sps, B);
     const long long total = sps[B];
     long long T = (total + slots - 1) / (slots > 0 ? slots : 1);
