@@ -23,6 +23,8 @@ def to_device(x: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
 
 
 def raw_to_device(buf: np.ndarray, device="cuda") -> torch.Tensor:
+    if buf.size == 0:  # an empty cache still needs a valid (never dereferenced) device pointer
+        buf = np.zeros(256, dtype=buf.dtype)
     if buf.dtype == np.uint16:
         return torch.from_numpy(buf.view(np.int16)).view(torch.bfloat16).to(device)
     return torch.from_numpy(buf).to(device)

@@ -362,3 +362,67 @@ def test_prefill_pipeline_end_to_end_reduced_config3():
         _say(f"  seq {b}: {len(r.sel)} rounds selected, row error {err:.3e}")
         assert err < OUT_TOL and err < STREAM_TOL
     eng.close()
+
+
+# --------------------------------------------------------------------------- degenerate cases and determinism
+def test_first_turn_without_history_attends_over_the_current_round_only():
+    """R = 0 history rounds (first turn of a dialogue): nothing to score or select; decode and prefill
+    attend over the current round alone."""
+    w = make_workload("cfg2", B=2, R=0, cur_len=23, q_len=1)
+    assert w.R_max == 0
+    eng = Engine(w)
+    view = device_view(w, 1)
+    out, lse = _gpu_decode(eng, w, 1, [[], []], view=view, use_sel=False)
+    ref_o, ref_l = _oracle_attention(w, 1, [[], []])
+    assert ora.row_error(out, ref_o[:, 0]) < STREAM_TOL
+    wp = make_workload("cfg3", B=2, R=0, cur_len=40, q_len=40)
+    engp = Engine(wp)
+    o, _ = ra.ra_round_sparse_attn_prefill(engp.ctx, to_device(wp.q(1), wp.dtype), device_view(wp, 1), None, None,
+                                           to_device(wp.cur_k(1), wp.dtype), to_device(wp.cur_v(1), wp.dtype),
+                                           scale=wp.scale)
+    torch.cuda.synchronize()
+    ref_o, _ = _oracle_attention(wp, 1, [[], []])
+    assert ora.row_error(o.cpu().numpy(), ref_o) < STREAM_TOL
+    # no history and no current round: the key set is empty, which only the device can see -> zeros, lse = -inf
+    o, l = ra.ra_round_sparse_attn_decode(eng.ctx, to_device(w.q(1)[:, 0], w.dtype), view, scale=w.scale)
+    torch.cuda.synchronize()
+    assert (o.cpu().numpy() == 0).all() and np.isneginf(l.cpu().numpy()).all()
+    eng.close()
+    engp.close()
+
+
+def test_whole_path_is_bitwise_deterministic():
+    w = make_workload("cfg2", B=4)
+    eng = Engine(w)
+    runs = [_run_gpu_pipeline(eng, w) for _ in range(3)]
+    for other in runs[1:]:
+        for x, y in zip(runs[0], other):
+            assert np.array_equal(x, y)
+    wp = make_workload("cfg3", B=1, R=6, q_len=48, cur_len=48, length=("uniform", 50, 400))
+    engp = Engine(wp)
+    v0, v1 = device_view(wp, 0, with_v=False), device_view(wp, 1)
+    outs = []
+    for _ in range(2):
+        P, S = ra.ra_round_scores(engp.ctx, to_device(wp.q(0), wp.dtype), v0, to_device(wp.cur_k(0), wp.dtype), scale=wp.scale)
+        sel_idx, n_sel = ra.ra_select_rounds(engp.ctx, S, v0.n_rounds)
+        o, l = ra.ra_round_sparse_attn_prefill(engp.ctx, to_device(wp.q(1), wp.dtype), v1, sel_idx, n_sel,
+                                               to_device(wp.cur_k(1), wp.dtype), to_device(wp.cur_v(1), wp.dtype), scale=wp.scale)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy() for t in (P, S, sel_idx, n_sel, o, l)])
+    for x, y in zip(*outs):
+        assert np.array_equal(x, y)
+    eng.close()
+    engp.close()
+
+
+def test_understated_max_tokens_is_reported_as_nan_scores():
+    """max_tokens sizes the score pass; a value below the true history length must not go unnoticed."""
+    w = make_workload("cfg2", B=1, R=6, length=("fixed", 600))
+    eng = Engine(w)
+    view = device_view(w, 0, with_v=False)
+    k, v, seg_off, seg_len, n_rounds, bt, seg_off_v = view.tensors
+    small = ra.KVView(k, v, seg_off, seg_len, n_rounds, view.Hkv, view.d, 256)      # truth: 3600 tokens
+    _, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), small, scale=w.scale)
+    torch.cuda.synchronize()
+    assert np.isnan(S.cpu().numpy()).all()
+    eng.close()
