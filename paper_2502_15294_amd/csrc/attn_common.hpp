@@ -50,8 +50,11 @@ inline AttnWorkspace attn_workspace(size_t rows, int S, int D, int B, int R_max)
 void launch_plan(const AttnArgs& a, int unit_tokens, hipStream_t st);
 int attn_min_units();  // tuning knob (environment RA_ATTN_MIN_UNITS), default 8
 
-// bf16, d = 128, Hq/Hkv <= 16: matrix-core streaming kernel (decode: q_len == 1; prefill: q_len > 1).
+// bf16, d = 128, Hq/Hkv <= 16: matrix-core streaming kernel, the waves of a workgroup split the key tiles
+// of 16 query rows (decode, short questions).
 int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st);
+// Same operands, many query rows per KV head: the waves own different rows and share key tiles through LDS.
+int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st);
 // Most pieces one sequence can be cut into by the matrix-core kernel (row length of the piece buffers).
 inline int mfma_max_pieces(int64_t max_tokens, int min_units, int cap) {
     int64_t s = max_tokens / (32 * (int64_t)min_units);

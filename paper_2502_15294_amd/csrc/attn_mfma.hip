@@ -1,9 +1,10 @@
 // Round-sparse attention over the selected rounds, bf16 / head_dim 128, on the matrix cores
 // (paper Sec. 3.2 steps 4 and 5: question prefill and decode after the watershed layer).
 //
-// One kernel serves both shapes.  The "query rows" of a KV head g are the pairs (query token i,
-// head h of the group), row = i * G + h: G rows for decode, q_len * G for prefill; they are handled
-// in tiles of 16 rows.  Keys/values are streamed in tiles of 32 tokens that never cross a round:
+// This kernel serves decode and short questions; long questions use the kernel that shares key tiles
+// through LDS.  The "query rows" of a KV head g are the pairs (query token i, head h of the group),
+// row = i * G + h: G rows for decode, q_len * G in general; they are handled in tiles of 16 rows.
+// Keys/values are streamed in tiles of 32 tokens that never cross a round:
 //
 //   S^T tile  [16 tokens x 16 rows]  = K[16 x 128] . Q^T[128 x 16]        4 x mfma 16x16x32 per 16 tokens
 //   O^T tile  [16 channels x 16 rows] += V^T[16 x 32 tokens] . P[32 x 16]  8 x mfma 16x16x32 (x2: P = hi + lo)
@@ -21,18 +22,12 @@
 // Launch: persistent workgroups, about two per compute unit.  Every workgroup derives the same
 // balanced schedule of the batch (see build_schedule) and walks the work items
 // (piece of a sequence, KV head, row block) with stride gridDim.x.
-//   decode  (token split): the four waves of a workgroup take different key tiles of the same rows
-//            and are merged through LDS;
-//   prefill (row split): the four waves take different row tiles and read the same key tiles (from
-//            L1/L2 after the first wave), each writing its own result.
+// The four waves of a workgroup take different key tiles of the same 16 rows and are merged through LDS.
 #include "attn_common.hpp"
-#include "stream_kv.hpp"
+#include "mfma_util.hpp"
 #include "debug_ts.hpp"
 
 namespace ra {
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kTile = 32;  // tokens per key tile (two 16-token halves)
 constexpr int D128 = 128;
@@ -43,15 +38,7 @@ struct KVTile {
     uint2 v[8][2];  // [dt][half]: tokens 4*(lane/16) .. +3 of that half, channel dt*16 + lane%16
 };
 
-__device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
-                                                   0, 0, 0);
-}
-// Two floats -> packed bf16 pair by truncation (low half = a, high half = b).
-__device__ __forceinline__ uint32_t pack_trunc(float a, float b) { return (as_u32(b) & 0xffff0000u) | (as_u32(a) >> 16); }
-__device__ __forceinline__ float trunc_bf16(float a) { return as_f32(as_u32(a) & 0xffff0000u); }
-
-template <bool PAGED, int NT, bool ROW_SPLIT>
+template <bool PAGED>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
@@ -63,7 +50,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
     const int lane = tid & 63, n = lane & 15, q4 = lane >> 4;
     const int G = a.G, q_len = a.q_len;
     const int rows_total = q_len * G;
-    constexpr int RB = (ROW_SPLIT ? 4 : 1) * NT * 16;  // rows per work item
+    constexpr int NT = 1, RB = 16;  // one tile of 16 rows per work item
 
     const int cap = vw.R_max + 1;
     SlotTable tab;
@@ -108,7 +95,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
         uint4 qf[NT][4];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const int row = rowblock * RB + (ROW_SPLIT ? wave * NT * 16 : 0) + nt * 16 + n;
+            const int row = rowblock * RB + nt * 16 + n;
             row_ok[nt] = row < rows_total;
             const int rr = row_ok[nt] ? row : 0;
             qtok[nt] = rr / G;
@@ -243,54 +230,38 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
 
         // ---- stream the key tiles --------------------------------------------------------------------
         {
-            const int step = ROW_SPLIT ? 1 : 4;
-            int u = u_lo + (ROW_SPLIT ? 0 : wave);
+            const int step = 4;
+            int u = u_lo + wave;
             bool have = u < u_hi;
             int slot = 0;
-            if constexpr (ROW_SPLIT) {
-                // no software prefetch here: four waves on the same tiles hide each other's latency, and
-                // the registers go to two row tiles per wave instead
-                if (have) slot = find_slot(tab.cum, n_slots, u);
-                while (have) {
+            // Two tile buffers used alternately: the loads of one tile are in flight while the other
+            // is consumed, and no register that is still being loaded is ever copied.
+            KVTile ta, tb;
+            int len_a = 0, uin_a = 0, len_b = 0, uin_b = 0;
+            bool cur_a = false, cur_b = false;
+            if (have) {
+                slot = find_slot(tab.cum, n_slots, u);
+                uin_a = u - tab.cum[slot];
+                issue(uin_a, slot, ta, len_a, cur_a);
+            }
+            while (have) {
+                u += step;
+                const bool have_b = u < u_hi;
+                if (have_b) {
                     while (u >= tab.cum[slot + 1]) ++slot;
-                    KVTile t;
-                    int len;
-                    bool is_cur;
-                    issue(u - tab.cum[slot], slot, t, len, is_cur);
-                    consume(t, u - tab.cum[slot], len, is_cur);
-                    u += step;
-                    have = u < u_hi;
+                    uin_b = u - tab.cum[slot];
+                    issue(uin_b, slot, tb, len_b, cur_b);
                 }
-            } else {
-                // Two tile buffers used alternately: the loads of one tile are in flight while the other
-                // is consumed, and no register that is still being loaded is ever copied.
-                KVTile ta, tb;
-                int len_a = 0, uin_a = 0, len_b = 0, uin_b = 0;
-                bool cur_a = false, cur_b = false;
+                consume(ta, uin_a, len_a, cur_a);
+                if (!have_b) break;
+                u += step;
+                have = u < u_hi;
                 if (have) {
-                    slot = find_slot(tab.cum, n_slots, u);
+                    while (u >= tab.cum[slot + 1]) ++slot;
                     uin_a = u - tab.cum[slot];
                     issue(uin_a, slot, ta, len_a, cur_a);
                 }
-                while (have) {
-                    u += step;
-                    const bool have_b = u < u_hi;
-                    if (have_b) {
-                        while (u >= tab.cum[slot + 1]) ++slot;
-                        uin_b = u - tab.cum[slot];
-                        issue(uin_b, slot, tb, len_b, cur_b);
-                    }
-                    consume(ta, uin_a, len_a, cur_a);
-                    if (!have_b) break;
-                    u += step;
-                    have = u < u_hi;
-                    if (have) {
-                        while (u >= tab.cum[slot + 1]) ++slot;
-                        uin_a = u - tab.cum[slot];
-                        issue(uin_a, slot, ta, len_a, cur_a);
-                    }
-                    consume(tb, uin_b, len_b, cur_b);
-                }
+                consume(tb, uin_b, len_b, cur_b);
             }
         }
 
@@ -302,32 +273,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             l[nt] += xrow_get(l[nt], 32);
         }
 
-        if constexpr (ROW_SPLIT) {
-            // each wave owns its rows: write the piece (or the final result) straight from registers
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                if (!row_ok[nt]) continue;
-                if (S_eff > 1) {
-                    const size_t pr = rowid[nt] * a.S + s;
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt)
-                        *reinterpret_cast<floatx4_t*>(a.part_acc + pr * D128 + dt * 16 + q4 * 4) = acc[nt][dt];
-                    if (q4 == 0) {
-                        a.part_m[pr] = m[nt];
-                        a.part_l[pr] = l[nt];
-                    }
-                } else {
-                    const float inv = l[nt] > 0.f ? 1.f / l[nt] : 0.f;
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt)
-                        *reinterpret_cast<floatx4_t*>(a.out + rowid[nt] * D128 + dt * 16 + q4 * 4) = acc[nt][dt] * inv;
-                    if (a.lse && q4 == 0)
-                        a.lse[rowid[nt]] =
-                            l[nt] > 0.f ? __builtin_fmaf(m[nt], a.scale, __builtin_logf(l[nt])) : -__builtin_inff();
-                }
-            }
-        } else {
-            static_assert(ROW_SPLIT || NT == 1, "token-split mode handles one row tile per work item");
+        {
             // ---- merge the four waves (different tokens, same rows) through LDS ----------------------------
             float* sm = red;          // [4][16]
             float* sl = red + 64;     // [4][16]
@@ -381,10 +327,7 @@ int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) 
     if (a.G > 16) return fail(RA_ERR_UNSUPPORTED, "attention: Hq / Hkv = %d exceeds 16", a.G);
     if (B > kMaxBatch) return fail(RA_ERR_UNSUPPORTED, "attention: batch %d exceeds %d", B, kMaxBatch);
     const size_t tab_bytes = align_up(SlotTable::bytes(a.view.R_max + 1), 16);
-    const bool decode = a.q_len == 1;
-    constexpr int NT_PREFILL = 2;
-    const int rb = decode ? 16 : 4 * NT_PREFILL * 16;
-    const int n_rowblocks = (rows_total + rb - 1) / rb;
+    const int n_rowblocks = (rows_total + 15) / 16;
     // Persistent launch: two workgroups per compute unit, but never more than the work items the batch
     // can have at most (every sequence has at least one piece and at most S).
     const long long max_tiles = (long long)B * (a.max_tokens / kTile + a.view.R_max + 1 + a.cur_cap / kTile + 1);
@@ -393,20 +336,11 @@ int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) 
     long long grid = (long long)2 * num_cu;
     if (grid > max_pieces * Hkv * n_rowblocks) grid = max_pieces * Hkv * n_rowblocks;
     if (grid < 1) grid = 1;
-    if (decode) {
-        const size_t smem = tab_bytes + (128 + 4 * 16 * 128) * sizeof(float);
-        if (paged)
-            hipLaunchKernelGGL((attn_mfma_kernel<true, 1, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-        else
-            hipLaunchKernelGGL((attn_mfma_kernel<false, 1, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-    } else {
-        if (paged)
-            hipLaunchKernelGGL((attn_mfma_kernel<true, NT_PREFILL, true>), dim3((unsigned)grid), dim3(256), tab_bytes, st,
-                               a, n_rowblocks);
-        else
-            hipLaunchKernelGGL((attn_mfma_kernel<false, NT_PREFILL, true>), dim3((unsigned)grid), dim3(256), tab_bytes, st,
-                               a, n_rowblocks);
-    }
+    const size_t smem = tab_bytes + (128 + 4 * 16 * 128) * sizeof(float);
+    if (paged)
+        hipLaunchKernelGGL((attn_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    else
+        hipLaunchKernelGGL((attn_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
     return RA_OK;
 }
 

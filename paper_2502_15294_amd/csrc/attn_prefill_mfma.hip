@@ -1,0 +1,376 @@
+// Round-sparse question-prefill attention on the matrix cores (paper Sec. 3.2 step 4), bf16 / head_dim 128.
+//
+// Same operand roles as the decode kernel (S^T = K.Q^T, O^T += V^T.P, query row = lane%16, P = hi + lo), but
+// here a KV head has many query rows (q_len * G), so the key/value tiles are shared:
+//   * a work item is (piece of the sequence's key tiles, KV head, block of 128 query rows); its four
+//     waves own two 16-row tiles each and walk the key tiles in lockstep;
+//   * every 32-token tile (8 KB of keys, 8 KB of transposed values) is fetched from global memory ONCE per
+//     workgroup: each wave loads a quarter of the tile's MFMA operand fragments into registers while the
+//     previous tile is being consumed, writes them to one of two LDS buffers, and after one barrier all
+//     waves read the fragments they need straight in operand layout (fragment-major, 16 or 8 bytes per
+//     lane, conflict-free);
+//   * with two buffers a single barrier per tile is enough: a wave can only write buffer X again after
+//     the barrier that every wave passes once it has finished reading X.
+// The launch is persistent with the balanced schedule of the decode kernel; pieces are merged by the same
+// merge kernel.
+#include "attn_common.hpp"
+#include "mfma_util.hpp"
+#include "stream_kv.hpp"
+#include "debug_ts.hpp"
+
+namespace ra {
+
+constexpr int kTileP = 32;                      // tokens per key tile
+constexpr int kNTP = 2;                         // 16-row tiles per wave
+constexpr int kRowsPerItem = 4 * kNTP * 16;     // 128
+constexpr int kTileBytes = 16384;               // 8 K fragments of 1 KB + 16 V fragments of 512 B
+constexpr int kPiecesPerWorkgroupP = 4;
+
+// A wave's quarter of a key/value tile on its way from global memory to LDS.
+struct Share {
+    uint4 k0, k1;          // chunk lane%16 of two key rows
+    uint2 v0, v1, v2, v3;  // V^T fragments (dt, half) = (2*wave, 0), (2*wave, 1), (2*wave + 1, 0), (2*wave + 1, 1)
+};
+
+template <bool PAGED>
+__global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, int n_rowblocks) {
+    extern __shared__ __align__(16) char smem[];
+    __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
+    RA_TS(0);
+    const DevView& vw = a.view;
+    const int Hkv = vw.Hkv;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, n = lane & 15, q4 = lane >> 4;
+    const int G = a.G, q_len = a.q_len;
+    const int rows_total = q_len * G;
+
+    const int cap = vw.R_max + 1;
+    SlotTable tab;
+    tab.carve(smem, cap);
+    char* tiles = smem + ((SlotTable::bytes(cap) + 15) & ~(size_t)15);  // two tile buffers
+
+    const int inner = Hkv * n_rowblocks;
+    const long long slots = ((long long)gridDim.x * kPiecesPerWorkgroupP + inner - 1) / inner;
+    const int P = build_schedule(a.plan, cap, vw.B, a.S, a.min_units, slots, sU, sps);
+    if (blockIdx.x == 0)
+        for (int b = tid; b < vw.B; b += 256) a.n_parts[b] = sps[b + 1] - sps[b];
+
+    const char* kbase = reinterpret_cast<const char*>(vw.k);
+    const char* vbase = reinterpret_cast<const char*>(vw.v);
+    const char* ck = reinterpret_cast<const char*>(a.cur_k);
+    const char* cv = reinterpret_cast<const char*>(a.cur_v);
+    const long long n_items = (long long)P * inner;
+    RA_TS(1);
+    RA_LAP_DECL;
+
+    for (long long item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int piece = (int)(item / inner);
+        const int rest = (int)(item - (long long)piece * inner);
+        const int g = rest % Hkv, rowblock = rest / Hkv;
+        const int b = find_slot(sps, vw.B, piece);
+        const int s = piece - sps[b];
+        const int S_eff = sps[b + 1] - sps[b];
+        const int U = sU[b];
+        const int u_lo = (int)(((long long)U * s) / S_eff);
+        const int u_hi = (int)(((long long)U * (s + 1)) / S_eff);
+
+        __syncthreads();  // the previous item's readers of the table and the tile buffers are done
+        const PlanHeader hdr = load_plan(a.plan + (size_t)b * plan_stride(cap), cap, tab);
+        const int n_slots = __builtin_amdgcn_readfirstlane(hdr.n_slots), n_hist = __builtin_amdgcn_readfirstlane(hdr.n_hist);
+        __syncthreads();
+
+        // ---- this wave's query rows -------------------------------------------------------------------
+        int qtok[kNTP];
+        bool row_ok[kNTP];
+        size_t rowid[kNTP];
+        uint4 qf[kNTP][4];
+#pragma unroll
+        for (int nt = 0; nt < kNTP; ++nt) {
+            const int row = rowblock * kRowsPerItem + wave * kNTP * 16 + nt * 16 + n;
+            row_ok[nt] = row < rows_total;
+            const int rr = row_ok[nt] ? row : 0;
+            qtok[nt] = rr / G;
+            rowid[nt] = ((size_t)b * q_len + qtok[nt]) * a.Hq + (size_t)g * G + (rr - qtok[nt] * G);
+            const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.q) + rowid[nt] * 256);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) qf[nt][kk] = row_ok[nt] ? qp[kk * 4 + q4] : make_uint4(0, 0, 0, 0);
+        }
+        floatx4_t acc[kNTP][8];
+        float m[kNTP], l[kNTP];
+        const float slack = 16.f / a.c;
+#pragma unroll
+        for (int nt = 0; nt < kNTP; ++nt) {
+            m[nt] = kNegBig;
+            l[nt] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) acc[nt][dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+        }
+
+        // Uniform description of the segment the loader stands in; the table in LDS is only read when the
+        // loader enters a segment, so a tile's addresses cost a few scalar operations.
+        int seg_len = 0, seg_nblk = 0, seg_first = 0, seg_end = 0;
+        bool seg_cur = false;
+        const char *seg_k = nullptr, *seg_v = nullptr;  // contiguous history / current round: token 0 of head g
+        long long seg_tab = 0;                          // paged history: first block-table slot
+        auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
+        auto uni64 = [&](long long x) { return ((long long)uni((int)(x >> 32)) << 32) | (unsigned)uni((int)x); };
+        auto open_seg = [&](int slot) {
+            seg_len = uni(tab.len[slot]);
+            seg_first = uni(tab.cum[slot]);
+            seg_end = uni(tab.cum[slot + 1]);
+            seg_nblk = (seg_len + 15) >> 4;
+            seg_cur = slot >= n_hist;
+            if (seg_cur) {
+                seg_k = ck + ((size_t)b * a.cur_cap * Hkv + g) * 256;
+                seg_v = cv + ((size_t)b * a.cur_cap * Hkv + g) * 256;
+            } else if (PAGED) {
+                seg_tab = uni64(tab.off_k[slot]);
+            } else {
+                seg_k = kbase + ((size_t)uni64(tab.off_k[slot]) * Hkv + (size_t)g * seg_len) * 256;
+                seg_v = vbase + ((size_t)uni64(tab.off_v[slot]) * Hkv + (size_t)g * seg_nblk * 16) * 256;
+            }
+        };
+        // This wave's quarter of tile `uin` of the open segment: eight key rows of half wave/2,
+        // V fragments (dt = 2*wave + j/2, half = j%2).  Halves past the segment's end re-read its last
+        // 16-token block (their scores are masked).
+        auto load_share = [&](int uin) -> Share {
+            Share sh;
+            const size_t kstride = seg_cur ? (size_t)Hkv * 256 : 256;  // bytes from one token's keys to the next
+            const int blk0 = min(uin * 2, seg_nblk - 1), blk1 = min(uin * 2 + 1, seg_nblk - 1);
+            const char *kb0, *kb1, *vb0, *vb1;
+            if (!seg_cur && PAGED) {
+                const long long last = vw.max_blocks - 1;
+                const long long s0 = min(max(seg_tab + blk0, 0ll), last), s1 = min(max(seg_tab + blk1, 0ll), last);
+                const int p0 = max(uni(vw.block_table[(size_t)b * vw.max_blocks + s0]), 0);
+                const int p1 = max(uni(vw.block_table[(size_t)b * vw.max_blocks + s1]), 0);
+                kb0 = kbase + ((size_t)p0 * Hkv + g) * 4096;
+                kb1 = kbase + ((size_t)p1 * Hkv + g) * 4096;
+                vb0 = vbase + ((size_t)p0 * Hkv + g) * 4096;
+                vb1 = vbase + ((size_t)p1 * Hkv + g) * 4096;
+            } else {
+                kb0 = seg_k + (size_t)blk0 * 16 * kstride;
+                kb1 = seg_k + (size_t)blk1 * 16 * kstride;
+                vb0 = seg_v + (size_t)blk0 * 4096;
+                vb1 = seg_v + (size_t)blk1 * 4096;
+            }
+            {   // keys: whole 256-byte rows, 16 lanes per row (rows 8*(wave%2) + 4*j + lane/16 of half wave/2)
+                const bool upper = wave >> 1;
+                const char* kb = upper ? kb1 : kb0;
+                const int last_row = seg_len - 1 - (upper ? blk1 : blk0) * 16;
+                const int r0 = min(8 * (wave & 1) + q4, last_row), r1 = min(8 * (wave & 1) + 4 + q4, last_row);
+                sh.k0 = *reinterpret_cast<const uint4*>(kb + (size_t)r0 * kstride + n * 16);
+                sh.k1 = *reinterpret_cast<const uint4*>(kb + (size_t)r1 * kstride + n * 16);
+            }
+            if (seg_cur) {  // token-major values: gather 4 tokens of one channel with 2-byte loads
+                auto gather = [&](int dt, int blk) {
+                    uint32_t e[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int tok = min(blk * 16 + q4 * 4 + t, seg_len - 1);
+                        e[t] = *reinterpret_cast<const unsigned short*>(seg_v + (size_t)tok * kstride + (dt * 16 + n) * 2);
+                    }
+                    return make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
+                };
+                sh.v0 = gather(2 * wave, blk0);
+                sh.v1 = gather(2 * wave, blk1);
+                sh.v2 = gather(2 * wave + 1, blk0);
+                sh.v3 = gather(2 * wave + 1, blk1);
+            } else {
+                const int o = ((2 * wave * 16 + n) * 4 + q4) * 8;
+                sh.v0 = *reinterpret_cast<const uint2*>(vb0 + o);
+                sh.v1 = *reinterpret_cast<const uint2*>(vb1 + o);
+                sh.v2 = *reinterpret_cast<const uint2*>(vb0 + o + 512);
+                sh.v3 = *reinterpret_cast<const uint2*>(vb1 + o + 512);
+            }
+            return sh;
+        };
+        // LDS tile: K operand fragment (half, kk) holds its 64 lanes' 16-byte pieces at
+        //   ((half*4 + kk)*64 + q4*16 + ((n + 4*kk + q4) % 16)) * 16,
+        // a rotation inside each 16-piece group that makes both the row-wise writes below and the operand reads
+        // (16 lanes = 16 rows of one channel group) touch every bank once.  V fragments are stored as loaded.
+        auto store_share = [&](char* buf, const Share& sh) {
+            uint4* kd = reinterpret_cast<uint4*>(buf) + ((wave >> 1) * 4 + (n >> 2)) * 64 + (n & 3) * 16;
+            const int row = 8 * (wave & 1) + q4;  // lane holds chunk n (kk = n/4, piece n%4) of rows `row`, `row + 4`
+            kd[(row + n) & 15] = sh.k0;
+            kd[(row + 4 + n) & 15] = sh.k1;
+            uint2* vd = reinterpret_cast<uint2*>(buf + 8192) + 4 * wave * 64 + lane;
+            vd[0] = sh.v0;
+            vd[64] = sh.v1;
+            vd[128] = sh.v2;
+            vd[192] = sh.v3;
+        };
+        auto consume = [&](const char* buf, int uin, int len, bool is_cur) {
+            const int tok0 = uin * kTileP;
+            const bool full = !is_cur && (len - tok0 >= kTileP);
+            const uint4* kb = reinterpret_cast<const uint4*>(buf);
+            const uint2* vb = reinterpret_cast<const uint2*>(buf + 8192);
+            uint4 kf[2][4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) kf[h][kk] = kb[(h * 4 + kk) * 64 + q4 * 16 + ((n + 4 * kk + q4) & 15)];
+            floatx4_t sc[kNTP][2];
+#pragma unroll
+            for (int nt = 0; nt < kNTP; ++nt)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    sc[nt][h] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) sc[nt][h] = mfma16(kf[h][kk], qf[nt][kk], sc[nt][h]);
+                }
+            if (!full) {
+#pragma unroll
+                for (int nt = 0; nt < kNTP; ++nt) {
+                    // tokens this row may see: the segment's length, or inside the current round the causal limit
+                    int lim = len;
+                    if (is_cur) lim = min(len, max(len - q_len + qtok[nt] + 1, 0));
+                    if (!row_ok[nt]) lim = 0;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (tok0 + h * 16 + q4 * 4 + i >= lim) sc[nt][h][i] = -__builtin_inff();
+                }
+            }
+            // The reference logit m of a row is only raised when some logit exceeds it by more than `slack`
+            // (2^16 after scaling), which a lane can tell from its own eight logits: the common tile has no
+            // cross-lane traffic and no rescale, and P stays far inside the fp32 / bf16 range.
+            float mx[kNTP];
+            bool raise = false;
+#pragma unroll
+            for (int nt = 0; nt < kNTP; ++nt) {
+                mx[nt] = fmaxf(fmaxf(fmaxf(sc[nt][0][0], sc[nt][0][1]), fmaxf(sc[nt][0][2], sc[nt][0][3])),
+                               fmaxf(fmaxf(sc[nt][1][0], sc[nt][1][1]), fmaxf(sc[nt][1][2], sc[nt][1][3])));
+                raise |= mx[nt] > m[nt] + slack;
+            }
+            RA_LAP(2);
+            if (__any(raise)) {
+#pragma unroll
+                for (int nt = 0; nt < kNTP; ++nt) {
+                    float r = fmaxf(mx[nt], xrow_get(mx[nt], 16));
+                    r = fmaxf(r, xrow_get(r, 32));
+                    const float m_new = fmaxf(m[nt], r);
+                    const float alpha = fast_exp2((m[nt] - m_new) * a.c);
+                    l[nt] *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < 8; ++dt) acc[nt][dt] *= alpha;
+                    m[nt] = m_new;
+                }
+            }
+            uint4 phi[kNTP], plo[kNTP];
+#pragma unroll
+            for (int nt = 0; nt < kNTP; ++nt) {
+                const float mc = m[nt] * a.c;
+                float p[8];
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) p[h * 4 + i] = fast_exp2(__builtin_fmaf(sc[nt][h][i], a.c, -mc));
+                l[nt] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+                phi[nt].x = pack_hi16(p[0], p[1]);
+                phi[nt].y = pack_hi16(p[2], p[3]);
+                phi[nt].z = pack_hi16(p[4], p[5]);
+                phi[nt].w = pack_hi16(p[6], p[7]);
+                plo[nt].x = pack_hi16(p[0] - trunc_bf16(p[0]), p[1] - trunc_bf16(p[1]));
+                plo[nt].y = pack_hi16(p[2] - trunc_bf16(p[2]), p[3] - trunc_bf16(p[3]));
+                plo[nt].z = pack_hi16(p[4] - trunc_bf16(p[4]), p[5] - trunc_bf16(p[5]));
+                plo[nt].w = pack_hi16(p[6] - trunc_bf16(p[6]), p[7] - trunc_bf16(p[7]));
+            }
+            RA_LAP(3);
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                const uint2 v0 = vb[(dt * 2 + 0) * 64 + lane], v1 = vb[(dt * 2 + 1) * 64 + lane];
+                const uint4 vf = make_uint4(v0.x, v0.y, v1.x, v1.y);
+#pragma unroll
+                for (int nt = 0; nt < kNTP; ++nt) {
+                    acc[nt][dt] = mfma16(vf, phi[nt], acc[nt][dt]);
+                    acc[nt][dt] = mfma16(vf, plo[nt], acc[nt][dt]);
+                }
+            }
+        };
+
+        // ---- walk the key tiles: the whole workgroup in lockstep -----------------------------------------
+        RA_TS(2);
+        if (u_lo < u_hi) {
+            int slot = find_slot(tab.cum, n_slots, u_lo);
+            open_seg(slot);
+            Share sh = load_share(u_lo - seg_first);
+            int bufsel = 0;
+            for (int u = u_lo; u < u_hi; ++u) {
+                char* buf = tiles + bufsel * kTileBytes;
+                RA_LAP_START;
+                store_share(buf, sh);
+                const int len = seg_len, uin = u - seg_first;  // of the tile just stored
+                const bool is_cur = seg_cur;
+                __syncthreads();
+                RA_LAP(0);
+                if (u + 1 < u_hi) {
+                    if (u + 1 >= seg_end) {
+                        do ++slot; while (u + 1 >= uni(tab.cum[slot + 1]));
+                        open_seg(slot);
+                    }
+                    sh = load_share(u + 1 - seg_first);
+                }
+                RA_LAP(1);
+                consume(buf, uin, len, is_cur);
+                RA_LAP(5);
+                bufsel ^= 1;
+            }
+        }
+
+        RA_TS(3);
+        // ---- the four lane groups hold partial sums of the same rows; each wave owns its rows ------------------
+#pragma unroll
+        for (int nt = 0; nt < kNTP; ++nt) {
+            l[nt] += xrow_get(l[nt], 16);
+            l[nt] += xrow_get(l[nt], 32);
+            if (!row_ok[nt]) continue;
+            if (S_eff > 1) {
+                const size_t pr = rowid[nt] * a.S + s;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt)
+                    *reinterpret_cast<floatx4_t*>(a.part_acc + pr * 128 + dt * 16 + q4 * 4) = acc[nt][dt];
+                if (q4 == 0) {
+                    a.part_m[pr] = m[nt];
+                    a.part_l[pr] = l[nt];
+                }
+            } else {
+                const float inv = l[nt] > 0.f ? 1.f / l[nt] : 0.f;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt)
+                    *reinterpret_cast<floatx4_t*>(a.out + rowid[nt] * 128 + dt * 16 + q4 * 4) = acc[nt][dt] * inv;
+                if (a.lse && q4 == 0)
+                    a.lse[rowid[nt]] =
+                        l[nt] > 0.f ? __builtin_fmaf(m[nt], a.scale, __builtin_logf(l[nt])) : -__builtin_inff();
+            }
+        }
+        RA_TS(4);
+    }
+    RA_TS(5);
+    RA_LAP_FLUSH(8);
+}
+
+RA_TS_DEFINE_READER(ra_debug_read_ts_prefill)
+
+int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) {
+    const int rows_total = a.q_len * a.G;
+    const int B = a.view.B, Hkv = a.view.Hkv;
+    if (a.G > 16) return fail(RA_ERR_UNSUPPORTED, "prefill: Hq / Hkv = %d exceeds 16", a.G);
+    if (B > kMaxBatch) return fail(RA_ERR_UNSUPPORTED, "prefill: batch %d exceeds %d", B, kMaxBatch);
+    const int n_rowblocks = (rows_total + kRowsPerItem - 1) / kRowsPerItem;
+    const size_t smem = align_up(SlotTable::bytes(a.view.R_max + 1), 16) + 2 * kTileBytes;
+    const long long max_tiles = (long long)B * (a.max_tokens / kTileP + a.view.R_max + 1 + a.cur_cap / kTileP + 1);
+    long long max_pieces = (long long)B + max_tiles / a.min_units;
+    if (max_pieces > (long long)B * a.S) max_pieces = (long long)B * a.S;
+    long long grid = (long long)2 * num_cu;
+    if (grid > max_pieces * Hkv * n_rowblocks) grid = max_pieces * Hkv * n_rowblocks;
+    if (grid < 1) grid = 1;
+    if (paged)
+        hipLaunchKernelGGL((attn_prefill_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    else
+        hipLaunchKernelGGL((attn_prefill_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    return RA_OK;
+}
+
+}  // namespace ra

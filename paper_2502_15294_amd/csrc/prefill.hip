@@ -1,7 +1,6 @@
 // Round-sparse question-prefill attention (paper Sec. 3.2 step 4): the q_len tokens of the current
 // question attend over the selected rounds' KV (fully visible) and, causally, over the question's own
-// KV.  Entry point only; the arithmetic is the matrix-core kernel shared with decode, run with the
-// query rows split over the waves of a workgroup.
+// KV.  Entry point only; the arithmetic is in the matrix-core kernels.
 #include "attn_common.hpp"
 
 using namespace ra;
@@ -32,7 +31,7 @@ extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const voi
     RA_REQUIRE((size_t)B * sizeof(int) <= kWsReserved, RA_ERR_UNSUPPORTED, "prefill: B = %d exceeds %zu", B,
                kWsReserved / sizeof(int));
 
-    const int S = mfma_max_pieces(layer->max_tokens + cur_len, attn_min_units(), q_len == 1 ? 64 : 8);
+    const int S = mfma_max_pieces(layer->max_tokens + cur_len, attn_min_units(), q_len * G <= 32 ? 64 : 8);
     const size_t rows = (size_t)B * q_len * Hq;
     const AttnWorkspace w = attn_workspace(rows, S, D, B, layer->R_max);
     RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total, RA_ERR_WORKSPACE,
@@ -65,7 +64,12 @@ extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const voi
     a.lse = lse;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     launch_plan(a, 32, st);
-    if (int rc = launch_attn_mfma(a, layer->block_size != 0, ctx->num_cu, st)) return rc;
+    // Few query rows per KV head: the decode kernel's token split keeps all four waves busy; otherwise
+    // the kernel whose waves own different rows and share each key tile through LDS.
+    const bool few_rows = q_len * G <= 32;
+    if (int rc = few_rows ? launch_attn_mfma(a, layer->block_size != 0, ctx->num_cu, st)
+                          : launch_attn_prefill_mfma(a, layer->block_size != 0, ctx->num_cu, st))
+        return rc;
     if (S > 1) launch_combine(a, D, rows, st);
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
