@@ -193,8 +193,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                 }
                 float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                                  fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
-                mx = fmaxf(mx, xrow_get(mx, 16));
-                mx = fmaxf(mx, xrow_get(mx, 32));
+                mx = xrow_max4(mx);
                 const float m_new = fmaxf(m[nt], mx);
                 if (__any(m_new > m[nt])) {
                     const float alpha = fast_exp2((m[nt] - m_new) * a.c);
@@ -269,8 +268,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
         // ---- the four lane groups hold partial sums of the same rows ---------------------------------------
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            l[nt] += xrow_get(l[nt], 16);
-            l[nt] += xrow_get(l[nt], 32);
+            l[nt] = xrow_sum4(l[nt]);
         }
 
         {

@@ -212,13 +212,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                 for (int kk = 0; kk < 4; ++kk) kf[h][kk] = kb[(h * 4 + kk) * 64 + q4 * 16 + ((n + 4 * kk + q4) & 15)];
             floatx4_t sc[kNTP][2];
 #pragma unroll
-            for (int nt = 0; nt < kNTP; ++nt)
+            for (int kk = 0; kk < 4; ++kk)  // four independent chains interleaved: no instruction waits for the one before
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    sc[nt][h] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+                for (int nt = 0; nt < kNTP; ++nt)
 #pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) sc[nt][h] = mfma16(kf[h][kk], qf[nt][kk], sc[nt][h]);
-                }
+                    for (int h = 0; h < 2; ++h)
+                        sc[nt][h] = mfma16(kf[h][kk], qf[nt][kk], kk ? sc[nt][h] : floatx4_t{0.f, 0.f, 0.f, 0.f});
             if (!full) {
 #pragma unroll
                 for (int nt = 0; nt < kNTP; ++nt) {
@@ -240,17 +239,15 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             bool raise = false;
 #pragma unroll
             for (int nt = 0; nt < kNTP; ++nt) {
-                mx[nt] = fmaxf(fmaxf(fmaxf(sc[nt][0][0], sc[nt][0][1]), fmaxf(sc[nt][0][2], sc[nt][0][3])),
-                               fmaxf(fmaxf(sc[nt][1][0], sc[nt][1][1]), fmaxf(sc[nt][1][2], sc[nt][1][3])));
+                mx[nt] = max8(sc[nt][0], sc[nt][1]);
                 raise |= mx[nt] > m[nt] + slack;
             }
             RA_LAP(2);
             if (__any(raise)) {
 #pragma unroll
                 for (int nt = 0; nt < kNTP; ++nt) {
-                    float r = fmaxf(mx[nt], xrow_get(mx[nt], 16));
-                    r = fmaxf(r, xrow_get(r, 32));
-                    const float m_new = fmaxf(m[nt], r);
+                    const float r = xrow_max4(mx[nt]);
+                    const float m_new = vmax(m[nt], r);
                     const float alpha = fast_exp2((m[nt] - m_new) * a.c);
                     l[nt] *= alpha;
 #pragma unroll
@@ -323,8 +320,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
         // ---- the four lane groups hold partial sums of the same rows; each wave owns its rows ------------------
 #pragma unroll
         for (int nt = 0; nt < kNTP; ++nt) {
-            l[nt] += xrow_get(l[nt], 16);
-            l[nt] += xrow_get(l[nt], 32);
+            l[nt] = xrow_sum4(l[nt]);
             if (!row_ok[nt]) continue;
             if (S_eff > 1) {
                 const size_t pr = rowid[nt] * a.S + s;

@@ -29,6 +29,7 @@ static __device__ long long dbg_ts[kDbgWorkgroups * kDbgSlots];
         lap_[i] += now_ - lap_t_;          \
         lap_t_ = now_;                     \
     } while (0)
+#define RA_LAP_COUNT(i, v) lap_[i] += (v)
 #define RA_LAP_FLUSH(first)                                                              \
     do {                                                                                 \
         const int wg_ = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;  \
@@ -41,5 +42,6 @@ static __device__ long long dbg_ts[kDbgWorkgroups * kDbgSlots];
 #define RA_LAP_DECL
 #define RA_LAP_START
 #define RA_LAP(i)
+#define RA_LAP_COUNT(i, v)
 #define RA_LAP_FLUSH(first)
 #endif

@@ -222,8 +222,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(AttnArgs a) {
                 sc[j] = (j * 4 + grp) < ntok ? d : -__builtin_inff();
             }
             float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-            mx = fmaxf(mx, xrow_get(mx, 16));
-            mx = fmaxf(mx, xrow_get(mx, 32));
+            mx = xrow_max4(mx);
             const float m_new = fmaxf(m[h], mx);
             const float mc = m_new * a.c;
             const float alpha = fast_exp2(__builtin_fmaf(m[h], a.c, -mc));
@@ -258,8 +257,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(AttnArgs a) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
         float lv = l[h];
-        lv += xrow_get(lv, 16);
-        lv += xrow_get(lv, 32);
+        lv = xrow_sum4(lv);
         if (lane == 0) {
             sm[wave * G + h] = m[h];
             sl[wave * G + h] = lv;

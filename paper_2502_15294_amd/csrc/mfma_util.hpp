@@ -16,6 +16,10 @@ __device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
                                                    0, 0, 0);
 }
+// Largest of the eight logits a lane holds of one 16-row x 32-token score tile.
+__device__ __forceinline__ float max8(floatx4_t a, floatx4_t b) {
+    return vmax(vmax3(a[0], a[1], a[2]), vmax3(vmax3(a[3], b[0], b[1]), b[2], b[3]));
+}
 // Two floats -> packed bf16 pair by truncation (low half = a, high half = b).
 __device__ __forceinline__ uint32_t pack_trunc(float a, float b) { return (as_u32(b) & 0xffff0000u) | (as_u32(a) >> 16); }
 // Same value with one byte-permute instruction: bytes 2,3 of a, then bytes 2,3 of b.

@@ -146,11 +146,9 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
     // ---- merge the four 16-lane rows of the wave, then the four waves ------------------------------------
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        float M = fmaxf(m[h], xrow_get(m[h], 16));
-        M = fmaxf(M, xrow_get(M, 32));
+        const float M = xrow_max4(m[h]);
         float lv = l[h] * fast_exp2((m[h] - M) * a.c);
-        lv += xrow_get(lv, 16);
-        lv += xrow_get(lv, 32);
+        lv = xrow_sum4(lv);
         if (lane == 0) {
             sm[wave][h] = M;
             sl[wave][h] = lv;
@@ -435,9 +433,14 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     const size_t part_bytes = align_up(rows * n_chunks_max * sizeof(float), 256);
     // several query tokens: per-head distributions are finished by one workgroup per head and need a buffer
     const size_t p_bytes = (q_len > 1 && !scores_head) ? align_up((size_t)B * Hq * R_max * sizeof(float), 256) : 0;
-    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= kWsReserved + part_bytes + p_bytes, RA_ERR_WORKSPACE,
-               "round_scores: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes,
-               kWsReserved + part_bytes + p_bytes);
+    // more than 16 query rows per KV head on the matrix cores: persistent kernel driven by segment tables
+    const bool many_rows = mfma && q_len * G > 16;
+    const size_t plan_bytes = many_rows ? align_up((size_t)B * plan_stride(R_max + 1), 256) : 0;
+    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= kWsReserved + part_bytes + p_bytes + plan_bytes,
+               RA_ERR_WORKSPACE, "round_scores: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes,
+               kWsReserved + part_bytes + p_bytes + plan_bytes);
+    RA_REQUIRE(!many_rows || (size_t)B * sizeof(int) <= kWsReserved, RA_ERR_UNSUPPORTED, "round_scores: B = %d exceeds %zu",
+               B, kWsReserved / sizeof(int));
 
     ScoreArgs a;
     a.view = to_dev(watershed);
@@ -450,13 +453,18 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     a.chunk_tokens = chunk_tokens;
     a.c = scale * kLog2e;
     a.part = reinterpret_cast<float*>(ctx->ws.base + kWsReserved);
+    a.plan = ctx->ws.base + kWsReserved + part_bytes + p_bytes;
+    a.S = 1 << 20;
+    a.min_units = 16;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const dim3 grid(n_chunks_max, watershed->Hkv, B * q_len);
     const size_t tab_bytes = (size_t)(R_max + 1) * 16 + 16;
     const bool paged = watershed->block_size != 0;
     int rc;
-    if (mfma)
+    if (many_rows) {
+        rc = launch_scores_prefill_mfma(a, paged, ctx->num_cu, st);
+    } else if (mfma)
         rc = launch_scores_mfma(a, paged, ctx->num_cu, st);
     else if (watershed->dtype == RA_BF16)
         rc = dispatch_scores<BF16, 64>(G, paged, grid, tab_bytes, st, a);

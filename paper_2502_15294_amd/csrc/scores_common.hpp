@@ -17,6 +17,9 @@ struct ScoreArgs {
     int chunk_tokens;   // tokens per chunk (a chunk never crosses a round)
     float c;            // scale * log2(e)
     float* part;        // [B][Hq][q_len][n_chunks_max] natural-log sum-exp of the scaled logits of one chunk
+    // many-row kernel only: room for its segment tables and the bounds of its schedule
+    const char* plan;   // [B][plan_stride(R_max + 1)]
+    int S, min_units;   // a sequence is cut into at most S pieces of at least min_units key tiles
 };
 
 __device__ __forceinline__ int chunks_of(int len, int chunk_tokens = kChunkTokens) {
@@ -27,7 +30,8 @@ __device__ __forceinline__ int cur_visible(int cur_len, int q_len, int i) {
     return min(max(cur_len - q_len + i + 1, 0), cur_len);
 }
 
-// bf16, d = 128, Hq/Hkv <= 16: matrix-core streaming kernel for any q_len.
+// bf16, d = 128, Hq/Hkv <= 16: matrix-core streaming kernels, for up to 16 query rows per KV head and for more.
+int launch_scores_prefill_mfma(const ScoreArgs& a, bool paged, int num_cu, hipStream_t st);
 int launch_scores_mfma(const ScoreArgs& a, bool paged, int num_cu, hipStream_t st);
 
 }  // namespace ra

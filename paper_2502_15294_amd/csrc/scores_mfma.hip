@@ -4,31 +4,23 @@
 // tiles of 32 tokens, S^T[16 tokens x 16 rows] = K . Q^T with four mfma 16x16x32 per 16 tokens, and
 // lane%16 is the query row, so the running (max, sum-exp) of a row stays in its lane.
 //
-// Work item: (chunk c of 256 tokens, KV head g, row block, sequence b) -> one log-sum-exp per row.
-//   decode shape (rows <= 16, token split): the four waves take two key tiles each, all loads issued
-//     up front, and are merged through LDS;
-//   prefill shape (row split): the four waves take NT row tiles each and walk the chunk's eight key
-//     tiles together, so a key tile is fetched from HBM once and then served from L1/L2.
+// This kernel serves up to 16 query rows per KV head (decode, very short questions); more rows use the
+// kernel that shares key tiles through LDS.
+// Work item: (chunk c of 256 tokens, KV head g, sequence b) -> one log-sum-exp per row.  The four waves
+// take two key tiles each, all loads issued up front, and are merged through LDS.
 #include "scores_common.hpp"
-#include "stream_kv.hpp"
+#include "mfma_util.hpp"
 #include "debug_ts.hpp"
 
 namespace ra {
 
-typedef __bf16 bf16x8s_t __attribute__((ext_vector_type(8)));
-typedef float floatx4s_t __attribute__((ext_vector_type(4)));
 constexpr int kTileS = 32;
-
-__device__ __forceinline__ floatx4s_t mfma16s(uint4 a, uint4 b, floatx4s_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8s_t, a), __builtin_bit_cast(bf16x8s_t, b),
-                                                   c, 0, 0, 0);
-}
 
 struct KTile {
     uint4 k[2][4];  // [half][kk]: 8 channels kk*32 + 8*(lane/16) .. of token half*16 + lane%16
 };
 
-template <bool PAGED, int NT, bool ROW_SPLIT>
+template <bool PAGED>
 __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     extern __shared__ __align__(16) char smem[];
     __shared__ float sm[4][16], sl[4][16];
@@ -42,7 +34,7 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     const int lane = tid & 63, n = lane & 15, q4 = lane >> 4;
     const int G = a.Hq / Hkv, q_len = a.q_len;
     const int rows_total = q_len * G;
-    constexpr int RB = (ROW_SPLIT ? 4 : 1) * NT * 16;
+    constexpr int NT = 1, RB = 16;
 
     // ---- which round does chunk c belong to? -------------------------------------------------------
     const int n_hist = min(max(vw.n_rounds[b], 0), vw.R_max);
@@ -80,7 +72,7 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     uint4 qf[NT][4];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int row = rowblock * RB + (ROW_SPLIT ? wave * NT * 16 : 0) + nt * 16 + n;
+        const int row = rowblock * RB + nt * 16 + n;
         row_ok[nt] = row < rows_total;
         const int rr = row_ok[nt] ? row : 0;
         const int qtok = rr / G;
@@ -126,12 +118,12 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
         const bool full = !is_cur && (len - tok0 >= kTileS);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            floatx4s_t sc[2];
+            floatx4_t sc[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                sc[h] = floatx4s_t{0.f, 0.f, 0.f, 0.f};
+                sc[h] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) sc[h] = mfma16s(t.k[h][kk], qf[nt][kk], sc[h]);
+                for (int kk = 0; kk < 4; ++kk) sc[h] = mfma16(t.k[h][kk], qf[nt][kk], sc[h]);
             }
             if (!full) {
 #pragma unroll
@@ -155,15 +147,7 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
         }
     };
 
-    if constexpr (ROW_SPLIT) {
-        for (int j = 0; j < kChunkTokens / kTileS; ++j) {
-            const int tok0 = chunk_tok0 + j * kTileS;
-            if (tok0 >= len) break;
-            KTile t;
-            issue(tok0, t);
-            consume(t, tok0);
-        }
-    } else {
+    {
         KTile t[2];
         int tok0[2];
 #pragma unroll
@@ -180,21 +164,13 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     // ---- merge the four lane groups of every row
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        float M = fmaxf(m[nt], xrow_get(m[nt], 16));
-        M = fmaxf(M, xrow_get(M, 32));
+        const float M = xrow_max4(m[nt]);
         float lv = l[nt] * fast_exp2((m[nt] - M) * a.c);
-        lv += xrow_get(lv, 16);
-        lv += xrow_get(lv, 32);
+        lv = xrow_sum4(lv);
         m[nt] = M;
         l[nt] = lv;
     }
-    if constexpr (ROW_SPLIT) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            if (row_ok[nt] && q4 == 0)
-                a.part[rowid[nt] * a.n_chunks_max + c] =
-                    l[nt] > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(l[nt])) : -__builtin_inff();
-    } else {
+    {
         if (q4 == 0) {
             sm[wave][n] = m[0];
             sl[wave][n] = l[0];
@@ -221,24 +197,12 @@ int launch_scores_mfma(const ScoreArgs& a, bool paged, int /*num_cu*/, hipStream
     if (G > 16) return fail(RA_ERR_UNSUPPORTED, "round_scores: Hq / Hkv = %d exceeds 16", G);
     const int rows_total = a.q_len * G;
     const size_t tab_bytes = (size_t)(a.view.R_max + 1) * 16 + 16;
-    if (rows_total <= 16) {
-        const dim3 grid(a.n_chunks_max, a.view.Hkv, a.view.B);
-        if (paged)
-            hipLaunchKernelGGL((scores_mfma_kernel<true, 1, false>), grid, dim3(256), tab_bytes, st, a);
-        else
-            hipLaunchKernelGGL((scores_mfma_kernel<false, 1, false>), grid, dim3(256), tab_bytes, st, a);
-    } else {
-        constexpr int NT = 4;
-        const int rb = 4 * NT * 16;
-        const int n_rowblocks = (rows_total + rb - 1) / rb;
-        if ((long long)a.view.Hkv * n_rowblocks > 65535)
-            return fail(RA_ERR_UNSUPPORTED, "round_scores: too many row blocks (q_len * Hq too large)");
-        const dim3 grid(a.n_chunks_max, a.view.Hkv * n_rowblocks, a.view.B);
-        if (paged)
-            hipLaunchKernelGGL((scores_mfma_kernel<true, NT, true>), grid, dim3(256), tab_bytes, st, a);
-        else
-            hipLaunchKernelGGL((scores_mfma_kernel<false, NT, true>), grid, dim3(256), tab_bytes, st, a);
-    }
+    if (rows_total > 16) return fail(RA_ERR_UNSUPPORTED, "round_scores: %d query rows per KV head in the 16-row kernel", rows_total);
+    const dim3 grid(a.n_chunks_max, a.view.Hkv, a.view.B);
+    if (paged)
+        hipLaunchKernelGGL((scores_mfma_kernel<true>), grid, dim3(256), tab_bytes, st, a);
+    else
+        hipLaunchKernelGGL((scores_mfma_kernel<false>), grid, dim3(256), tab_bytes, st, a);
     return RA_OK;
 }
 

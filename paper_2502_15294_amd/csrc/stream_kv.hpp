@@ -32,6 +32,32 @@ __device__ __forceinline__ float row16_sum(float v) {
     return v;
 }
 __device__ __forceinline__ float xrow_get(float v, int xor_mask) { return __shfl_xor(v, xor_mask, 64); }
+// Maxima without the NaN-quieting copies the compiler puts in front of fmaxf (three instructions per call).
+__device__ __forceinline__ float vmax(float a, float b) {
+    float d;
+    asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+__device__ __forceinline__ float vmax3(float a, float b, float c) {
+    float d;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+// Reductions over the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48); every lane ends with the
+// result.  v_permlane16_swap / v_permlane32_swap applied to two copies of a value hand each lane the values of
+// both rows of a pair (of both halves of the wave), so the exchange stays in the vector ALU.
+__device__ __forceinline__ float xrow_max4(float v) {
+    auto a = __builtin_amdgcn_permlane16_swap(as_u32(v), as_u32(v), false, false);
+    v = vmax(as_f32(a[0]), as_f32(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
+    return vmax(as_f32(b[0]), as_f32(b[1]));
+}
+__device__ __forceinline__ float xrow_sum4(float v) {
+    auto a = __builtin_amdgcn_permlane16_swap(as_u32(v), as_u32(v), false, false);
+    v = as_f32(a[0]) + as_f32(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
+    return as_f32(b[0]) + as_f32(b[1]);
+}
 
 // Element-type specific pieces.  A lane's share of one K or V row is WORDS 32-bit words.
 struct F32 {};
@@ -208,7 +234,8 @@ __device__ inline int schedule_from_counts(int B, int S, int min_units, long lon
 }
 
 // Largest slot with cum[slot] <= u, for 0 <= u < cum[n].
-__device__ __forceinline__ int find_slot(const int* cum, int n, int u) {
+template <typename T>
+__device__ __forceinline__ int find_slot(const T* cum, int n, T u) {
     int lo = 0, hi = n;  // invariant: cum[lo] <= u < cum[hi]
     while (hi - lo > 1) {
         int mid = (lo + hi) >> 1;
