@@ -107,20 +107,26 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             for (int dt = 0; dt < 8; ++dt) acc[nt][dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
         }
 
-        // Uniform description of the segment the loader stands in; the table in LDS is only read when the
-        // loader enters a segment, so a tile's addresses cost a few scalar operations.
-        int seg_len = 0, seg_nblk = 0, seg_first = 0, seg_end = 0;
+        // Uniform state of the loader: the segment it stands in (the table in LDS is only read on entry) and,
+        // inside it, the next tile: the addresses of its first token's keys and of its first V^T block (head g)
+        // and the tokens left from there.  A tile's addresses then cost a handful of scalar operations.
+        int seg_len = 0, seg_first = 0, seg_end = 0, rows_left = 0;
         bool seg_cur = false;
         const char *seg_k = nullptr, *seg_v = nullptr;  // contiguous history / current round: token 0 of head g
+        const char *tile_k = nullptr, *tile_v = nullptr;
         long long seg_tab = 0;                          // paged history: first block-table slot
+        unsigned kstride = 256;                         // bytes from one token's keys to the next
+        const int row_a = 8 * wave + q4;                // this lane loads chunk n of tile rows row_a and row_a + 4
+        unsigned off_a = 0, off_b = 0;                  // their byte offsets from tile_k
+        const unsigned off_v = ((2 * wave * 16 + n) * 4 + q4) * 8;  // V^T fragment (dt = 2*wave) inside a 16-token block
         auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
         auto uni64 = [&](long long x) { return ((long long)uni((int)(x >> 32)) << 32) | (unsigned)uni((int)x); };
-        auto open_seg = [&](int slot) {
+        auto open_seg = [&](int slot, int u) {  // ... and stand at its tile u - first
             seg_len = uni(tab.len[slot]);
             seg_first = uni(tab.cum[slot]);
             seg_end = uni(tab.cum[slot + 1]);
-            seg_nblk = (seg_len + 15) >> 4;
             seg_cur = slot >= n_hist;
+            kstride = seg_cur ? (unsigned)Hkv * 256u : 256u;
             if (seg_cur) {
                 seg_k = ck + ((size_t)b * a.cur_cap * Hkv + g) * 256;
                 seg_v = cv + ((size_t)b * a.cur_cap * Hkv + g) * 256;
@@ -128,61 +134,73 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                 seg_tab = uni64(tab.off_k[slot]);
             } else {
                 seg_k = kbase + ((size_t)uni64(tab.off_k[slot]) * Hkv + (size_t)g * seg_len) * 256;
-                seg_v = vbase + ((size_t)uni64(tab.off_v[slot]) * Hkv + (size_t)g * seg_nblk * 16) * 256;
+                seg_v = vbase + ((size_t)uni64(tab.off_v[slot]) * Hkv + (size_t)g * ((seg_len + 15) & ~15)) * 256;
             }
+            off_a = (unsigned)row_a * kstride + n * 16;
+            off_b = off_a + 4 * kstride;
+            const int uin = u - seg_first;
+            rows_left = seg_len - uin * kTileP;
+            tile_k = seg_k + (size_t)uin * kTileP * kstride;
+            tile_v = seg_v + (size_t)uin * 8192;
         };
-        // This wave's quarter of tile `uin` of the open segment: eight key rows of half wave/2,
-        // V fragments (dt = 2*wave + j/2, half = j%2).  Halves past the segment's end re-read its last
-        // 16-token block (their scores are masked).
-        auto load_share = [&](int uin) -> Share {
+        // This wave's quarter of the next tile: key rows 8*wave .. +7 (chunk n of two rows per lane) and the
+        // V^T fragments (dt, half) = (2*wave, 0), (2*wave, 1), (2*wave + 1, 0), (2*wave + 1, 1); afterwards the
+        // loader stands at the tile that follows.  Rows and blocks past the segment's end re-read its last ones
+        // (their scores are masked).
+        auto load_share = [&]() -> Share {
             Share sh;
-            const size_t kstride = seg_cur ? (size_t)Hkv * 256 : 256;  // bytes from one token's keys to the next
-            const int blk0 = min(uin * 2, seg_nblk - 1), blk1 = min(uin * 2 + 1, seg_nblk - 1);
-            const char *kb0, *kb1, *vb0, *vb1;
+            const int tok0 = seg_len - rows_left;
             if (!seg_cur && PAGED) {
+                const int blk0 = tok0 >> 4, blk1 = min(blk0 + 1, (seg_len - 1) >> 4);
                 const long long last = vw.max_blocks - 1;
                 const long long s0 = min(max(seg_tab + blk0, 0ll), last), s1 = min(max(seg_tab + blk1, 0ll), last);
                 const int p0 = max(uni(vw.block_table[(size_t)b * vw.max_blocks + s0]), 0);
                 const int p1 = max(uni(vw.block_table[(size_t)b * vw.max_blocks + s1]), 0);
-                kb0 = kbase + ((size_t)p0 * Hkv + g) * 4096;
-                kb1 = kbase + ((size_t)p1 * Hkv + g) * 4096;
-                vb0 = vbase + ((size_t)p0 * Hkv + g) * 4096;
-                vb1 = vbase + ((size_t)p1 * Hkv + g) * 4096;
-            } else {
-                kb0 = seg_k + (size_t)blk0 * 16 * kstride;
-                kb1 = seg_k + (size_t)blk1 * 16 * kstride;
-                vb0 = seg_v + (size_t)blk0 * 4096;
-                vb1 = seg_v + (size_t)blk1 * 4096;
-            }
-            {   // keys: whole 256-byte rows, 16 lanes per row (rows 8*(wave%2) + 4*j + lane/16 of half wave/2)
                 const bool upper = wave >> 1;
-                const char* kb = upper ? kb1 : kb0;
+                const char* kb = kbase + ((size_t)(upper ? p1 : p0) * Hkv + g) * 4096;
                 const int last_row = seg_len - 1 - (upper ? blk1 : blk0) * 16;
                 const int r0 = min(8 * (wave & 1) + q4, last_row), r1 = min(8 * (wave & 1) + 4 + q4, last_row);
-                sh.k0 = *reinterpret_cast<const uint4*>(kb + (size_t)r0 * kstride + n * 16);
-                sh.k1 = *reinterpret_cast<const uint4*>(kb + (size_t)r1 * kstride + n * 16);
-            }
-            if (seg_cur) {  // token-major values: gather 4 tokens of one channel with 2-byte loads
-                auto gather = [&](int dt, int blk) {
-                    uint32_t e[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const int tok = min(blk * 16 + q4 * 4 + t, seg_len - 1);
-                        e[t] = *reinterpret_cast<const unsigned short*>(seg_v + (size_t)tok * kstride + (dt * 16 + n) * 2);
-                    }
-                    return make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
-                };
-                sh.v0 = gather(2 * wave, blk0);
-                sh.v1 = gather(2 * wave, blk1);
-                sh.v2 = gather(2 * wave + 1, blk0);
-                sh.v3 = gather(2 * wave + 1, blk1);
+                sh.k0 = *reinterpret_cast<const uint4*>(kb + r0 * 256 + n * 16);
+                sh.k1 = *reinterpret_cast<const uint4*>(kb + r1 * 256 + n * 16);
+                const char* vb0 = vbase + ((size_t)p0 * Hkv + g) * 4096;
+                const char* vb1 = vbase + ((size_t)p1 * Hkv + g) * 4096;
+                sh.v0 = *reinterpret_cast<const uint2*>(vb0 + off_v);
+                sh.v1 = *reinterpret_cast<const uint2*>(vb1 + off_v);
+                sh.v2 = *reinterpret_cast<const uint2*>(vb0 + off_v + 512);
+                sh.v3 = *reinterpret_cast<const uint2*>(vb1 + off_v + 512);
             } else {
-                const int o = ((2 * wave * 16 + n) * 4 + q4) * 8;
-                sh.v0 = *reinterpret_cast<const uint2*>(vb0 + o);
-                sh.v1 = *reinterpret_cast<const uint2*>(vb1 + o);
-                sh.v2 = *reinterpret_cast<const uint2*>(vb0 + o + 512);
-                sh.v3 = *reinterpret_cast<const uint2*>(vb1 + o + 512);
+                if (rows_left >= kTileP) {
+                    sh.k0 = *reinterpret_cast<const uint4*>(tile_k + off_a);
+                    sh.k1 = *reinterpret_cast<const uint4*>(tile_k + off_b);
+                } else {
+                    sh.k0 = *reinterpret_cast<const uint4*>(tile_k + (unsigned)min(row_a, rows_left - 1) * kstride + n * 16);
+                    sh.k1 = *reinterpret_cast<const uint4*>(tile_k + (unsigned)min(row_a + 4, rows_left - 1) * kstride + n * 16);
+                }
+                if (seg_cur) {  // token-major values: gather 4 tokens of one channel with 2-byte loads
+                    auto gather = [&](int dt, int h) {
+                        uint32_t e[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const int tok = min(tok0 + h * 16 + q4 * 4 + t, seg_len - 1);
+                            e[t] = *reinterpret_cast<const unsigned short*>(seg_v + (size_t)tok * kstride + (dt * 16 + n) * 2);
+                        }
+                        return make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
+                    };
+                    sh.v0 = gather(2 * wave, 0);
+                    sh.v1 = gather(2 * wave, 1);
+                    sh.v2 = gather(2 * wave + 1, 0);
+                    sh.v3 = gather(2 * wave + 1, 1);
+                } else {
+                    const unsigned second = rows_left > 16 ? 4096u : 0u;  // the tile's second 16-token block, if any
+                    sh.v0 = *reinterpret_cast<const uint2*>(tile_v + off_v);
+                    sh.v1 = *reinterpret_cast<const uint2*>(tile_v + (off_v + second));
+                    sh.v2 = *reinterpret_cast<const uint2*>(tile_v + (off_v + 512));
+                    sh.v3 = *reinterpret_cast<const uint2*>(tile_v + (off_v + second + 512));
+                }
             }
+            rows_left -= kTileP;
+            tile_k += (size_t)kTileP * kstride;
+            tile_v += 8192;
             return sh;
         };
         // LDS tile: K operand fragment (half, kk) holds its 64 lanes' 16-byte pieces at
@@ -200,8 +218,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             vd[128] = sh.v2;
             vd[192] = sh.v3;
         };
-        auto consume = [&](const char* buf, int uin, int len, bool is_cur) {
-            const int tok0 = uin * kTileP;
+        auto consume = [&](const char* buf, int tok0, int len, bool is_cur) {
             const bool full = !is_cur && (len - tok0 >= kTileP);
             const uint4* kb = reinterpret_cast<const uint4*>(buf);
             const uint2* vb = reinterpret_cast<const uint2*>(buf + 8192);
@@ -255,9 +272,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                     m[nt] = m_new;
                 }
             }
-            uint4 phi[kNTP], plo[kNTP];
+            uint4 vf[8];  // V^T operand fragments of the tile, shared by both row tiles
 #pragma unroll
-            for (int nt = 0; nt < kNTP; ++nt) {
+            for (int dt = 0; dt < 8; ++dt) {
+                const uint2 v0 = vb[(dt * 2 + 0) * 64 + lane], v1 = vb[(dt * 2 + 1) * 64 + lane];
+                vf[dt] = make_uint4(v0.x, v0.y, v1.x, v1.y);
+            }
+            auto probabilities = [&](int nt, uint4& phi, uint4& plo) {  // P = hi + lo of row tile nt, and its row sums
                 const float mc = m[nt] * a.c;
                 float p[8];
 #pragma unroll
@@ -265,52 +286,58 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
 #pragma unroll
                     for (int i = 0; i < 4; ++i) p[h * 4 + i] = fast_exp2(__builtin_fmaf(sc[nt][h][i], a.c, -mc));
                 l[nt] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-                phi[nt].x = pack_hi16(p[0], p[1]);
-                phi[nt].y = pack_hi16(p[2], p[3]);
-                phi[nt].z = pack_hi16(p[4], p[5]);
-                phi[nt].w = pack_hi16(p[6], p[7]);
-                plo[nt].x = pack_hi16(p[0] - trunc_bf16(p[0]), p[1] - trunc_bf16(p[1]));
-                plo[nt].y = pack_hi16(p[2] - trunc_bf16(p[2]), p[3] - trunc_bf16(p[3]));
-                plo[nt].z = pack_hi16(p[4] - trunc_bf16(p[4]), p[5] - trunc_bf16(p[5]));
-                plo[nt].w = pack_hi16(p[6] - trunc_bf16(p[6]), p[7] - trunc_bf16(p[7]));
-            }
-            RA_LAP(3);
+                phi.x = pack_hi16(p[0], p[1]);
+                phi.y = pack_hi16(p[2], p[3]);
+                phi.z = pack_hi16(p[4], p[5]);
+                phi.w = pack_hi16(p[6], p[7]);
+                plo.x = pack_hi16(p[0] - trunc_bf16(p[0]), p[1] - trunc_bf16(p[1]));
+                plo.y = pack_hi16(p[2] - trunc_bf16(p[2]), p[3] - trunc_bf16(p[3]));
+                plo.z = pack_hi16(p[4] - trunc_bf16(p[4]), p[5] - trunc_bf16(p[5]));
+                plo.w = pack_hi16(p[6] - trunc_bf16(p[6]), p[7] - trunc_bf16(p[7]));
+            };
+            auto accumulate = [&](int nt, const uint4& phi, const uint4& plo) {
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                const uint2 v0 = vb[(dt * 2 + 0) * 64 + lane], v1 = vb[(dt * 2 + 1) * 64 + lane];
-                const uint4 vf = make_uint4(v0.x, v0.y, v1.x, v1.y);
-#pragma unroll
-                for (int nt = 0; nt < kNTP; ++nt) {
-                    acc[nt][dt] = mfma16(vf, phi[nt], acc[nt][dt]);
-                    acc[nt][dt] = mfma16(vf, plo[nt], acc[nt][dt]);
+                for (int dt = 0; dt < 8; ++dt) {
+                    acc[nt][dt] = mfma16(vf[dt], phi, acc[nt][dt]);
+                    acc[nt][dt] = mfma16(vf[dt], plo, acc[nt][dt]);
                 }
-            }
+            };
+            // Row tile by row tile: the first tile's products can run on the matrix cores while the vector ALU
+            // turns the second tile's logits into probabilities.
+            uint4 phi0, plo0, phi1, plo1;
+            probabilities(0, phi0, plo0);
+            accumulate(0, phi0, plo0);
+            probabilities(1, phi1, plo1);
+            accumulate(1, phi1, plo1);
+            RA_LAP(3);
         };
 
         // ---- walk the key tiles: the whole workgroup in lockstep -----------------------------------------
         RA_TS(2);
         if (u_lo < u_hi) {
             int slot = find_slot(tab.cum, n_slots, u_lo);
-            open_seg(slot);
-            Share sh = load_share(u_lo - seg_first);
+            open_seg(slot, u_lo);
+            int c_tok0 = seg_len - rows_left;
+            Share sh = load_share();
             int bufsel = 0;
             for (int u = u_lo; u < u_hi; ++u) {
                 char* buf = tiles + bufsel * kTileBytes;
                 RA_LAP_START;
                 store_share(buf, sh);
-                const int len = seg_len, uin = u - seg_first;  // of the tile just stored
+                const int len = seg_len, tok0 = c_tok0;  // of the tile just stored
                 const bool is_cur = seg_cur;
                 __syncthreads();
                 RA_LAP(0);
                 if (u + 1 < u_hi) {
                     if (u + 1 >= seg_end) {
                         do ++slot; while (u + 1 >= uni(tab.cum[slot + 1]));
-                        open_seg(slot);
+                        open_seg(slot, u + 1);
                     }
-                    sh = load_share(u + 1 - seg_first);
+                    c_tok0 = seg_len - rows_left;
+                    sh = load_share();
                 }
                 RA_LAP(1);
-                consume(buf, uin, len, is_cur);
+                consume(buf, tok0, len, is_cur);
                 RA_LAP(5);
                 bufsel ^= 1;
             }

@@ -111,9 +111,9 @@ int ra_workspace_bytes(const ra_problem* p, size_t* bytes_out) {
     const size_t rows = (size_t)p->B * p->q_len_max * p->Hq;
     // attention partials: up to 64 splits of (d accumulators + running max + running sum) per output row
     const size_t attn = rows * 64 * ((size_t)p->d + 2) * sizeof(float);
-    // score intermediates: one log-sum-exp per (row, 256-token chunk), plus a per-head score buffer
+    // score intermediates: one log-sum-exp per (row, 256-token chunk), plus up to eight partial per-head score rows
     const size_t chunks = (size_t)(p->max_tokens / 256) + p->R_max + 2;
-    const size_t sc = rows * chunks * sizeof(float) + (size_t)p->B * p->Hq * p->R_max * sizeof(float);
+    const size_t sc = rows * chunks * sizeof(float) + (size_t)8 * p->B * p->Hq * p->R_max * sizeof(float) + 256;
     const size_t both = align_up(attn, 256) > align_up(sc, 256) + 256 ? align_up(attn, 256) : align_up(sc, 256) + 256;
     const size_t plan = (size_t)p->B * (((size_t)(p->R_max + 1) * 24 + 4 + 16 + 15) & ~(size_t)15);
     *bytes_out = kWsReserved + align_up(plan, 256) + both + 3 * 256;

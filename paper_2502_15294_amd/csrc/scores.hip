@@ -285,14 +285,14 @@ __global__ __launch_bounds__(W * 64) void scores_finish_kernel(FinishArgs a, boo
     }
 }
 
-// Finishing kernel for several query tokens: grid (B, Hq), block 512.  One workgroup per (sequence, head);
-// its eight waves take the query tokens i = wave, wave + 8, ...  A wave first copies token i's row of chunk
-// log-sum-exps into its own LDS strip with coalesced loads (when it fits), then every lane folds the
-// chunks of its rounds.  The per-wave round masses are summed over the waves in LDS in a fixed order,
-// normalised, and written to p_buf [B][Hq][R_max]; the head mean is taken by scores_head_mean_kernel.
+// Finishing kernel for several query tokens: grid (B, Hq, Z), block 512.  Z workgroups per (sequence, head);
+// the eight waves of workgroup z take the query tokens i = 8*z + wave, + 8*Z, ...  A wave first copies token
+// i's row of chunk log-sum-exps into its own LDS strip with coalesced loads (when it fits), then every lane
+// folds the chunks of its rounds.  The per-wave round masses are summed over the waves in LDS in a fixed
+// order and written, not yet normalised, to p_part [B][Hq][Z][R_max]; scores_heads_kernel finishes.
 
 template <int KPL>
-__global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_rows_kernel(FinishArgs a, float* p_buf,
+__global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_rows_kernel(FinishArgs a, float* p_part,
                                                                                 bool stage_rows) {
     extern __shared__ __align__(16) char smem[];
     int* cum = reinterpret_cast<int*>(smem);                        // [R_max + 2]
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_rows_kernel(F
 #pragma unroll
     for (int k = 0; k < KPL; ++k) qatt[k] = 0.f;
     float* mybuf = rowbuf + (size_t)wave * a.n_chunks_max;
-    for (int i = wave; i < a.q_len && !overflow; i += kFinishWaves) {
+    for (int i = blockIdx.z * kFinishWaves + wave; i < a.q_len && !overflow; i += kFinishWaves * gridDim.z) {
         const float* row = a.part + (((size_t)b * a.Hq + h) * a.q_len + i) * a.n_chunks_max;
         if (stage_rows) {
             for (int c = lane; c < all_chunks; c += 64) mybuf[c] = row[c];
@@ -348,33 +348,60 @@ __global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_rows_kernel(F
     }
     __syncthreads();
     if (wave == 0) {
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            const int r = lane + 64 * k;
+            float tot = 0.f;
+            if (r < R)
+                for (int w = 0; w < kFinishWaves; ++w) tot += hs[w * a.R_max + r];
+            if (r < a.R_max)
+                p_part[(((size_t)b * a.Hq + h) * gridDim.z + blockIdx.z) * a.R_max + r] = overflow ? __builtin_nanf("") : tot;
+        }
+    }
+}
+
+// grid (B), block 1024: per head, the Z partial round masses are added in order and normalised over the rounds
+// (Eq. 1; written to p_out [B][Hq][R_max] if given); scores[b][r] is the mean over heads.  A wave takes heads
+// wave, wave + 16, ... and a lane the rounds lane, lane + 64, ..., so all sums run in a fixed order.
+constexpr int kHeadsWaves = 16;
+__global__ __launch_bounds__(kHeadsWaves * 64) void scores_heads_kernel(const float* p_part, int Z, int R_max, int Hq,
+                                                                        float* p_out, float* s_out) {
+    extern __shared__ __align__(16) char smem[];
+    float* sacc = reinterpret_cast<float*>(smem);  // [kHeadsWaves][R_max]
+    constexpr int KPL = kMaxRounds / 64;
+    const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float mine[KPL];  // this wave's sum over its heads of the normalised masses of rounds lane + 64 k
+#pragma unroll
+    for (int k = 0; k < KPL; ++k) mine[k] = 0.f;
+    for (int h = wave; h < Hq; h += kHeadsWaves) {
+        const float* ph = p_part + ((size_t)b * Hq + h) * Z * R_max;
         float tot[KPL], all = 0.f;
 #pragma unroll
         for (int k = 0; k < KPL; ++k) {
             const int r = lane + 64 * k;
             tot[k] = 0.f;
-            if (r < R)
-                for (int w = 0; w < kFinishWaves; ++w) tot[k] += hs[w * a.R_max + r];
+            if (r < R_max)
+                for (int z = 0; z < Z; ++z) tot[k] += ph[(size_t)z * R_max + r];
             all += tot[k];
         }
         all = wave_sum(all);
-        const float inv = all > 0.f ? 1.f / all : 0.f;
+        const float inv = all > 0.f ? 1.f / all : (all == all ? 0.f : all);  // (NaN marks an undersized pass)
 #pragma unroll
         for (int k = 0; k < KPL; ++k) {
             const int r = lane + 64 * k;
-            if (r < a.R_max)
-                p_buf[((size_t)b * a.Hq + h) * a.R_max + r] = overflow ? __builtin_nanf("") : (r < R ? tot[k] * inv : 0.f);
+            const float p = tot[k] * inv;
+            if (p_out && r < R_max) p_out[((size_t)b * Hq + h) * R_max + r] = p;
+            mine[k] += p;
         }
     }
-}
-
-// grid (B), block 256: scores[b][r] = mean over heads of p_buf[b][h][r], heads added in order.
-__global__ __launch_bounds__(256) void scores_head_mean_kernel(const float* p_buf, int R_max, int Hq, float* s_out) {
-    const int b = blockIdx.x;
+#pragma unroll
+    for (int k = 0; k < KPL; ++k)
+        if (lane + 64 * k < R_max) sacc[wave * R_max + lane + 64 * k] = mine[k];
+    __syncthreads();
     const float inv_h = 1.f / (float)Hq;
-    for (int r = threadIdx.x; r < R_max; r += 256) {
+    for (int r = threadIdx.x; r < R_max; r += kHeadsWaves * 64) {
         float s = 0.f;
-        for (int h = 0; h < Hq; ++h) s += p_buf[((size_t)b * Hq + h) * R_max + r];
+        for (int w = 0; w < kHeadsWaves; ++w) s += sacc[w * R_max + r];
         s_out[(size_t)b * R_max + r] = s * inv_h;
     }
 }
@@ -431,8 +458,10 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     const int n_chunks_max = (int)(nc64 < 1 ? 1 : nc64);
     const size_t rows = (size_t)B * Hq * q_len;
     const size_t part_bytes = align_up(rows * n_chunks_max * sizeof(float), 256);
-    // several query tokens: per-head distributions are finished by one workgroup per head and need a buffer
-    const size_t p_bytes = (q_len > 1 && !scores_head) ? align_up((size_t)B * Hq * R_max * sizeof(float), 256) : 0;
+    // several query tokens: Z workgroups per head leave partial round masses in a buffer
+    int Z = q_len / 32 < 1 ? 1 : (q_len / 32 > 8 ? 8 : q_len / 32);
+    while (Z > 1 && (int64_t)B * Hq * Z > 2048) --Z;
+    const size_t p_bytes = q_len > 1 ? align_up((size_t)B * Hq * Z * R_max * sizeof(float), 256) : 0;
     // more than 16 query rows per KV head on the matrix cores: persistent kernel driven by segment tables
     const bool many_rows = mfma && q_len * G > 16;
     const size_t plan_bytes = many_rows ? align_up((size_t)B * plan_stride(R_max + 1), 256) : 0;
@@ -489,11 +518,11 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     const size_t fin_smem = (size_t)(R_max + 2) * sizeof(int) + (size_t)kFinishWaves * R_max * sizeof(float);
     const dim3 fin_block(kFinishWaves * 64);
     if (q_len > 1) {
-        float* p_buf = scores_head ? scores_head : reinterpret_cast<float*>(ctx->ws.base + kWsReserved + part_bytes);
+        float* p_buf = reinterpret_cast<float*>(ctx->ws.base + kWsReserved + part_bytes);
         const bool stage_rows =
             n_chunks_max <= kRowBufMax && fin_smem + (size_t)kFinishWaves * n_chunks_max * sizeof(float) <= 60 * 1024;
         const size_t smem = fin_smem + (stage_rows ? (size_t)kFinishWaves * n_chunks_max * sizeof(float) : 0);
-        const dim3 fgrid(B, Hq);
+        const dim3 fgrid(B, Hq, Z);
         if (R_max <= 64)
             hipLaunchKernelGGL((scores_finish_rows_kernel<1>), fgrid, fin_block, smem, st, f, p_buf, stage_rows);
         else if (R_max <= 256)
@@ -501,7 +530,8 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
         else
             hipLaunchKernelGGL((scores_finish_rows_kernel<kMaxRounds / 64>), fgrid, fin_block, smem, st, f, p_buf,
                                stage_rows);
-        hipLaunchKernelGGL(scores_head_mean_kernel, dim3(B), dim3(256), 0, st, p_buf, R_max, Hq, scores);
+        hipLaunchKernelGGL(scores_heads_kernel, dim3(B), dim3(kHeadsWaves * 64), (size_t)kHeadsWaves * R_max * sizeof(float),
+                           st, p_buf, Z, R_max, Hq, scores_head, scores);
     } else {
         const bool stage_rows =
             n_chunks_max <= kRowBufMax && fin_smem + (size_t)kFinishWaves * n_chunks_max * sizeof(float) <= 60 * 1024;

@@ -317,6 +317,7 @@ def test_prefill_with_one_query_token_equals_decode():
 
 
 SCORE_PREFILL_CASES = {
+    "q3_cur7_one_row_tile": dict(B=2, R=4, q_len=3, cur_len=7, length=("uniform", 10, 300)),
     "q8_cur8": dict(B=2, R=5, q_len=8, cur_len=8, length=("uniform", 10, 150)),
     "q40_cur64": dict(B=2, R=6, q_len=40, cur_len=64, length=("uniform", 20, 600)),
     "q100_two_rowblocks": dict(B=1, R=7, q_len=100, cur_len=100, length=("uniform", 20, 400)),
@@ -425,4 +426,15 @@ def test_understated_max_tokens_is_reported_as_nan_scores():
     _, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), small, scale=w.scale)
     torch.cuda.synchronize()
     assert np.isnan(S.cpu().numpy()).all()
+    # the kernel for many query rows walks the true lengths: it must drop the chunks that have no room, not write them
+    wq = make_workload("cfg3", B=1, R=6, q_len=24, cur_len=24, length=("fixed", 600))
+    engq = Engine(wq)
+    vq = device_view(wq, 0, with_v=False)
+    k, v, seg_off, seg_len, n_rounds, bt, seg_off_v = vq.tensors
+    smallq = ra.KVView(k, v, seg_off, seg_len, n_rounds, vq.Hkv, vq.d, 256)
+    _, Sq = ra.ra_round_scores(engq.ctx, to_device(wq.q(0), wq.dtype), smallq, to_device(wq.cur_k(0), wq.dtype),
+                               scale=wq.scale)
+    torch.cuda.synchronize()
+    assert np.isnan(Sq.cpu().numpy()).all()
+    engq.close()
     eng.close()
