@@ -26,6 +26,7 @@ RA_OK, RA_ERR_INVALID_ARG, RA_ERR_UNSUPPORTED, RA_ERR_WORKSPACE, RA_ERR_STATE, R
 
 EXPORTS = [
     "ra_last_error", "ra_create", "ra_destroy", "ra_workspace_bytes", "ra_set_workspace",
+    "ra_profile_kernels", "ra_profile_last_ms",
     "ra_round_scores", "ra_select_rounds", "ra_round_sparse_attn_decode", "ra_round_sparse_attn_prefill",
     "ra_kv_store_create", "ra_kv_store_destroy", "ra_kv_store_register_round", "ra_kv_store_round_bytes",
     "ra_kv_store_stage", "ra_kv_store_wait_layer", "ra_kv_store_layer_view", "ra_kv_store_stats",
@@ -80,6 +81,8 @@ def lib() -> C.CDLL:
         L.ra_destroy.argtypes = [C.c_void_p]
         L.ra_workspace_bytes.argtypes = [C.POINTER(ra_problem), C.POINTER(C.c_size_t)]
         L.ra_set_workspace.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+        L.ra_profile_kernels.argtypes = [C.c_void_p, C.c_int]
+        L.ra_profile_last_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.ra_round_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(ra_kv_view),
                                       C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p]
         L.ra_select_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
@@ -183,6 +186,16 @@ def ra_set_workspace(ctx, workspace: Optional[torch.Tensor]) -> None:
         _check(lib().ra_set_workspace(ctx, None, 0))
     else:
         _check(lib().ra_set_workspace(ctx, workspace.data_ptr(), workspace.numel() * workspace.element_size()))
+
+
+def ra_profile_kernels(ctx, enable: bool) -> None:
+    _check(lib().ra_profile_kernels(ctx, 1 if enable else 0))
+
+
+def ra_profile_last_ms(ctx) -> float:
+    ms = C.c_float(0.0)
+    _check(lib().ra_profile_last_ms(ctx, C.byref(ms)))
+    return ms.value
 
 
 # ---- compute -----------------------------------------------------------------------------------

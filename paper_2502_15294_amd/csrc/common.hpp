@@ -33,7 +33,27 @@ struct ra_ctx {
     int device = 0;
     int num_cu = 256;
     ra::Workspace ws;
+    // kernel timing on request (ra_profile_kernels)
+    bool profile = false, timed = false;
+    hipEvent_t ev_start = nullptr, ev_stop = nullptr;
 };
+
+namespace ra {
+// Brackets the launches made during its lifetime with the context's two events when profiling is on.
+struct KernelTimer {
+    ra_ctx* c;
+    hipStream_t st;
+    KernelTimer(ra_ctx* ctx, hipStream_t stream) : c(ctx), st(stream) {
+        if (c->profile) (void)hipEventRecord(c->ev_start, st);
+    }
+    ~KernelTimer() {
+        if (c->profile) {
+            (void)hipEventRecord(c->ev_stop, st);
+            c->timed = true;
+        }
+    }
+};
+}  // namespace ra
 
 namespace ra {
 

@@ -98,7 +98,31 @@ int ra_create(ra_ctx** out, int device) {
 }
 
 int ra_destroy(ra_ctx* ctx) {
+    if (ctx) {
+        if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
+        if (ctx->ev_stop) (void)hipEventDestroy(ctx->ev_stop);
+    }
     delete ctx;
+    return RA_OK;
+}
+
+int ra_profile_kernels(ra_ctx* ctx, int enable) {
+    RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "ra_profile_kernels: ctx is NULL");
+    if (enable && !ctx->ev_start) {
+        RA_HIP_CHECK(hipEventCreate(&ctx->ev_start));
+        RA_HIP_CHECK(hipEventCreate(&ctx->ev_stop));
+    }
+    ctx->profile = enable != 0;
+    ctx->timed = false;
+    return RA_OK;
+}
+
+int ra_profile_last_ms(ra_ctx* ctx, float* ms_out) {
+    RA_REQUIRE(ctx != nullptr && ms_out != nullptr, RA_ERR_INVALID_ARG, "ra_profile_last_ms: NULL argument");
+    RA_REQUIRE(ctx->profile && ctx->timed, RA_ERR_STATE,
+               "ra_profile_last_ms: no profiled call since ra_profile_kernels(ctx, 1)");
+    RA_HIP_CHECK(hipEventSynchronize(ctx->ev_stop));
+    RA_HIP_CHECK(hipEventElapsedTime(ms_out, ctx->ev_start, ctx->ev_stop));
     return RA_OK;
 }
 

@@ -428,16 +428,19 @@ extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void
     const bool paged = layer->block_size != 0;
     int rc;
     launch_plan(a, mfma ? 32 : kUnitTokens, st);
-    if (mfma) {
-        rc = launch_attn_mfma(a, paged, ctx->num_cu, st);
-    } else {
-        const dim3 grid(S, layer->Hkv, B);
-        const size_t tab_bytes = align_up(SlotTable::bytes(layer->R_max + 1), 16);
-        if (layer->dtype == RA_BF16)
-            rc = dispatch_generic<BF16, 64>(paged, grid, st, a, tab_bytes);
-        else
-            rc = D == 128 ? dispatch_generic<F32, 128>(paged, grid, st, a, tab_bytes)
-                          : dispatch_generic<F32, 64>(paged, grid, st, a, tab_bytes);
+    {
+        KernelTimer timer(ctx, st);
+        if (mfma) {
+            rc = launch_attn_mfma(a, paged, ctx->num_cu, st);
+        } else {
+            const dim3 grid(S, layer->Hkv, B);
+            const size_t tab_bytes = align_up(SlotTable::bytes(layer->R_max + 1), 16);
+            if (layer->dtype == RA_BF16)
+                rc = dispatch_generic<BF16, 64>(paged, grid, st, a, tab_bytes);
+            else
+                rc = D == 128 ? dispatch_generic<F32, 128>(paged, grid, st, a, tab_bytes)
+                              : dispatch_generic<F32, 64>(paged, grid, st, a, tab_bytes);
+        }
     }
     if (rc) return rc;
     if (S > 1) launch_combine(a, D, rows, st);

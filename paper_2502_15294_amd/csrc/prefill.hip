@@ -67,9 +67,12 @@ extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const voi
     // Few query rows per KV head: the decode kernel's token split keeps all four waves busy; otherwise
     // the kernel whose waves own different rows and share each key tile through LDS.
     const bool few_rows = q_len * G <= 32;
-    if (int rc = few_rows ? launch_attn_mfma(a, layer->block_size != 0, ctx->num_cu, st)
-                          : launch_attn_prefill_mfma(a, layer->block_size != 0, ctx->num_cu, st))
-        return rc;
+    {
+        KernelTimer timer(ctx, st);
+        if (int rc = few_rows ? launch_attn_mfma(a, layer->block_size != 0, ctx->num_cu, st)
+                              : launch_attn_prefill_mfma(a, layer->block_size != 0, ctx->num_cu, st))
+            return rc;
+    }
     if (S > 1) launch_combine(a, D, rows, st);
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;

@@ -491,15 +491,19 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     const size_t tab_bytes = (size_t)(R_max + 1) * 16 + 16;
     const bool paged = watershed->block_size != 0;
     int rc;
-    if (many_rows) {
-        rc = launch_scores_prefill_mfma(a, paged, ctx->num_cu, st);
-    } else if (mfma)
-        rc = launch_scores_mfma(a, paged, ctx->num_cu, st);
-    else if (watershed->dtype == RA_BF16)
-        rc = dispatch_scores<BF16, 64>(G, paged, grid, tab_bytes, st, a);
-    else
-        rc = D == 128 ? dispatch_scores<F32, 128>(G, paged, grid, tab_bytes, st, a)
-                      : dispatch_scores<F32, 64>(G, paged, grid, tab_bytes, st, a);
+    if (many_rows) launch_scores_plan(a, st);
+    {
+        KernelTimer timer(ctx, st);
+        if (many_rows)
+            rc = launch_scores_prefill_mfma(a, paged, ctx->num_cu, st);
+        else if (mfma)
+            rc = launch_scores_mfma(a, paged, ctx->num_cu, st);
+        else if (watershed->dtype == RA_BF16)
+            rc = dispatch_scores<BF16, 64>(G, paged, grid, tab_bytes, st, a);
+        else
+            rc = D == 128 ? dispatch_scores<F32, 128>(G, paged, grid, tab_bytes, st, a)
+                          : dispatch_scores<F32, 64>(G, paged, grid, tab_bytes, st, a);
+    }
     if (rc) return rc;
 
     FinishArgs f;

@@ -31,6 +31,7 @@ __device__ __forceinline__ int cur_visible(int cur_len, int q_len, int i) {
 }
 
 // bf16, d = 128, Hq/Hkv <= 16: matrix-core streaming kernels, for up to 16 query rows per KV head and for more.
+void launch_scores_plan(const ScoreArgs& a, hipStream_t st);  // segment tables of the many-row kernel; run it first
 int launch_scores_prefill_mfma(const ScoreArgs& a, bool paged, int num_cu, hipStream_t st);
 int launch_scores_mfma(const ScoreArgs& a, bool paged, int num_cu, hipStream_t st);
 

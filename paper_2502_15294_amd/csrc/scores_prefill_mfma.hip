@@ -335,6 +335,11 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
 
 RA_TS_DEFINE_READER(ra_debug_read_ts_scores_prefill)
 
+void launch_scores_plan(const ScoreArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(scores_plan_kernel, dim3(a.view.B), dim3(256), (size_t)(a.view.R_max + 2) * 2 * sizeof(int), st, a,
+                       const_cast<char*>(a.plan));
+}
+
 int launch_scores_prefill_mfma(const ScoreArgs& a, bool paged, int num_cu, hipStream_t st) {
     const int G = a.Hq / a.view.Hkv;
     if (G > 16) return fail(RA_ERR_UNSUPPORTED, "round_scores: Hq / Hkv = %d exceeds 16", G);
@@ -343,8 +348,6 @@ int launch_scores_prefill_mfma(const ScoreArgs& a, bool paged, int num_cu, hipSt
     const int rows_total = a.q_len * G;
     const int n_rowblocks = (rows_total + kRowsPerItemS - 1) / kRowsPerItemS;
     const size_t smem = align_up(SlotTable::bytes(a.view.R_max + 1), 16) + 2 * kKTileBytes;
-    hipLaunchKernelGGL(scores_plan_kernel, dim3(B), dim3(256), (size_t)(a.view.R_max + 2) * 2 * sizeof(int), st, a,
-                       const_cast<char*>(a.plan));
     long long max_pieces = (long long)B + (long long)B * a.n_chunks_max * kTilesPerChunk / a.min_units;
     if (max_pieces > (long long)B * a.S) max_pieces = (long long)B * a.S;
     long long grid = (long long)kWorkgroupsPerCuS * num_cu;

@@ -438,3 +438,30 @@ def test_understated_max_tokens_is_reported_as_nan_scores():
     assert np.isnan(Sq.cpu().numpy()).all()
     engq.close()
     eng.close()
+
+
+def test_kernel_timing_hooks():
+    """The measurement aid brackets the streaming kernel of a call: its time is positive and below the whole call's."""
+    w = make_workload("cfg2", B=2, R=6, length=("uniform", 200, 600))
+    eng = Engine(w)
+    view = device_view(w, 0, with_v=False)
+    q = to_device(w.q(0), w.dtype)
+    with pytest.raises(ra.RaError):
+        ra.ra_profile_last_ms(eng.ctx)            # not enabled
+    ra.ra_profile_kernels(eng.ctx, True)
+    with pytest.raises(ra.RaError):
+        ra.ra_profile_last_ms(eng.ctx)            # no call yet
+    ra.ra_round_scores(eng.ctx, q, view, scale=w.scale)          # warm-up
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    _, S1 = ra.ra_round_scores(eng.ctx, q, view, scale=w.scale)
+    e1.record()
+    k_ms = ra.ra_profile_last_ms(eng.ctx)
+    torch.cuda.synchronize()
+    assert 0.0 < k_ms <= e0.elapsed_time(e1)
+    ra.ra_profile_kernels(eng.ctx, False)
+    _, S2 = ra.ra_round_scores(eng.ctx, q, view, scale=w.scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(S1.cpu().numpy(), S2.cpu().numpy())
+    eng.close()
