@@ -167,16 +167,16 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
     }
 }
 
+// Reductions over the 64 lanes of a wavefront, every lane ends with the result: DPP inside the 16-lane rows,
+// then lane-permute swaps across the rows; no LDS traffic.
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    v = vmax(v, dpp_mov<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = vmax(v, dpp_mov<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = vmax(v, dpp_mov<0x141>(v));  // row_half_mirror
+    v = vmax(v, dpp_mov<0x140>(v));  // row_mirror
+    return xrow_max4(v);
 }
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
+__device__ __forceinline__ float wave_sum(float v) { return xrow_sum4(row16_sum(v)); }
 // log-sum-exp of x[lo .. hi)
 __device__ __forceinline__ float lse_range(const float* x, int lo, int hi) {
     float mx = -__builtin_inff();
@@ -210,8 +210,19 @@ __global__ __launch_bounds__(W * 64) void scores_finish_kernel(FinishArgs a, boo
     float* rowbuf = hs + W * a.R_max;                   // [W][n_chunks_max] if staged
     const int b = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // The first row this wave needs is fetched (whole, whatever the number of chunks turns out to be) while the
+    // round lengths are on their way: one memory round trip less on the path of this latency-bound kernel.
+    const bool prefetched = stage_rows && wave < a.Hq;
+    if (prefetched) {
+        const float* row = a.part + ((size_t)b * a.Hq + wave) * a.q_len * a.n_chunks_max;
+        float* mybuf = rowbuf + (size_t)wave * a.n_chunks_max;
+        for (int c = lane; c < a.n_chunks_max; c += 64) mybuf[c] = row[c];
+    }
     const int R = min(max(a.n_rounds[b], 0), a.R_max);
-    for (int r = tid; r < R; r += W * 64) cum[r] = chunks_of(max(a.seg_len[(size_t)b * a.R_max + r], 0), a.chunk_tokens);
+    for (int r = tid; r < a.R_max; r += W * 64) {
+        const int len = a.seg_len[(size_t)b * a.R_max + r];  // (loaded whether or not r < R: no wait for R)
+        if (r < R) cum[r] = chunks_of(max(len, 0), a.chunk_tokens);
+    }
     exclusive_scan_units(cum, R);
     const int hist_chunks = R > 0 ? cum[R] : 0;
     const bool overflow = hist_chunks + (a.has_cur ? chunks_of(a.cur_len, a.chunk_tokens) : 0) > a.n_chunks_max;
@@ -228,8 +239,9 @@ __global__ __launch_bounds__(W * 64) void scores_finish_kernel(FinishArgs a, boo
             if (stage_rows) {  // one coalesced pass over the row instead of dependent loads per round
                 float* mybuf = rowbuf + (size_t)(tid >> 6) * a.n_chunks_max;
                 __builtin_amdgcn_wave_barrier();
-                for (int c = lane; c < hist_chunks + (a.has_cur ? chunks_of(a.cur_len, a.chunk_tokens) : 0); c += 64)
-                    mybuf[c] = row[c];
+                if (!(prefetched && h == wave && i == 0))
+                    for (int c = lane; c < hist_chunks + (a.has_cur ? chunks_of(a.cur_len, a.chunk_tokens) : 0); c += 64)
+                        mybuf[c] = row[c];
                 __builtin_amdgcn_wave_barrier();  // same wave: LDS operations complete in program order
                 row = mybuf;
             }
