@@ -61,6 +61,9 @@ def parse():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three device-to-device copies of 1 GiB, so that a hardware-counter run of this "
                          "command contains a copy kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--sweep", action="store_true",
+                    help="cfg5 only: measure the key bias alpha in {0.5, 1, 2, 4} x lambda in {0, 0.5, 1} (kept fraction "
+                         "from about 5 to 60 %%) and print one JSON line with a `sweep` table instead of the usual line")
     ap.add_argument("--cpu-baseline-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     ap.add_argument("--stage-order", default="round", choices=["round", "layer"], help="cfg4: order of the host-to-device copies")
     return ap.parse_args()
@@ -135,110 +138,114 @@ def bench_step(name, steps, warmup, lam, alpha, replicas):
     hist_tokens = sum(w.total_tokens(b) for b in range(w.B))
     k_bytes_tok = w.Hkv * w.d * eb
 
-    params = ra.make_select_params(lam=lam)
-    P = torch.empty((w.B, w.Hq, view0.R_max), dtype=torch.float32, device="cuda")
-    S = torch.empty((w.B, view0.R_max), dtype=torch.float32, device="cuda")
-    sel_idx = torch.empty((w.B, view0.R_max), dtype=torch.int32, device="cuda")
-    n_sel = torch.empty((w.B,), dtype=torch.int32, device="cuda")
-    out = torch.empty((w.B, w.q_len, w.Hq, w.d) if prefill else (w.B, w.Hq, w.d), dtype=torch.float32, device="cuda")
-    lse = torch.empty((w.B, w.q_len, w.Hq) if prefill else (w.B, w.Hq), dtype=torch.float32, device="cuda")
+    def measure(lam):
+        params = ra.make_select_params(lam=lam)
+        P = torch.empty((w.B, w.Hq, view0.R_max), dtype=torch.float32, device="cuda")
+        S = torch.empty((w.B, view0.R_max), dtype=torch.float32, device="cuda")
+        sel_idx = torch.empty((w.B, view0.R_max), dtype=torch.int32, device="cuda")
+        n_sel = torch.empty((w.B,), dtype=torch.int32, device="cuda")
+        out = torch.empty((w.B, w.q_len, w.Hq, w.d) if prefill else (w.B, w.Hq, w.d), dtype=torch.float32, device="cuda")
+        lse = torch.empty((w.B, w.q_len, w.Hq) if prefill else (w.B, w.Hq), dtype=torch.float32, device="cuda")
 
-    def attend(v1):
-        if prefill:
-            ra.ra_round_sparse_attn_prefill(eng.ctx, q1, v1, sel_idx, n_sel, ck1, cv1, scale=w.scale, out=out, lse=lse)
-        else:
-            ra.ra_round_sparse_attn_decode(eng.ctx, q1, v1, sel_idx, n_sel, ck1, cv1, cl1, scale=w.scale, out=out, lse=lse)
+        def attend(v1):
+            if prefill:
+                ra.ra_round_sparse_attn_prefill(eng.ctx, q1, v1, sel_idx, n_sel, ck1, cv1, scale=w.scale, out=out, lse=lse)
+            else:
+                ra.ra_round_sparse_attn_decode(eng.ctx, q1, v1, sel_idx, n_sel, ck1, cv1, cl1, scale=w.scale, out=out, lse=lse)
 
-    def step(v0, v1, ev=None):
-        if ev: ev[0].record()
-        ra.ra_round_scores(eng.ctx, q0, v0, ck0, scale=w.scale, scores_head=P, scores=S)
-        if ev: ev[1].record()
-        ra.ra_select_rounds(eng.ctx, S, v0.n_rounds, params, sel_idx=sel_idx, n_sel=n_sel)
-        if ev: ev[2].record()
-        attend(v1)
-        if ev: ev[3].record()
+        def step(v0, v1, ev=None):
+            if ev: ev[0].record()
+            ra.ra_round_scores(eng.ctx, q0, v0, ck0, scale=w.scale, scores_head=P, scores=S)
+            if ev: ev[1].record()
+            ra.ra_select_rounds(eng.ctx, S, v0.n_rounds, params, sel_idx=sel_idx, n_sel=n_sel)
+            if ev: ev[2].record()
+            attend(v1)
+            if ev: ev[3].record()
 
-    step(view0, view1)
-    torch.cuda.synchronize()
-    n_sel_h, sel_h = n_sel.cpu().numpy(), sel_idx.cpu().numpy()
-    sel_tokens = int(sum(int(w.lens[b][sel_h[b, :n_sel_h[b]]].sum()) for b in range(w.B)))
-    step_bytes = hist_tokens * k_bytes_tok + sel_tokens * 2 * k_bytes_tok
-    n_rep = replicas or int(max(1, min(8, -(-CACHE_DEFEAT_BYTES // max(step_bytes, 1)))))
+        step(view0, view1)
+        torch.cuda.synchronize()
+        n_sel_h, sel_h = n_sel.cpu().numpy(), sel_idx.cpu().numpy()
+        sel_tokens = int(sum(int(w.lens[b][sel_h[b, :n_sel_h[b]]].sum()) for b in range(w.B)))
+        step_bytes = hist_tokens * k_bytes_tok + sel_tokens * 2 * k_bytes_tok
+        n_rep = replicas or int(max(1, min(8, -(-CACHE_DEFEAT_BYTES // max(step_bytes, 1)))))
 
-    def clone_view(v):
-        k, vv, seg_off, seg_len, n_rounds, bt, seg_off_v = v.tensors
-        return ra.KVView(k.clone(), None if vv is None else vv.clone(), seg_off, seg_len, n_rounds, v.Hkv, v.d,
-                         v.c.max_tokens, block_table=bt, block_size=v.c.block_size, seg_off_v=seg_off_v)
+        def clone_view(v):
+            k, vv, seg_off, seg_len, n_rounds, bt, seg_off_v = v.tensors
+            return ra.KVView(k.clone(), None if vv is None else vv.clone(), seg_off, seg_len, n_rounds, v.Hkv, v.d,
+                             v.c.max_tokens, block_table=bt, block_size=v.c.block_size, seg_off_v=seg_off_v)
 
-    reps = [(view0, view1)] + [(clone_view(view0), clone_view(view1)) for _ in range(n_rep - 1)]
-    for i in range(warmup):
-        step(*reps[i % n_rep])
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        step(*reps[i % n_rep])
-    torch.cuda.synchronize()
-    total = time.perf_counter() - t0
+        reps = [(view0, view1)] + [(clone_view(view0), clone_view(view1)) for _ in range(n_rep - 1)]
+        for i in range(warmup):
+            step(*reps[i % n_rep])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(*reps[i % n_rep])
+        torch.cuda.synchronize()
+        total = time.perf_counter() - t0
 
-    # Per-call durations: a second pass with events between the calls (recording them costs about 3 us each,
-    # so they stay out of the timed region above).
-    n_ev = min(steps, 100)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n_ev)]
-    for i in range(n_ev):
-        step(*reps[i % n_rep], evs[i])
-    torch.cuda.synchronize()
-    ms = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evs])
-    avg_ms, med_ms = ms.mean(axis=0), np.median(ms, axis=0)
+        # Per-call durations: a second pass with events between the calls (recording them costs about 3 us each,
+        # so they stay out of the timed region above).
+        n_ev = min(steps, 100)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n_ev)]
+        for i in range(n_ev):
+            step(*reps[i % n_rep], evs[i])
+        torch.cuda.synchronize()
+        ms = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evs])
+        avg_ms, med_ms = ms.mean(axis=0), np.median(ms, axis=0)
 
-    # Duration of the streaming kernel inside the two big calls (the library brackets it with HIP events on
-    # request); separate pass, because those events cost a few microseconds per call.
-    ra.ra_profile_kernels(eng.ctx, True)
-    kern_ms = [[], []]
-    for i in range(min(steps, 50)):
-        v0, v1 = reps[i % n_rep]
-        ra.ra_round_scores(eng.ctx, q0, v0, ck0, scale=w.scale, scores_head=P, scores=S)
-        kern_ms[0].append(ra.ra_profile_last_ms(eng.ctx))
-        ra.ra_select_rounds(eng.ctx, S, v0.n_rounds, params, sel_idx=sel_idx, n_sel=n_sel)
-        attend(v1)
-        kern_ms[1].append(ra.ra_profile_last_ms(eng.ctx))
-    ra.ra_profile_kernels(eng.ctx, False)
-    many_rows = w.q_len * (w.Hq // w.Hkv) > 16
-    mfma = w.dtype == "bf16" and w.d == 128
-    scores_kernel = ("scores_prefill_mfma_kernel" if many_rows else "scores_mfma_kernel") if mfma else "scores_stream_kernel"
-    attn_kernel = (("attn_prefill_mfma_kernel" if w.q_len * (w.Hq // w.Hkv) > 32 else "attn_mfma_kernel") if mfma
-                   else "decode_generic_kernel")
+        # Duration of the streaming kernel inside the two big calls (the library brackets it with HIP events on
+        # request); separate pass, because those events cost a few microseconds per call.
+        ra.ra_profile_kernels(eng.ctx, True)
+        kern_ms = [[], []]
+        for i in range(min(steps, 50)):
+            v0, v1 = reps[i % n_rep]
+            ra.ra_round_scores(eng.ctx, q0, v0, ck0, scale=w.scale, scores_head=P, scores=S)
+            kern_ms[0].append(ra.ra_profile_last_ms(eng.ctx))
+            ra.ra_select_rounds(eng.ctx, S, v0.n_rounds, params, sel_idx=sel_idx, n_sel=n_sel)
+            attend(v1)
+            kern_ms[1].append(ra.ra_profile_last_ms(eng.ctx))
+        ra.ra_profile_kernels(eng.ctx, False)
+        many_rows = w.q_len * (w.Hq // w.Hkv) > 16
+        mfma = w.dtype == "bf16" and w.d == 128
+        scores_kernel = ("scores_prefill_mfma_kernel" if many_rows else "scores_mfma_kernel") if mfma else "scores_stream_kernel"
+        attn_kernel = (("attn_prefill_mfma_kernel" if w.q_len * (w.Hq // w.Hkv) > 32 else "attn_mfma_kernel") if mfma
+                       else "decode_generic_kernel")
 
-    q_rows = w.B * w.q_len * w.Hq
-    attn_name = "ra_round_sparse_attn_prefill" if prefill else "ra_round_sparse_attn_decode"
-    groups = {
-        "ra_round_scores": {"ms": float(avg_ms[0]), "median_ms": float(med_ms[0]),
-                            "bytes": int(hist_tokens * k_bytes_tok + q_rows * w.d * eb),
-                            "kernel": scores_kernel, "kernel_ms": float(np.mean(kern_ms[0]))},
-        "ra_select_rounds": {"ms": float(avg_ms[1]), "median_ms": float(med_ms[1]), "bytes": int(w.B * view0.R_max * 8),
-                             "kernel": "select_kernel", "kernel_ms": float(avg_ms[1])},
-        attn_name: {"ms": float(avg_ms[2]), "median_ms": float(med_ms[2]),
-                    "bytes": int((sel_tokens + w.B * w.cur_len) * 2 * k_bytes_tok + q_rows * w.d * (eb + 4)),
-                    "kernel": attn_kernel, "kernel_ms": float(np.mean(kern_ms[1]))},
-    }
-    for g in groups.values():
-        g["GB/s"] = g["bytes"] / (g["ms"] * 1e-3) / 1e9 if g["ms"] > 0 else None
-    dom = max(groups, key=lambda k: groups[k]["ms"])
-    res = {
-        "value": w.B * w.q_len * steps / total,
-        "ms_per_step": total / steps * 1e3,
-        "dtype": w.dtype,
-        "config": {"workload": f"{name}: {WORKLOADS[name]}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d,
-                   "q_len": w.q_len, "history_tokens": hist_tokens, "selected_tokens": sel_tokens,
-                   "kept_token_fraction": sel_tokens / max(hist_tokens, 1),
-                   "selected_rounds": [int(x) for x in n_sel_h], "lambda": lam, "alpha": w.alpha,
-                   "replicas_rotated": n_rep,
-                   "step": f"ra_round_scores -> ra_select_rounds -> {attn_name}"},
-        "roofline": _roofline(groups, dom, prefill, w, hist_tokens, sel_tokens),
-        "kernel_groups": groups,
-        "input_generation_s": t_gen,
-    }
+        q_rows = w.B * w.q_len * w.Hq
+        attn_name = "ra_round_sparse_attn_prefill" if prefill else "ra_round_sparse_attn_decode"
+        groups = {
+            "ra_round_scores": {"ms": float(avg_ms[0]), "median_ms": float(med_ms[0]),
+                                "bytes": int(hist_tokens * k_bytes_tok + q_rows * w.d * eb),
+                                "kernel": scores_kernel, "kernel_ms": float(np.mean(kern_ms[0]))},
+            "ra_select_rounds": {"ms": float(avg_ms[1]), "median_ms": float(med_ms[1]), "bytes": int(w.B * view0.R_max * 8),
+                                 "kernel": "select_kernel", "kernel_ms": float(avg_ms[1])},
+            attn_name: {"ms": float(avg_ms[2]), "median_ms": float(med_ms[2]),
+                        "bytes": int((sel_tokens + w.B * w.cur_len) * 2 * k_bytes_tok + q_rows * w.d * (eb + 4)),
+                        "kernel": attn_kernel, "kernel_ms": float(np.mean(kern_ms[1]))},
+        }
+        for g in groups.values():
+            g["GB/s"] = g["bytes"] / (g["ms"] * 1e-3) / 1e9 if g["ms"] > 0 else None
+        dom = max(groups, key=lambda k: groups[k]["ms"])
+        res = {
+            "value": w.B * w.q_len * steps / total,
+            "ms_per_step": total / steps * 1e3,
+            "dtype": w.dtype,
+            "config": {"workload": f"{name}: {WORKLOADS[name]}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d,
+                       "q_len": w.q_len, "history_tokens": hist_tokens, "selected_tokens": sel_tokens,
+                       "kept_token_fraction": sel_tokens / max(hist_tokens, 1),
+                       "selected_rounds": [int(x) for x in n_sel_h], "lambda": lam, "alpha": w.alpha,
+                       "replicas_rotated": n_rep,
+                       "step": f"ra_round_scores -> ra_select_rounds -> {attn_name}"},
+            "roofline": _roofline(groups, dom, prefill, w, hist_tokens, sel_tokens),
+            "kernel_groups": groups,
+            "input_generation_s": t_gen,
+        }
+        return res
+
+    results = [measure(l) for l in (lam if isinstance(lam, (list, tuple)) else [lam])]
     eng.close()
-    return res, w
+    return (results if isinstance(lam, (list, tuple)) else results[0]), w
 
 
 def bench_long_context(steps, warmup, lam, order_name):
@@ -416,6 +423,22 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.sweep:
+        table = []
+        for alpha in (0.5, 1.0, 2.0, 4.0):
+            many, _ = bench_step("cfg5", 10, 2, [0.0, 0.5, 1.0], alpha, 1)
+            for r in many:
+                g = r["kernel_groups"]
+                table.append({"alpha": alpha, "lambda": r["config"]["lambda"],
+                              "kept_token_fraction": r["config"]["kept_token_fraction"],
+                              "ms_per_step": r["ms_per_step"], "tokens/s": r["value"],
+                              "decode_kernel_ms": g["ra_round_sparse_attn_decode"]["kernel_ms"],
+                              "decode_kernel_GB/s": g["ra_round_sparse_attn_decode"]["bytes"] /
+                              g["ra_round_sparse_attn_decode"]["kernel_ms"] / 1e6,
+                              "scores_kernel_GB/s": g["ra_round_scores"]["bytes"] / g["ra_round_scores"]["kernel_ms"] / 1e6})
+        print(json.dumps({"metric": METRIC, "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+                          "config": {"workload": f"cfg5: {WORKLOADS['cfg5']}", "steps": 10, "warmup": 2}, "sweep": table}))
+        return
     if args.workload == "cfg4":
         res, w = bench_long_context(args.steps, args.warmup, args.lam, args.stage_order)
     else:

@@ -276,6 +276,13 @@ PREFILL_CASES = {
     "q33_paged_g8": (dict(B=2, R=5, q_len=33, cur_len=40, Hq=64, block_size=16, length=("uniform", 5, 200)),
                      [[0, 1, 4], [2]]),
     "q128_long": (dict(B=1, R=12, q_len=128, cur_len=128, length=("lognormal", 400.0, 0.8, 6000)), [[1, 4, 7, 8, 11]]),
+    # ragged rounds around the 16 / 32-token tile sizes, empty rounds (selected too), uneven round counts
+    "q20_ragged_rounds": (dict(B=3, q_len=20, cur_len=23, lens=[[5, 16, 17, 0, 33, 1, 250], [64, 3, 0, 0, 15, 48, 31], [96]]),
+                          [[0, 1, 2, 3, 4, 5, 6], [2, 3, 5], [0]]),
+    "q20_ragged_rounds_paged_g8": (dict(B=2, q_len=20, cur_len=20, Hq=64, block_size=16,
+                                        lens=[[300, 17, 16, 1, 999, 50], [31, 32, 33, 0, 64, 5]]), [[0, 3, 4], [0, 1, 2, 3, 5]]),
+    "q24_many_short_rounds": (dict(B=2, R=300, q_len=24, cur_len=24, length=("uniform", 1, 40)),
+                              [list(range(0, 300, 3)), list(range(5, 300, 7))]),
 }
 
 
@@ -323,6 +330,11 @@ SCORE_PREFILL_CASES = {
     "q100_two_rowblocks": dict(B=1, R=7, q_len=100, cur_len=100, length=("uniform", 20, 400)),
     "q24_history_only_paged_g8": dict(B=2, R=5, q_len=24, cur_len=0, Hq=64, block_size=16, length=("uniform", 5, 300)),
     "q300_long_question": dict(B=1, R=4, q_len=300, cur_len=300, length=("uniform", 100, 700)),
+    "q20_ragged_rounds": dict(B=3, q_len=20, cur_len=23, lens=[[5, 16, 17, 0, 33, 1, 250], [64, 3, 0, 0, 15, 48, 31], [96]]),
+    "q20_ragged_rounds_paged_g8": dict(B=2, q_len=20, cur_len=0, Hq=64, block_size=16,
+                                       lens=[[300, 17, 16, 1, 999, 50], [31, 32, 33, 0, 64, 5]]),
+    "q24_many_short_rounds": dict(B=2, R=300, q_len=24, cur_len=24, length=("uniform", 1, 40)),
+    "q20_chunk_boundaries": dict(B=1, q_len=20, cur_len=300, lens=[[256, 257, 255, 512, 1, 513, 32, 31]]),
 }
 
 
@@ -338,7 +350,9 @@ def test_round_scores_prefill_shape_match_oracle(name):
     P, S = P.cpu().numpy(), S.cpu().numpy()
     for b in range(w.B):
         rP, rS = pipeline.scores_for_sequence(w, b)
-        assert np.abs(P[b] - rP).max() < SCORE_TOL and np.abs(S[b] - rS).max() < SCORE_TOL
+        R = w.n_rounds(b)
+        assert np.abs(P[b, :, :R] - rP).max() < SCORE_TOL and np.abs(S[b, :R] - rS).max() < SCORE_TOL
+        assert np.all(P[b, :, R:] == 0) and np.all(S[b, R:] == 0)
         assert np.abs(P[b].sum(axis=1) - 1).max() < SCORE_TOL
     eng.close()
 
