@@ -479,3 +479,39 @@ def test_kernel_timing_hooks():
     torch.cuda.synchronize()
     assert np.array_equal(S1.cpu().numpy(), S2.cpu().numpy())
     eng.close()
+
+
+def test_largest_round_count_decode_and_prefill():
+    """R_max = 1024 rounds (the largest the entry points accept): the segment tables are at their biggest."""
+    w = make_workload("cfg2", B=2, R=1024, length=("uniform", 1, 6))
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0, with_v=False), device_view(w, 1)
+    P, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, scale=w.scale)
+    sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, v0.n_rounds, ra.make_select_params(lam=0.0))
+    out, _ = ra.ra_round_sparse_attn_decode(eng.ctx, to_device(w.q(1)[:, 0], w.dtype), v1, sel_idx, n_sel, scale=w.scale)
+    torch.cuda.synchronize()
+    S, sel_idx, n_sel, out = S.cpu().numpy(), sel_idx.cpu().numpy(), n_sel.cpu().numpy(), out.cpu().numpy()
+    for b in range(w.B):
+        _, rS = pipeline.scores_for_sequence(w, b)
+        assert np.abs(S[b] - rS).max() < SCORE_TOL
+        sel = sel_idx[b, :n_sel[b]].tolist()
+        assert sel == _oracle_select_on(S[b], 1024, dict(strategy=ora.ADAPTIVE, lam=0.0))
+        ref_o, _ = pipeline.attention_for_sequence(w, b, 1, sel)
+        assert ora.row_error(out[b], ref_o[0]) < STREAM_TOL
+    eng.close()
+
+    w = make_workload("cfg3", B=1, R=1024, q_len=40, cur_len=40, length=("uniform", 1, 6))
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0, with_v=False), device_view(w, 1)
+    P, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, to_device(w.cur_k(0), w.dtype), scale=w.scale)
+    sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, v0.n_rounds, ra.make_select_params(lam=0.0))
+    out, _ = ra.ra_round_sparse_attn_prefill(eng.ctx, to_device(w.q(1), w.dtype), v1, sel_idx, n_sel,
+                                             to_device(w.cur_k(1), w.dtype), to_device(w.cur_v(1), w.dtype), scale=w.scale)
+    torch.cuda.synchronize()
+    S, sel_idx, n_sel, out = S.cpu().numpy(), sel_idx.cpu().numpy(), n_sel.cpu().numpy(), out.cpu().numpy()
+    _, rS = pipeline.scores_for_sequence(w, 0)
+    assert np.abs(S[0] - rS).max() < SCORE_TOL
+    sel = sel_idx[0, :n_sel[0]].tolist()
+    ref_o, _ = pipeline.attention_for_sequence(w, 0, 1, sel)
+    assert ora.row_error(out[0], ref_o) < STREAM_TOL
+    eng.close()
