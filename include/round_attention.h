@@ -124,8 +124,8 @@ int ra_workspace_bytes(const ra_problem* p, size_t* bytes_out);
 int ra_set_workspace(ra_ctx* ctx, void* device_ptr, size_t bytes);
 
 /*
- * Measurement aid (Sec. 4.5 / App. D report the time of the attention and scoring steps; this is how a
- * benchmark gets the duration of the kernel that dominates a call, without the small kernels around it).
+ * Measurement aid (Sec. 4.3 and App. C break the latency down into the selection and attention steps; this is
+ * how a benchmark gets the duration of the kernel that dominates a call, without the small kernels around it).
  * While enabled, ra_round_scores, ra_round_sparse_attn_decode and ra_round_sparse_attn_prefill record one
  * HIP event on the caller's stream before and one after their streaming kernel (the pass over the keys, or
  * over the selected keys and values).  ra_profile_last_ms waits for the later event of the most recent such

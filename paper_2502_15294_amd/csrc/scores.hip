@@ -1,16 +1,18 @@
-// Round scores at the watershed layer (paper Sec. 3.1, Eq. 1 and the normalisation after it).
+// Round scores at the watershed layer (paper Sec. 3.1, Eq. 1 and the normalisation after it): the generic
+// streaming kernel, the finishing kernels and the entry point.
 //
-// Two kernels.
 // (1) A streaming pass over the watershed layer's keys, HBM-bandwidth bound like decode attention but
-//     without values.  Every round is cut into chunks of 256 tokens; workgroup (c, g, b*q_len+i) owns
-//     chunk c of sequence b for KV head g and query token i.  Each of its four waves issues the loads
-//     of its four 16-token units up front (16 KB in flight per workgroup), then reduces the logits of
-//     the chunk to one log-sum-exp per query head.  Equal-sized work items keep long rounds from
-//     becoming the tail of the launch.
-// (2) A small finishing kernel turns the per-chunk log-sum-exps into Eq. 1: per round the
-//     log-sum-exp over its chunks, per query token the softmax normaliser over all rounds and the
-//     visible part of the current round, the probability mass of every history round summed over the
-//     query tokens, normalisation over history rounds, mean over query heads.
+//     without values, leaves one log-sum-exp per (query row, 256-token chunk of a round).  For bf16 / d = 128
+//     it runs on the matrix cores (scores_mfma.hip, scores_prefill_mfma.hip); the kernel below serves fp32 and
+//     d = 64: workgroup (c, g, b*q_len+i) owns chunk c of sequence b for KV head g and query token i, each of
+//     its four waves issues the loads of its four 16-token units up front (16 KB in flight per workgroup), then
+//     reduces the logits of the chunk to one log-sum-exp per query head.  Equal-sized work items keep long
+//     rounds from becoming the tail of the launch.
+// (2) Finishing kernels turn the per-chunk log-sum-exps into Eq. 1: per round the log-sum-exp over its chunks,
+//     per query token the softmax normaliser over all rounds and the visible part of the current round, the
+//     probability mass of every history round summed over the query tokens, normalisation over history
+//     rounds, mean over query heads.  One kernel does all of it for a single query token; for several query
+//     tokens the work of a head is split over several workgroups and a second small kernel normalises.
 #include "scores_common.hpp"
 #include "stream_kv.hpp"
 
