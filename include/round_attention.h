@@ -126,12 +126,12 @@ int ra_set_workspace(ra_ctx* ctx, void* device_ptr, size_t bytes);
 /*
  * Measurement aid (Sec. 4.3 and App. C break the latency down into the selection and attention steps; this is
  * how a benchmark gets the duration of the kernel that dominates a call, without the small kernels around it).
- * While enabled, ra_round_scores, ra_round_sparse_attn_decode and ra_round_sparse_attn_prefill record one
- * HIP event on the caller's stream before and one after their streaming kernel (the pass over the keys, or
- * over the selected keys and values).  ra_profile_last_ms waits for the later event of the most recent such
- * call and returns the milliseconds between the two; RA_ERR_STATE if no call was made since enabling.
- * The events cost a few microseconds per call: leave this off when timing whole steps.  The first enable
- * creates the two events (the only allocation); not for use under stream capture.
+ * While enabled, ra_round_scores, ra_round_sparse_attn_decode and ra_round_sparse_attn_prefill attach two HIP
+ * events to the launch of their streaming kernel (the pass over the keys, or over the selected keys and
+ * values), which then carry that kernel's own start and end time stamps.  ra_profile_last_ms waits for the end
+ * event of the most recent such call and returns the milliseconds between the two; RA_ERR_STATE if no call was
+ * made since enabling.  Leave this off when timing whole steps.  The first enable creates the two events (the
+ * only allocation); not for use under stream capture.
  */
 int ra_profile_kernels(ra_ctx* ctx, int enable);
 int ra_profile_last_ms(ra_ctx* ctx, float* ms_out);

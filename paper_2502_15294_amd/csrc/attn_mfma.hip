@@ -336,9 +336,9 @@ int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) 
     if (grid < 1) grid = 1;
     const size_t smem = tab_bytes + (128 + 4 * 16 * 128) * sizeof(float);
     if (paged)
-        hipLaunchKernelGGL((attn_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        RA_LAUNCH_TIMED((attn_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
     else
-        hipLaunchKernelGGL((attn_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        RA_LAUNCH_TIMED((attn_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
     return RA_OK;
 }
 

@@ -390,9 +390,9 @@ int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStrea
     if (grid > max_pieces * Hkv * n_rowblocks) grid = max_pieces * Hkv * n_rowblocks;
     if (grid < 1) grid = 1;
     if (paged)
-        hipLaunchKernelGGL((attn_prefill_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
     else
-        hipLaunchKernelGGL((attn_prefill_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
     return RA_OK;
 }
 

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -39,21 +40,27 @@ struct ra_ctx {
 };
 
 namespace ra {
-// Brackets the launches made during its lifetime with the context's two events when profiling is on.
+// While a KernelTimer is alive on a profiling context, RA_LAUNCH_TIMED hands the context's two events to the
+// launch itself, so that they carry the kernel's own start and end time stamps (no extra packets on the stream).
+extern thread_local ra_ctx* g_timed_ctx;
 struct KernelTimer {
-    ra_ctx* c;
-    hipStream_t st;
-    KernelTimer(ra_ctx* ctx, hipStream_t stream) : c(ctx), st(stream) {
-        if (c->profile) (void)hipEventRecord(c->ev_start, st);
-    }
-    ~KernelTimer() {
-        if (c->profile) {
-            (void)hipEventRecord(c->ev_stop, st);
-            c->timed = true;
-        }
-    }
+    ra_ctx* prev;
+    KernelTimer(ra_ctx* ctx, hipStream_t) : prev(g_timed_ctx) { g_timed_ctx = ctx->profile ? ctx : nullptr; }
+    ~KernelTimer() { g_timed_ctx = prev; }
 };
 }  // namespace ra
+
+// Launch of a streaming kernel (the one ra_profile_last_ms reports).
+#define RA_LAUNCH_TIMED(kernel, grid, block, smem, st, ...)                                                      \
+    do {                                                                                                         \
+        if (::ra::g_timed_ctx) {                                                                                 \
+            hipExtLaunchKernelGGL(kernel, grid, block, (std::uint32_t)(smem), st, ::ra::g_timed_ctx->ev_start,    \
+                                  ::ra::g_timed_ctx->ev_stop, 0, __VA_ARGS__);                                   \
+            ::ra::g_timed_ctx->timed = true;                                                                     \
+        } else {                                                                                                 \
+            hipLaunchKernelGGL(kernel, grid, block, smem, st, __VA_ARGS__);                                      \
+        }                                                                                                        \
+    } while (0)
 
 namespace ra {
 

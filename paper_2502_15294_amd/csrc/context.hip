@@ -72,6 +72,8 @@ int decode_splits(int num_cu, int B, int Hkv, int64_t max_tokens) {
     return (int)s;
 }
 
+thread_local ra_ctx* g_timed_ctx = nullptr;
+
 }  // namespace ra
 
 using namespace ra;

@@ -340,9 +340,9 @@ void launch_combine(const AttnArgs& a, int D, size_t rows, hipStream_t st) {
 template <typename T, int D, int G>
 static void launch_generic(bool paged, dim3 grid, size_t smem, hipStream_t st, const AttnArgs& a) {
     if (paged)
-        hipLaunchKernelGGL((decode_generic_kernel<T, D, G, true>), grid, dim3(256), smem, st, a);
+        RA_LAUNCH_TIMED((decode_generic_kernel<T, D, G, true>), grid, dim3(256), smem, st, a);
     else
-        hipLaunchKernelGGL((decode_generic_kernel<T, D, G, false>), grid, dim3(256), smem, st, a);
+        RA_LAUNCH_TIMED((decode_generic_kernel<T, D, G, false>), grid, dim3(256), smem, st, a);
 }
 
 template <typename T, int D>

@@ -423,9 +423,9 @@ __global__ __launch_bounds__(kHeadsWaves * 64) void scores_heads_kernel(const fl
 template <typename T, int D, int G>
 static void launch_scores(bool paged, dim3 grid, size_t smem, hipStream_t st, const ScoreArgs& a) {
     if (paged)
-        hipLaunchKernelGGL((scores_stream_kernel<T, D, G, true>), grid, dim3(256), smem, st, a);
+        RA_LAUNCH_TIMED((scores_stream_kernel<T, D, G, true>), grid, dim3(256), smem, st, a);
     else
-        hipLaunchKernelGGL((scores_stream_kernel<T, D, G, false>), grid, dim3(256), smem, st, a);
+        RA_LAUNCH_TIMED((scores_stream_kernel<T, D, G, false>), grid, dim3(256), smem, st, a);
 }
 
 template <typename T, int D>

@@ -200,9 +200,9 @@ int launch_scores_mfma(const ScoreArgs& a, bool paged, int /*num_cu*/, hipStream
     if (rows_total > 16) return fail(RA_ERR_UNSUPPORTED, "round_scores: %d query rows per KV head in the 16-row kernel", rows_total);
     const dim3 grid(a.n_chunks_max, a.view.Hkv, a.view.B);
     if (paged)
-        hipLaunchKernelGGL((scores_mfma_kernel<true>), grid, dim3(256), tab_bytes, st, a);
+        RA_LAUNCH_TIMED((scores_mfma_kernel<true>), grid, dim3(256), tab_bytes, st, a);
     else
-        hipLaunchKernelGGL((scores_mfma_kernel<false>), grid, dim3(256), tab_bytes, st, a);
+        RA_LAUNCH_TIMED((scores_mfma_kernel<false>), grid, dim3(256), tab_bytes, st, a);
     return RA_OK;
 }
 

@@ -354,9 +354,9 @@ int launch_scores_prefill_mfma(const ScoreArgs& a, bool paged, int num_cu, hipSt
     if (grid > max_pieces * Hkv * n_rowblocks) grid = max_pieces * Hkv * n_rowblocks;
     if (grid < 1) grid = 1;
     if (paged)
-        hipLaunchKernelGGL((scores_prefill_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        RA_LAUNCH_TIMED((scores_prefill_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
     else
-        hipLaunchKernelGGL((scores_prefill_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        RA_LAUNCH_TIMED((scores_prefill_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
     return RA_OK;
 }
 
