@@ -53,8 +53,10 @@ __global__ __launch_bounds__(256) void plan_kernel(AttnArgs a, int unit_tokens) 
     for (int i = tid; i < cap; i += 256) {
         int len = 0;
         long long ok = 0, ov = 0;
+        // the list entry is asked for before the counts have arrived (one memory round trip less)
+        const int listed = (a.sel_idx && i < vw.R_max) ? a.sel_idx[(size_t)b * vw.R_max + i] : i;
         if (i < n_hist) {
-            const int r = a.sel_idx ? a.sel_idx[(size_t)b * vw.R_max + i] : i;
+            const int r = listed;
             if (r >= 0 && r < n_rounds) {  // entries that are not rounds of this sequence are ignored
                 len = max(vw.seg_len[(size_t)b * vw.R_max + r], 0);
                 ok = vw.seg_off[(size_t)b * vw.R_max + r];

@@ -44,7 +44,8 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     const int R = min(max(a.n_rounds[b], 0), a.R_max);
     int32_t* out = a.sel_idx + (size_t)b * a.R_max;
     for (int r = tid; r < a.R_max; r += 256) {
-        if (r < R) s[r] = a.scores[(size_t)b * a.R_max + r];
+        const float v = a.scores[(size_t)b * a.R_max + r];  // asked for before the round count has arrived
+        if (r < R) s[r] = v;
         out[r] = -1;
     }
     if (tid == 0) n_pass_sh = 0;
