@@ -64,6 +64,9 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="cfg5 only: measure the key bias alpha in {0.5, 1, 2, 4} x lambda in {0, 0.5, 1} (kept fraction "
                          "from about 5 to 60 %%) and print one JSON line with a `sweep` table instead of the usual line")
+    ap.add_argument("--watershed", action="store_true",
+                    help="measure decode at the watershed layer (cfg2 and cfg5): score pass + dense attention as two calls "
+                         "against the fused call; prints one JSON line with a `watershed_layer` list")
     ap.add_argument("--cpu-baseline-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     ap.add_argument("--stage-order", default="round", choices=["round", "layer"], help="cfg4: order of the host-to-device copies")
     return ap.parse_args()
@@ -246,6 +249,65 @@ def bench_step(name, steps, warmup, lam, alpha, replicas):
     results = [measure(l) for l in (lam if isinstance(lam, (list, tuple)) else [lam])]
     eng.close()
     return (results if isinstance(lam, (list, tuple)) else results[0]), w
+
+
+def bench_watershed(name, steps, warmup):
+    """Decode at the watershed layer: round scores + dense attention as two calls (K read twice) against the
+    fused call that takes the scores from the attention pass itself."""
+    import torch
+    import paper_2502_15294_amd as ra
+    from synth import make_workload
+    from synth.device import Engine, device_view, to_device
+
+    w = make_workload(name)
+    eng = Engine(w)
+    view = device_view(w, 0, threads=16)          # the watershed layer, keys and values
+    q = to_device(w.q(0)[:, 0], w.dtype)
+    q4 = to_device(w.q(0), w.dtype)
+    hist_tokens = sum(w.total_tokens(b) for b in range(w.B))
+    kv_bytes = hist_tokens * 2 * w.Hkv * w.d * 2
+    P = torch.empty((w.B, w.Hq, view.R_max), dtype=torch.float32, device="cuda")
+    S = torch.empty((w.B, view.R_max), dtype=torch.float32, device="cuda")
+    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((w.B, w.Hq), dtype=torch.float32, device="cuda")
+
+    def clone_view(v):
+        k, vv, seg_off, seg_len, n_rounds, bt, seg_off_v = v.tensors
+        return ra.KVView(k.clone(), vv.clone(), seg_off, seg_len, n_rounds, v.Hkv, v.d, v.c.max_tokens, block_table=bt,
+                         block_size=v.c.block_size, seg_off_v=seg_off_v)
+
+    n_rep = int(max(1, min(4, -(-CACHE_DEFEAT_BYTES // kv_bytes))))
+    reps = [view] + [clone_view(view) for _ in range(n_rep - 1)]
+
+    def separate(v):
+        ra.ra_round_scores(eng.ctx, q4, v, scale=w.scale, scores_head=P, scores=S)
+        ra.ra_round_sparse_attn_decode(eng.ctx, q, v, scale=w.scale, out=out, lse=lse)
+
+    def fused(v):
+        ra.ra_watershed_attn_decode(eng.ctx, q, v, scale=w.scale, out=out, lse=lse, scores_head=P, scores=S)
+
+    res = {}
+    for label, fn in (("two_calls", separate), ("fused", fused)):
+        for i in range(warmup):
+            fn(reps[i % n_rep])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(reps[i % n_rep])
+        torch.cuda.synchronize()
+        res[label + "_ms"] = (time.perf_counter() - t0) / steps * 1e3
+    ra.ra_profile_kernels(eng.ctx, True)
+    km = []
+    for i in range(min(steps, 20)):
+        fused(reps[i % n_rep])
+        km.append(ra.ra_profile_last_ms(eng.ctx))
+    ra.ra_profile_kernels(eng.ctx, False)
+    res.update({"workload": f"{name}: {WORKLOADS[name]}", "history_tokens": hist_tokens, "kv_bytes": kv_bytes,
+                "fused_kernel": "attn_mfma_kernel", "fused_kernel_ms": float(np.mean(km)),
+                "fused_kernel_GB/s": kv_bytes / float(np.mean(km)) / 1e6, "replicas_rotated": n_rep,
+                "speedup": res["two_calls_ms"] / res["fused_ms"]})
+    eng.close()
+    return res
 
 
 def bench_long_context(steps, warmup, lam, order_name):
@@ -438,6 +500,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.watershed:
+        rows = [bench_watershed("cfg2", 200, 20), bench_watershed("cfg5", 20, 3)]
+        print(json.dumps({"metric": METRIC, "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+                          "watershed_layer": rows}))
+        return
     if args.sweep:
         table = []
         for alpha in (0.5, 1.0, 2.0, 4.0):

@@ -10,6 +10,8 @@
  *   ra_kv_store_*                 round-indexed store of the post-watershed KV ("u_m", Sec. 3.2):
  *                                 host-resident per round, selected rounds copied to the GPU
  *   ra_round_sparse_attn_decode   attention of one new token over the selected rounds (step 5)
+ *   ra_watershed_attn_decode      decode at the watershed layer: dense attention and, from the same pass
+ *                                 over the keys, the round scores (steps 2-3 fused)
  *   ra_round_sparse_attn_prefill  attention of the question's tokens over the selected rounds
  *                                 and, causally, over the question itself (step 4)
  *
@@ -183,6 +185,22 @@ int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq
                                 const int32_t* sel_idx, const int32_t* n_sel, const void* cur_k,
                                 const void* cur_v, const int32_t* cur_len, int cur_cap, float scale, float* out,
                                 float* lse);
+
+/*
+ * Decode at the watershed layer itself (Sec. 3.2 steps 2-3: the round scores are taken with the watershed
+ * layer's own attention, qAtt^{L_w}; Eq. 1 in its one-query-token form): dense attention of one query token per
+ * sequence over every history round of `watershed` (which must carry values) plus the current round, and, from
+ * the same pass over the keys, the round scores that ra_round_scores would return for this q and this layer
+ * (no current round in the scores: with one query token it cancels in the normalisation over history rounds).
+ * One read of K and V instead of a read of K for the scores and another of K and V for the attention.
+ *   q, cur_k, cur_v, cur_len, cur_cap, out, lse   as for ra_round_sparse_attn_decode with sel_idx = NULL
+ *   scores_head  device float [B][Hq][R_max] or NULL;  scores  device float [B][R_max] (required)
+ * bf16 with d = 128 only (RA_ERR_UNSUPPORTED otherwise).  As in ra_round_scores, a view whose max_tokens
+ * understates the history gives NaN scores.
+ */
+int ra_watershed_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* watershed,
+                             const void* cur_k, const void* cur_v, const int32_t* cur_len, int cur_cap, float scale,
+                             float* out, float* lse, float* scores_head, float* scores);
 
 /*
  * Round-sparse question-prefill attention (Sec. 3.2 step 4): q_len query tokens per sequence, the

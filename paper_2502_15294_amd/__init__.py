@@ -27,7 +27,8 @@ RA_OK, RA_ERR_INVALID_ARG, RA_ERR_UNSUPPORTED, RA_ERR_WORKSPACE, RA_ERR_STATE, R
 EXPORTS = [
     "ra_last_error", "ra_create", "ra_destroy", "ra_workspace_bytes", "ra_set_workspace",
     "ra_profile_kernels", "ra_profile_last_ms",
-    "ra_round_scores", "ra_select_rounds", "ra_round_sparse_attn_decode", "ra_round_sparse_attn_prefill",
+    "ra_round_scores", "ra_select_rounds", "ra_round_sparse_attn_decode", "ra_watershed_attn_decode",
+    "ra_round_sparse_attn_prefill",
     "ra_kv_store_create", "ra_kv_store_destroy", "ra_kv_store_register_round", "ra_kv_store_round_bytes",
     "ra_kv_store_stage", "ra_kv_store_wait_layer", "ra_kv_store_layer_view", "ra_kv_store_stats",
     "ra_kv_store_release",
@@ -90,6 +91,9 @@ def lib() -> C.CDLL:
         L.ra_round_sparse_attn_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(ra_kv_view),
                                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                                   C.c_float, C.c_void_p, C.c_void_p]
+        L.ra_watershed_attn_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(ra_kv_view),
+                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
+                                               C.c_void_p, C.c_void_p, C.c_void_p]
         L.ra_round_sparse_attn_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                                    C.POINTER(ra_kv_view), C.c_void_p, C.c_void_p, C.c_void_p,
                                                    C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p]
@@ -254,6 +258,31 @@ def ra_round_sparse_attn_decode(ctx, q: torch.Tensor, view: KVView, sel_idx: Opt
                                              _ptr(n_sel), _ptr(cur_k), _ptr(cur_v), _ptr(cur_len), cur_cap, scale,
                                              _ptr(out), _ptr(lse)))
     return out, lse
+
+
+def ra_watershed_attn_decode(ctx, q: torch.Tensor, view: KVView, cur_k: Optional[torch.Tensor] = None,
+                             cur_v: Optional[torch.Tensor] = None, cur_len: Optional[torch.Tensor] = None,
+                             scale: Optional[float] = None, out: Optional[torch.Tensor] = None,
+                             lse: Optional[torch.Tensor] = None, scores_head: Optional[torch.Tensor] = None,
+                             scores: Optional[torch.Tensor] = None, stream=None
+                             ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Returns (out, lse, scores_head, scores)."""
+    B, Hq, d = q.shape
+    if scale is None:
+        scale = d ** -0.5
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    if scores_head is None:
+        scores_head = torch.empty((B, Hq, view.R_max), dtype=torch.float32, device=q.device)
+    if scores is None:
+        scores = torch.empty((B, view.R_max), dtype=torch.float32, device=q.device)
+    cur_cap = 0 if cur_k is None else cur_k.shape[1]
+    _check(lib().ra_watershed_attn_decode(ctx, _stream(stream), _ptr(q), Hq, C.byref(view.c), _ptr(cur_k), _ptr(cur_v),
+                                          _ptr(cur_len), cur_cap, scale, _ptr(out), _ptr(lse), _ptr(scores_head),
+                                          _ptr(scores)))
+    return out, lse, scores_head, scores
 
 
 def ra_round_sparse_attn_prefill(ctx, q: torch.Tensor, view: KVView, sel_idx: Optional[torch.Tensor] = None,

@@ -29,6 +29,11 @@ struct AttnArgs {
     char* plan;       // [B][plan_stride(R_max + 1)] per-sequence segment tables (see stream_kv.hpp)
     float* out;       // [rows][D]
     float* lse;       // [rows] or null
+    // decode at the watershed layer only: natural-log sum-exp of the scaled logits of every 32-token key tile,
+    // [rows][n_tiles_max], tile index = position in the sequence's table (history rounds in order, then the
+    // current round); null otherwise
+    float* tile_lse;
+    int n_tiles_max;
 };
 
 // Workspace layout of one attention call; returns the bytes needed past the reserved head.

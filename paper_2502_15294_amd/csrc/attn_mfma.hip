@@ -38,7 +38,7 @@ struct KVTile {
     uint2 v[8][2];  // [dt][half]: tokens 4*(lane/16) .. +3 of that half, channel dt*16 + lane%16
 };
 
-template <bool PAGED>
+template <bool PAGED, bool TILE_LSE>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             }
         };
 
-        auto consume = [&](const KVTile& t, int uin, int len, bool is_cur) {
+        auto consume = [&](const KVTile& t, int uin, int len, bool is_cur, int u_seq) {
             const int tok0 = uin * kTile;
             const bool full = !is_cur && (len - tok0 >= kTile);
 #pragma unroll
@@ -208,7 +208,14 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) p[h * 4 + i] = fast_exp2(__builtin_fmaf(sc[h][i], a.c, -mc));
-                l[nt] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+                const float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+                l[nt] += ps;
+                if constexpr (TILE_LSE) {  // the tile's share of the softmax normaliser: the round scores' raw material
+                    const float pt = xrow_sum4(ps);
+                    if (q4 == 0 && row_ok[nt] && u_seq < a.n_tiles_max)
+                        a.tile_lse[rowid[nt] * a.n_tiles_max + u_seq] =
+                            pt > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(pt)) : -__builtin_inff();
+                }
                 uint4 phi, plo;
                 phi.x = pack_trunc(p[0], p[1]);
                 phi.y = pack_trunc(p[2], p[3]);
@@ -236,11 +243,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             // Two tile buffers used alternately: the loads of one tile are in flight while the other
             // is consumed, and no register that is still being loaded is ever copied.
             KVTile ta, tb;
-            int len_a = 0, uin_a = 0, len_b = 0, uin_b = 0;
+            int len_a = 0, uin_a = 0, len_b = 0, uin_b = 0, us_a = 0, us_b = 0;
             bool cur_a = false, cur_b = false;
             if (have) {
                 slot = find_slot(tab.cum, n_slots, u);
                 uin_a = u - tab.cum[slot];
+                us_a = u;
                 issue(uin_a, slot, ta, len_a, cur_a);
             }
             while (have) {
@@ -249,18 +257,20 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                 if (have_b) {
                     while (u >= tab.cum[slot + 1]) ++slot;
                     uin_b = u - tab.cum[slot];
+                    us_b = u;
                     issue(uin_b, slot, tb, len_b, cur_b);
                 }
-                consume(ta, uin_a, len_a, cur_a);
+                consume(ta, uin_a, len_a, cur_a, us_a);
                 if (!have_b) break;
                 u += step;
                 have = u < u_hi;
                 if (have) {
                     while (u >= tab.cum[slot + 1]) ++slot;
                     uin_a = u - tab.cum[slot];
+                    us_a = u;
                     issue(uin_a, slot, ta, len_a, cur_a);
                 }
-                consume(tb, uin_b, len_b, cur_b);
+                consume(tb, uin_b, len_b, cur_b, us_b);
             }
         }
 
@@ -335,10 +345,17 @@ int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) 
     if (grid > max_pieces * Hkv * n_rowblocks) grid = max_pieces * Hkv * n_rowblocks;
     if (grid < 1) grid = 1;
     const size_t smem = tab_bytes + (128 + 4 * 16 * 128) * sizeof(float);
-    if (paged)
-        RA_LAUNCH_TIMED((attn_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-    else
-        RA_LAUNCH_TIMED((attn_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    if (a.tile_lse) {
+        if (paged)
+            RA_LAUNCH_TIMED((attn_mfma_kernel<true, true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        else
+            RA_LAUNCH_TIMED((attn_mfma_kernel<false, true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    } else {
+        if (paged)
+            RA_LAUNCH_TIMED((attn_mfma_kernel<true, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        else
+            RA_LAUNCH_TIMED((attn_mfma_kernel<false, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    }
     return RA_OK;
 }
 

@@ -13,6 +13,7 @@
 // accumulators) per query head.  A sequence with a short selection is not split and its output is
 // written directly; otherwise a second small kernel merges the pieces.
 #include "attn_common.hpp"
+#include "scores_common.hpp"
 #include "stream_kv.hpp"
 
 #include <stdlib.h>
@@ -363,10 +364,12 @@ static int dispatch_generic(bool paged, dim3 grid, hipStream_t st, const AttnArg
 
 using namespace ra;
 
-extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* layer,
-                                           const int32_t* sel_idx, const int32_t* n_sel, const void* cur_k,
-                                           const void* cur_v, const int32_t* cur_len, int cur_cap, float scale,
-                                           float* out, float* lse) {
+// Shared by the two decode entry points.  With `scores` given (watershed layer) the attention runs over every
+// history round and the kernel also leaves one log-sum-exp per 32-token key tile, which the finishing kernel of
+// the score pass turns into Eq. 1.
+static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* layer, const int32_t* sel_idx,
+                       const int32_t* n_sel, const void* cur_k, const void* cur_v, const int32_t* cur_len, int cur_cap,
+                       float scale, float* out, float* lse, float* scores_head, float* scores) {
     RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "decode: ctx is NULL");
     RA_REQUIRE(q != nullptr && out != nullptr, RA_ERR_INVALID_ARG, "decode: q or out is NULL");
     if (int rc = check_view(layer, true, "decode")) return rc;
@@ -393,12 +396,23 @@ extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void
     RA_REQUIRE((size_t)B * sizeof(int) <= kWsReserved, RA_ERR_UNSUPPORTED, "decode: B = %d exceeds %zu", B,
                kWsReserved / sizeof(int));
 
+    const bool with_scores = scores != nullptr;
+    if (with_scores) {
+        RA_REQUIRE(mfma, RA_ERR_UNSUPPORTED, "watershed decode: only bf16 with head_dim 128 is implemented");
+        RA_REQUIRE(layer->R_max > 0, RA_ERR_INVALID_ARG, "watershed decode: R_max is 0, there is nothing to score");
+    }
+
     const int64_t max_tok = layer->max_tokens + (has_cur ? cur_cap : 0);
     const int S = mfma ? mfma_max_pieces(max_tok, attn_min_units(), 64) : decode_splits(ctx->num_cu, B, layer->Hkv, max_tok);
     const size_t rows = (size_t)B * Hq;
     const AttnWorkspace w = attn_workspace(rows, S, D, B, layer->R_max);
-    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total, RA_ERR_WORKSPACE,
-               "decode: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total);
+    // one entry per 32-token tile of a sequence's table: history rounds (each rounded up), then the current round
+    const int64_t n_tiles64 = layer->max_tokens / 32 + layer->R_max + (has_cur ? cur_cap / 32 + 1 : 0);
+    RA_REQUIRE(!with_scores || n_tiles64 <= (int64_t)1 << 24, RA_ERR_UNSUPPORTED, "watershed decode: max_tokens too large");
+    const int n_tiles_max = (int)n_tiles64;
+    const size_t tile_bytes = with_scores ? align_up(rows * n_tiles_max * sizeof(float), 256) : 0;
+    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total + tile_bytes, RA_ERR_WORKSPACE,
+               "decode: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total + tile_bytes);
 
     AttnArgs a;
     a.view = to_dev(layer);
@@ -425,6 +439,8 @@ extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void
     a.plan = ctx->ws.base + w.plan_off;
     a.out = out;
     a.lse = lse;
+    a.tile_lse = with_scores ? reinterpret_cast<float*>(ctx->ws.base + w.total) : nullptr;
+    a.n_tiles_max = with_scores ? n_tiles_max : 0;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool paged = layer->block_size != 0;
@@ -446,6 +462,40 @@ extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void
     }
     if (rc) return rc;
     if (S > 1) launch_combine(a, D, rows, st);
+    if (with_scores) {
+        // With a single query token the current round cancels in the normalisation over history rounds: the
+        // finishing kernel reads the history tiles only.
+        FinishArgs f;
+        f.part = a.tile_lse;
+        f.n_rounds = layer->n_rounds;
+        f.seg_len = layer->seg_len;
+        f.R_max = layer->R_max;
+        f.Hq = Hq;
+        f.q_len = 1;
+        f.cur_len = 0;
+        f.n_chunks_max = n_tiles_max;
+        f.chunk_tokens = 32;
+        f.has_cur = false;
+        f.p_out = scores_head;
+        f.s_out = scores;
+        launch_scores_finish_single(f, B, st);
+    }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
+}
+
+extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* layer,
+                                           const int32_t* sel_idx, const int32_t* n_sel, const void* cur_k,
+                                           const void* cur_v, const int32_t* cur_len, int cur_cap, float scale,
+                                           float* out, float* lse) {
+    return decode_impl(ctx, stream, q, Hq, layer, sel_idx, n_sel, cur_k, cur_v, cur_len, cur_cap, scale, out, lse, nullptr,
+                       nullptr);
+}
+
+extern "C" int ra_watershed_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* watershed,
+                                        const void* cur_k, const void* cur_v, const int32_t* cur_len, int cur_cap,
+                                        float scale, float* out, float* lse, float* scores_head, float* scores) {
+    RA_REQUIRE(scores != nullptr, RA_ERR_INVALID_ARG, "watershed decode: scores is NULL");
+    return decode_impl(ctx, stream, q, Hq, watershed, nullptr, nullptr, cur_k, cur_v, cur_len, cur_cap, scale, out, lse,
+                       scores_head, scores);
 }

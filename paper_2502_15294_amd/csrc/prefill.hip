@@ -62,6 +62,8 @@ extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const voi
     a.plan = ctx->ws.base + w.plan_off;
     a.out = out;
     a.lse = lse;
+    a.tile_lse = nullptr;
+    a.n_tiles_max = 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     launch_plan(a, 32, st);
     // Few query rows per KV head: the decode kernel's token split keeps all four waves busy; otherwise

@@ -192,15 +192,6 @@ __device__ __forceinline__ float lse_range(const float* x, int lo, int hi) {
 // grid (B), block 512.  Wave w finishes heads w, w + 8, ...; lane j owns rounds j, j + 64, ...
 // (KPL rounds per lane).  P goes to p_out [B][Hq][R_max] if wanted; the head mean is accumulated per
 // wave in registers and reduced over the eight waves through LDS in a fixed order.
-struct FinishArgs {
-    const float* part;
-    const int32_t* n_rounds;
-    const int32_t* seg_len;
-    int R_max, Hq, q_len, cur_len, n_chunks_max, chunk_tokens;
-    bool has_cur;
-    float* p_out;  // may be null
-    float* s_out;
-};
 constexpr int kFinishWaves = 8;
 constexpr int kRowBufMax = 2048;  // chunk values a wave can stage in LDS (8 waves x 8 KB)
 
@@ -443,6 +434,32 @@ static int dispatch_scores(int G, bool paged, dim3 grid, size_t smem, hipStream_
 
 using namespace ra;
 
+namespace ra {
+// One query token: the finishing kernel for B sequences (a.q_len must be 1).
+void launch_scores_finish_single(const FinishArgs& f, int B, hipStream_t st) {
+    const int R_max = f.R_max, Hq = f.Hq, n_chunks_max = f.n_chunks_max;
+    const size_t fin_smem = (size_t)(R_max + 2) * sizeof(int) + (size_t)kFinishWaves * R_max * sizeof(float);
+    const dim3 fin_block(kFinishWaves * 64);
+    const bool stage_rows =
+        n_chunks_max <= kRowBufMax && fin_smem + (size_t)kFinishWaves * n_chunks_max * sizeof(float) <= 60 * 1024;
+    const size_t smem = fin_smem + (stage_rows ? (size_t)kFinishWaves * n_chunks_max * sizeof(float) : 0);
+    // sixteen waves (two heads each at Hq = 32) when the per-wave LDS strips still fit
+    const size_t smem16 = (size_t)(R_max + 2) * sizeof(int) + (size_t)16 * R_max * sizeof(float) +
+                          (stage_rows ? (size_t)16 * n_chunks_max * sizeof(float) : 0);
+    if (R_max <= 64 && Hq > 8 && smem16 <= 60 * 1024)
+        hipLaunchKernelGGL((scores_finish_kernel<1, 16>), dim3(B), dim3(1024), smem16, st, f, stage_rows);
+    else if (R_max <= 64)
+        hipLaunchKernelGGL((scores_finish_kernel<1, kFinishWaves>), dim3(B), fin_block, smem, st, f, stage_rows);
+    else if (R_max <= 256 && Hq > 8 && smem16 <= 60 * 1024)
+        hipLaunchKernelGGL((scores_finish_kernel<4, 16>), dim3(B), dim3(1024), smem16, st, f, stage_rows);
+    else if (R_max <= 256)
+        hipLaunchKernelGGL((scores_finish_kernel<4, kFinishWaves>), dim3(B), fin_block, smem, st, f, stage_rows);
+    else
+        hipLaunchKernelGGL((scores_finish_kernel<kMaxRounds / 64, kFinishWaves>), dim3(B), fin_block, smem, st, f,
+                           stage_rows);
+}
+}  // namespace ra
+
 extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
                                const ra_kv_view* watershed, const void* cur_k, int cur_len, float scale,
                                float* scores_head, float* scores) {
@@ -551,23 +568,7 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
         hipLaunchKernelGGL(scores_heads_kernel, dim3(B), dim3(kHeadsWaves * 64), (size_t)kHeadsWaves * R_max * sizeof(float),
                            st, p_buf, Z, R_max, Hq, scores_head, scores);
     } else {
-        const bool stage_rows =
-            n_chunks_max <= kRowBufMax && fin_smem + (size_t)kFinishWaves * n_chunks_max * sizeof(float) <= 60 * 1024;
-        const size_t smem = fin_smem + (stage_rows ? (size_t)kFinishWaves * n_chunks_max * sizeof(float) : 0);
-        // sixteen waves (two heads each at Hq = 32) when the per-wave LDS strips still fit
-        const size_t smem16 = (size_t)(R_max + 2) * sizeof(int) + (size_t)16 * R_max * sizeof(float) +
-                              (stage_rows ? (size_t)16 * n_chunks_max * sizeof(float) : 0);
-        if (R_max <= 64 && Hq > 8 && smem16 <= 60 * 1024)
-            hipLaunchKernelGGL((scores_finish_kernel<1, 16>), dim3(B), dim3(1024), smem16, st, f, stage_rows);
-        else if (R_max <= 64)
-            hipLaunchKernelGGL((scores_finish_kernel<1, kFinishWaves>), dim3(B), fin_block, smem, st, f, stage_rows);
-        else if (R_max <= 256 && Hq > 8 && smem16 <= 60 * 1024)
-            hipLaunchKernelGGL((scores_finish_kernel<4, 16>), dim3(B), dim3(1024), smem16, st, f, stage_rows);
-        else if (R_max <= 256)
-            hipLaunchKernelGGL((scores_finish_kernel<4, kFinishWaves>), dim3(B), fin_block, smem, st, f, stage_rows);
-        else
-            hipLaunchKernelGGL((scores_finish_kernel<kMaxRounds / 64, kFinishWaves>), dim3(B), fin_block, smem, st, f,
-                               stage_rows);
+        launch_scores_finish_single(f, B, st);
     }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;

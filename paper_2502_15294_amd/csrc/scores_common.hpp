@@ -22,6 +22,18 @@ struct ScoreArgs {
     int S, min_units;   // a sequence is cut into at most S pieces of at least min_units key tiles
 };
 
+// Input of the finishing kernels: per-chunk log-sum-exps -> Eq. 1.
+struct FinishArgs {
+    const float* part;         // [B][Hq][q_len][n_chunks_max]
+    const int32_t* n_rounds;
+    const int32_t* seg_len;
+    int R_max, Hq, q_len, cur_len, n_chunks_max, chunk_tokens;
+    bool has_cur;
+    float* p_out;  // may be null
+    float* s_out;
+};
+void launch_scores_finish_single(const FinishArgs& f, int B, hipStream_t st);
+
 __device__ __forceinline__ int chunks_of(int len, int chunk_tokens = kChunkTokens) {
     return (len + chunk_tokens - 1) / chunk_tokens;
 }

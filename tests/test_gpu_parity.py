@@ -515,3 +515,62 @@ def test_largest_round_count_decode_and_prefill():
     ref_o, _ = pipeline.attention_for_sequence(w, 0, 1, sel)
     assert ora.row_error(out[0], ref_o) < STREAM_TOL
     eng.close()
+
+
+WATERSHED_CASES = {
+    "bf16_g4_ragged_cur": ("cfg2", dict(B=3, R=7, cur_len=37, lens=[[5, 16, 17, 0, 33, 1, 250], [64, 3, 0, 0, 15, 48, 31],
+                                                                    [7, 9, 200, 31, 32, 33, 1]])),
+    "bf16_g8_paged": ("cfg5", dict(B=2, R=6, lens=[[300, 17, 16, 1, 999, 50], [31, 32, 33, 0, 64, 5]])),
+    "bf16_uneven_round_counts": ("cfg2", dict(B=3, lens=[[30, 40], [10, 20, 30, 40, 50], [700]])),
+    "bf16_many_rounds": ("cfg2", dict(B=2, R=300, length=("uniform", 1, 40))),
+    "bf16_cfg2_full": ("cfg2", dict()),
+}
+
+
+@pytest.mark.parametrize("name", list(WATERSHED_CASES))
+def test_watershed_decode_attention_and_scores_match_oracle(name):
+    """Dense decode attention at the watershed layer with the round scores from the same pass: both against the
+    oracle, the scores also against the stand-alone score pass, the output bitwise against the plain decode call."""
+    cfg, over = WATERSHED_CASES[name]
+    w = make_workload(cfg, **over)
+    _say(f"watershed decode case {name}: B={w.B} R_max={w.R_max} cur_len={w.cur_len} block={w.block_size}")
+    eng = Engine(w)
+    view = device_view(w, 0)                      # watershed layer with values
+    q = to_device(w.q(0)[:, 0], w.dtype)
+    ck = to_device(w.cur_k(0), w.dtype) if w.cur_len else None
+    cv = to_device(w.cur_v(0), w.dtype) if w.cur_len else None
+    cl = torch.full((w.B,), w.cur_len, dtype=torch.int32, device="cuda") if w.cur_len else None
+    out, lse, P, S = ra.ra_watershed_attn_decode(eng.ctx, q, view, ck, cv, cl, scale=w.scale)
+    out2, lse2 = ra.ra_round_sparse_attn_decode(eng.ctx, q, view, None, None, ck, cv, cl, scale=w.scale)
+    P2, S2 = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), view, scale=w.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(lse, lse2)
+    out, P, S, P2, S2 = out.cpu().numpy(), P.cpu().numpy(), S.cpu().numpy(), P2.cpu().numpy(), S2.cpu().numpy()
+    assert np.abs(P - P2).max() < SCORE_TOL and np.abs(S - S2).max() < SCORE_TOL
+    for b in (range(w.B) if w.B <= 4 else (0, w.B - 1)):
+        R = w.n_rounds(b)
+        rP, rS = pipeline.scores_for_sequence(w, b)
+        assert np.abs(P[b, :, :R] - rP).max() < SCORE_TOL and np.abs(S[b, :R] - rS).max() < SCORE_TOL
+        assert np.all(P[b, :, R:] == 0) and np.all(S[b, R:] == 0)
+        ref_o, _ = pipeline.attention_for_sequence(w, b, 0, list(range(R)))
+        assert ora.row_error(out[b], ref_o[0]) < STREAM_TOL
+    eng.close()
+
+
+def test_watershed_decode_rejects_what_it_cannot_do():
+    w = make_workload("cfg1")                     # fp32, d = 64
+    eng = Engine(w)
+    view = device_view(w, 0)
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_watershed_attn_decode(eng.ctx, to_device(w.q(0)[:, 0], w.dtype), view, scale=w.scale)
+    assert e.value.code == ra.RA_ERR_UNSUPPORTED
+    eng.close()
+    w = make_workload("cfg2", B=1, R=6, length=("fixed", 600))
+    eng = Engine(w)
+    view = device_view(w, 0)
+    k, v, seg_off, seg_len, n_rounds, bt, seg_off_v = view.tensors
+    small = ra.KVView(k, v, seg_off, seg_len, n_rounds, view.Hkv, view.d, 256, seg_off_v=seg_off_v)   # truth: 3600 tokens
+    _, _, _, S = ra.ra_watershed_attn_decode(eng.ctx, to_device(w.q(0)[:, 0], w.dtype), small, scale=w.scale)
+    torch.cuda.synchronize()
+    assert np.isnan(S.cpu().numpy()).all()
+    eng.close()
