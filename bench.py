@@ -65,7 +65,7 @@ def parse():
                     help="cfg5 only: measure the key bias alpha in {0.5, 1, 2, 4} x lambda in {0, 0.5, 1} (kept fraction "
                          "from about 5 to 60 %%) and print one JSON line with a `sweep` table instead of the usual line")
     ap.add_argument("--watershed", action="store_true",
-                    help="measure decode at the watershed layer (cfg2 and cfg5): score pass + dense attention as two calls "
+                    help="measure the watershed layer (decode: cfg2, cfg5; question prefill: cfg3): score pass + dense attention as two calls "
                          "against the fused call; prints one JSON line with a `watershed_layer` list")
     ap.add_argument("--cpu-baseline-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     ap.add_argument("--stage-order", default="round", choices=["round", "layer"], help="cfg4: order of the host-to-device copies")
@@ -252,24 +252,27 @@ def bench_step(name, steps, warmup, lam, alpha, replicas):
 
 
 def bench_watershed(name, steps, warmup):
-    """Decode at the watershed layer: round scores + dense attention as two calls (K read twice) against the
-    fused call that takes the scores from the attention pass itself."""
+    """Decode (or question prefill) at the watershed layer: round scores + dense attention as two calls (K read twice)
+    against the fused call that takes the scores from the attention pass itself."""
     import torch
     import paper_2502_15294_amd as ra
     from synth import make_workload
     from synth.device import Engine, device_view, to_device
 
     w = make_workload(name)
+    prefill = w.q_len > 1
     eng = Engine(w)
     view = device_view(w, 0, threads=16)          # the watershed layer, keys and values
-    q = to_device(w.q(0)[:, 0], w.dtype)
     q4 = to_device(w.q(0), w.dtype)
+    q = q4 if prefill else to_device(w.q(0)[:, 0], w.dtype)
+    ck = to_device(w.cur_k(0), w.dtype) if w.cur_len else None
+    cv = to_device(w.cur_v(0), w.dtype) if w.cur_len else None
     hist_tokens = sum(w.total_tokens(b) for b in range(w.B))
     kv_bytes = hist_tokens * 2 * w.Hkv * w.d * 2
     P = torch.empty((w.B, w.Hq, view.R_max), dtype=torch.float32, device="cuda")
     S = torch.empty((w.B, view.R_max), dtype=torch.float32, device="cuda")
-    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda")
-    lse = torch.empty((w.B, w.Hq), dtype=torch.float32, device="cuda")
+    out = torch.empty((w.B, w.q_len, w.Hq, w.d) if prefill else (w.B, w.Hq, w.d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((w.B, w.q_len, w.Hq) if prefill else (w.B, w.Hq), dtype=torch.float32, device="cuda")
 
     def clone_view(v):
         k, vv, seg_off, seg_len, n_rounds, bt, seg_off_v = v.tensors
@@ -280,11 +283,18 @@ def bench_watershed(name, steps, warmup):
     reps = [view] + [clone_view(view) for _ in range(n_rep - 1)]
 
     def separate(v):
-        ra.ra_round_scores(eng.ctx, q4, v, scale=w.scale, scores_head=P, scores=S)
-        ra.ra_round_sparse_attn_decode(eng.ctx, q, v, scale=w.scale, out=out, lse=lse)
+        if prefill:
+            ra.ra_round_scores(eng.ctx, q4, v, ck, scale=w.scale, scores_head=P, scores=S)
+            ra.ra_round_sparse_attn_prefill(eng.ctx, q, v, None, None, ck, cv, scale=w.scale, out=out, lse=lse)
+        else:
+            ra.ra_round_scores(eng.ctx, q4, v, scale=w.scale, scores_head=P, scores=S)
+            ra.ra_round_sparse_attn_decode(eng.ctx, q, v, scale=w.scale, out=out, lse=lse)
 
     def fused(v):
-        ra.ra_watershed_attn_decode(eng.ctx, q, v, scale=w.scale, out=out, lse=lse, scores_head=P, scores=S)
+        if prefill:
+            ra.ra_watershed_attn_prefill(eng.ctx, q, v, ck, cv, scale=w.scale, out=out, lse=lse, scores_head=P, scores=S)
+        else:
+            ra.ra_watershed_attn_decode(eng.ctx, q, v, scale=w.scale, out=out, lse=lse, scores_head=P, scores=S)
 
     res = {}
     for label, fn in (("two_calls", separate), ("fused", fused)):
@@ -302,10 +312,16 @@ def bench_watershed(name, steps, warmup):
         fused(reps[i % n_rep])
         km.append(ra.ra_profile_last_ms(eng.ctx))
     ra.ra_profile_kernels(eng.ctx, False)
-    res.update({"workload": f"{name}: {WORKLOADS[name]}", "history_tokens": hist_tokens, "kv_bytes": kv_bytes,
-                "fused_kernel": "attn_mfma_kernel", "fused_kernel_ms": float(np.mean(km)),
-                "fused_kernel_GB/s": kv_bytes / float(np.mean(km)) / 1e6, "replicas_rotated": n_rep,
+    kms = float(np.mean(km))
+    res.update({"workload": f"{name}: {WORKLOADS[name]}", "history_tokens": hist_tokens, "replicas_rotated": n_rep,
+                "fused_kernel": "attn_prefill_mfma_kernel" if prefill else "attn_mfma_kernel", "fused_kernel_ms": kms,
                 "speedup": res["two_calls_ms"] / res["fused_ms"]})
+    if prefill:
+        flops = 4 * w.B * w.q_len * w.Hq * w.d * (hist_tokens / w.B + w.cur_len / 2)
+        res["fused_kernel_TFLOP/s"] = flops / kms / 1e9
+    else:
+        res["kv_bytes"] = kv_bytes
+        res["fused_kernel_GB/s"] = kv_bytes / kms / 1e6
     eng.close()
     return res
 
@@ -501,7 +517,7 @@ def main():
         del src, dst
 
     if args.watershed:
-        rows = [bench_watershed("cfg2", 200, 20), bench_watershed("cfg5", 20, 3)]
+        rows = [bench_watershed("cfg2", 200, 20), bench_watershed("cfg5", 20, 3), bench_watershed("cfg3", 20, 3)]
         print(json.dumps({"metric": METRIC, "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
                           "watershed_layer": rows}))
         return

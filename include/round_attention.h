@@ -10,8 +10,8 @@
  *   ra_kv_store_*                 round-indexed store of the post-watershed KV ("u_m", Sec. 3.2):
  *                                 host-resident per round, selected rounds copied to the GPU
  *   ra_round_sparse_attn_decode   attention of one new token over the selected rounds (step 5)
- *   ra_watershed_attn_decode      decode at the watershed layer: dense attention and, from the same pass
- *                                 over the keys, the round scores (steps 2-3 fused)
+ *   ra_watershed_attn_decode,     decode / question prefill at the watershed layer: dense attention and, from
+ *   ra_watershed_attn_prefill     the same pass over the keys, the round scores (steps 2-3 fused)
  *   ra_round_sparse_attn_prefill  attention of the question's tokens over the selected rounds
  *                                 and, causally, over the question itself (step 4)
  *
@@ -201,6 +201,18 @@ int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq
 int ra_watershed_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* watershed,
                              const void* cur_k, const void* cur_v, const int32_t* cur_len, int cur_cap, float scale,
                              float* out, float* lse, float* scores_head, float* scores);
+
+/*
+ * Question prefill at the watershed layer itself (Sec. 3.2 steps 2-3, Eq. 1 in its q_len-token form): dense
+ * attention of the question's q_len tokens over every history round of `watershed` and, causally, over the
+ * question itself, and from the same pass the round scores that ra_round_scores would return for this q, this
+ * layer and this cur_k.
+ *   q, q_len, cur_k, cur_v, cur_len, out, lse   as for ra_round_sparse_attn_prefill with sel_idx = NULL
+ *   scores_head  device float [B][Hq][R_max] or NULL;  scores  device float [B][R_max] (required)
+ */
+int ra_watershed_attn_prefill(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq, const ra_kv_view* watershed,
+                              const void* cur_k, const void* cur_v, int cur_len, float scale, float* out, float* lse,
+                              float* scores_head, float* scores);
 
 /*
  * Round-sparse question-prefill attention (Sec. 3.2 step 4): q_len query tokens per sequence, the

@@ -28,7 +28,7 @@ EXPORTS = [
     "ra_last_error", "ra_create", "ra_destroy", "ra_workspace_bytes", "ra_set_workspace",
     "ra_profile_kernels", "ra_profile_last_ms",
     "ra_round_scores", "ra_select_rounds", "ra_round_sparse_attn_decode", "ra_watershed_attn_decode",
-    "ra_round_sparse_attn_prefill",
+    "ra_round_sparse_attn_prefill", "ra_watershed_attn_prefill",
     "ra_kv_store_create", "ra_kv_store_destroy", "ra_kv_store_register_round", "ra_kv_store_round_bytes",
     "ra_kv_store_stage", "ra_kv_store_wait_layer", "ra_kv_store_layer_view", "ra_kv_store_stats",
     "ra_kv_store_release",
@@ -97,6 +97,9 @@ def lib() -> C.CDLL:
         L.ra_round_sparse_attn_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                                    C.POINTER(ra_kv_view), C.c_void_p, C.c_void_p, C.c_void_p,
                                                    C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p]
+        L.ra_watershed_attn_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(ra_kv_view),
+                                                C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p,
+                                                C.c_void_p, C.c_void_p]
         L.ra_kv_store_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(ra_store_cfg)]
         L.ra_kv_store_destroy.argtypes = [C.c_void_p]
         L.ra_kv_store_register_round.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int]
@@ -302,6 +305,30 @@ def ra_round_sparse_attn_prefill(ctx, q: torch.Tensor, view: KVView, sel_idx: Op
                                               _ptr(sel_idx), _ptr(n_sel), _ptr(cur_k), _ptr(cur_v), cur_len, scale,
                                               _ptr(out), _ptr(lse)))
     return out, lse
+
+
+def ra_watershed_attn_prefill(ctx, q: torch.Tensor, view: KVView, cur_k: Optional[torch.Tensor] = None,
+                              cur_v: Optional[torch.Tensor] = None, scale: Optional[float] = None,
+                              out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                              scores_head: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                              stream=None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Returns (out, lse, scores_head, scores)."""
+    B, q_len, Hq, d = q.shape
+    if scale is None:
+        scale = d ** -0.5
+    if out is None:
+        out = torch.empty((B, q_len, Hq, d), dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, q_len, Hq), dtype=torch.float32, device=q.device)
+    if scores_head is None:
+        scores_head = torch.empty((B, Hq, view.R_max), dtype=torch.float32, device=q.device)
+    if scores is None:
+        scores = torch.empty((B, view.R_max), dtype=torch.float32, device=q.device)
+    cur_len = 0 if cur_k is None else cur_k.shape[1]
+    _check(lib().ra_watershed_attn_prefill(ctx, _stream(stream), _ptr(q), q_len, Hq, C.byref(view.c), _ptr(cur_k),
+                                           _ptr(cur_v), cur_len, scale, _ptr(out), _ptr(lse), _ptr(scores_head),
+                                           _ptr(scores)))
+    return out, lse, scores_head, scores
 
 
 # ---- round-indexed KV store ----------------------------------------------------------------------

@@ -212,9 +212,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                 l[nt] += ps;
                 if constexpr (TILE_LSE) {  // the tile's share of the softmax normaliser: the round scores' raw material
                     const float pt = xrow_sum4(ps);
-                    if (q4 == 0 && row_ok[nt] && u_seq < a.n_tiles_max)
-                        a.tile_lse[rowid[nt] * a.n_tiles_max + u_seq] =
+                    if (q4 == 0 && row_ok[nt] && u_seq < a.n_tiles_max) {
+                        // row order of the score pass: [B][Hq][q_len]
+                        const size_t head = rowid[nt] - ((size_t)b * q_len + qtok[nt]) * a.Hq;
+                        const size_t srow = ((size_t)b * a.Hq + head) * q_len + qtok[nt];
+                        a.tile_lse[srow * a.n_tiles_max + u_seq] =
                             pt > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(pt)) : -__builtin_inff();
+                    }
                 }
                 uint4 phi, plo;
                 phi.x = pack_trunc(p[0], p[1]);

@@ -32,7 +32,7 @@ struct Share {
     uint2 v0, v1, v2, v3;  // V^T fragments (dt, half) = (2*wave, 0), (2*wave, 1), (2*wave + 1, 0), (2*wave + 1, 1)
 };
 
-template <bool PAGED>
+template <bool PAGED, bool TILE_LSE>
 __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             vd[128] = sh.v2;
             vd[192] = sh.v3;
         };
-        auto consume = [&](const char* buf, int tok0, int len, bool is_cur) {
+        auto consume = [&](const char* buf, int tok0, int len, bool is_cur, int u_seq) {
             const bool full = !is_cur && (len - tok0 >= kTileP);
             const uint4* kb = reinterpret_cast<const uint4*>(buf);
             const uint2* vb = reinterpret_cast<const uint2*>(buf + 8192);
@@ -285,7 +285,18 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) p[h * 4 + i] = fast_exp2(__builtin_fmaf(sc[nt][h][i], a.c, -mc));
-                l[nt] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+                const float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+                l[nt] += ps;
+                if constexpr (TILE_LSE) {  // the tile's share of the softmax normaliser: the round scores' raw material
+                    const float pt = xrow_sum4(ps);
+                    if (q4 == 0 && row_ok[nt] && u_seq < a.n_tiles_max) {
+                        // row order of the score pass: [B][Hq][q_len]
+                        const size_t head = rowid[nt] - ((size_t)b * q_len + qtok[nt]) * a.Hq;
+                        const size_t srow = ((size_t)b * a.Hq + head) * q_len + qtok[nt];
+                        a.tile_lse[srow * a.n_tiles_max + u_seq] =
+                            pt > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(pt)) : -__builtin_inff();
+                    }
+                }
                 phi.x = pack_hi16(p[0], p[1]);
                 phi.y = pack_hi16(p[2], p[3]);
                 phi.z = pack_hi16(p[4], p[5]);
@@ -337,7 +348,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                     sh = load_share();
                 }
                 RA_LAP(1);
-                consume(buf, tok0, len, is_cur);
+                consume(buf, tok0, len, is_cur, u);
                 RA_LAP(5);
                 bufsel ^= 1;
             }
@@ -389,10 +400,17 @@ int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStrea
     long long grid = (long long)2 * num_cu;
     if (grid > max_pieces * Hkv * n_rowblocks) grid = max_pieces * Hkv * n_rowblocks;
     if (grid < 1) grid = 1;
-    if (paged)
-        RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-    else
-        RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    if (a.tile_lse) {
+        if (paged)
+            RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<true, true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        else
+            RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<false, true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    } else {
+        if (paged)
+            RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<true, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        else
+            RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<false, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    }
     return RA_OK;
 }
 

@@ -142,7 +142,8 @@ int ra_workspace_bytes(const ra_problem* p, size_t* bytes_out) {
     const size_t sc = rows * chunks * sizeof(float) + (size_t)8 * p->B * p->Hq * p->R_max * sizeof(float) + 256;
     // decode at the watershed layer keeps, besides the attention partials, one log-sum-exp per (row, 32-token tile)
     const size_t tiles = (size_t)(p->max_tokens / 32) + p->R_max + 2;
-    const size_t fused = align_up(attn, 256) + align_up((size_t)p->B * p->Hq * tiles * sizeof(float), 256) + 256;
+    const size_t fused = align_up(attn, 256) + align_up(rows * tiles * sizeof(float), 256) +
+                         (size_t)8 * p->B * p->Hq * p->R_max * sizeof(float) + 512;
     size_t both = align_up(attn, 256) > align_up(sc, 256) + 256 ? align_up(attn, 256) : align_up(sc, 256) + 256;
     if (fused > both) both = fused;
     const size_t plan = (size_t)p->B * (((size_t)(p->R_max + 1) * 24 + 4 + 16 + 15) & ~(size_t)15);

@@ -2,13 +2,16 @@
 // question attend over the selected rounds' KV (fully visible) and, causally, over the question's own
 // KV.  Entry point only; the arithmetic is in the matrix-core kernels.
 #include "attn_common.hpp"
+#include "scores_common.hpp"
 
 using namespace ra;
 
-extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
-                                            const ra_kv_view* layer, const int32_t* sel_idx, const int32_t* n_sel,
-                                            const void* cur_k, const void* cur_v, int cur_len, float scale, float* out,
-                                            float* lse) {
+// Shared by the two prefill entry points.  With `scores` given (watershed layer) the attention runs over every
+// history round and the kernel also leaves one log-sum-exp per (query row, 32-token key tile), which the
+// finishing kernels of the score pass turn into Eq. 1.
+static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq, const ra_kv_view* layer,
+                        const int32_t* sel_idx, const int32_t* n_sel, const void* cur_k, const void* cur_v, int cur_len,
+                        float scale, float* out, float* lse, float* scores_head, float* scores) {
     RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "prefill: ctx is NULL");
     RA_REQUIRE(q != nullptr && out != nullptr, RA_ERR_INVALID_ARG, "prefill: q or out is NULL");
     if (int rc = check_view(layer, true, "prefill")) return rc;
@@ -34,8 +37,17 @@ extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const voi
     const int S = mfma_max_pieces(layer->max_tokens + cur_len, attn_min_units(), q_len * G <= 32 ? 64 : 8);
     const size_t rows = (size_t)B * q_len * Hq;
     const AttnWorkspace w = attn_workspace(rows, S, D, B, layer->R_max);
-    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total, RA_ERR_WORKSPACE,
-               "prefill: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total);
+    const bool with_scores = scores != nullptr;
+    RA_REQUIRE(!with_scores || layer->R_max > 0, RA_ERR_INVALID_ARG, "watershed prefill: R_max is 0, there is nothing to score");
+    // one entry per 32-token tile of a sequence's table: history rounds (each rounded up), then the current round
+    const int64_t n_tiles64 = layer->max_tokens / 32 + layer->R_max + cur_len / 32 + 1;
+    RA_REQUIRE(!with_scores || n_tiles64 <= (int64_t)1 << 24, RA_ERR_UNSUPPORTED, "watershed prefill: max_tokens too large");
+    const int n_tiles_max = (int)n_tiles64;
+    const int Z = scores_finish_splits(q_len, B, Hq);
+    const size_t tile_bytes = with_scores ? align_up(rows * n_tiles_max * sizeof(float), 256) : 0;
+    const size_t p_bytes = with_scores && q_len > 1 ? align_up((size_t)B * Hq * Z * layer->R_max * sizeof(float), 256) : 0;
+    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total + tile_bytes + p_bytes, RA_ERR_WORKSPACE,
+               "prefill: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total + tile_bytes + p_bytes);
 
     AttnArgs a;
     a.view = to_dev(layer);
@@ -62,8 +74,8 @@ extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const voi
     a.plan = ctx->ws.base + w.plan_off;
     a.out = out;
     a.lse = lse;
-    a.tile_lse = nullptr;
-    a.n_tiles_max = 0;
+    a.tile_lse = with_scores ? reinterpret_cast<float*>(ctx->ws.base + w.total) : nullptr;
+    a.n_tiles_max = with_scores ? n_tiles_max : 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     launch_plan(a, 32, st);
     // Few query rows per KV head: the decode kernel's token split keeps all four waves busy; otherwise
@@ -76,6 +88,43 @@ extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const voi
             return rc;
     }
     if (S > 1) launch_combine(a, D, rows, st);
+    if (with_scores) {
+        // Eq. 1 over history rounds and, for several query tokens, the visible part of the question itself
+        // (with one query token the current round cancels in the normalisation over history rounds).
+        FinishArgs f;
+        f.part = a.tile_lse;
+        f.n_rounds = layer->n_rounds;
+        f.seg_len = layer->seg_len;
+        f.R_max = layer->R_max;
+        f.Hq = Hq;
+        f.q_len = q_len;
+        f.has_cur = cur_len > 0 && q_len > 1;
+        f.cur_len = f.has_cur ? cur_len : 0;
+        f.n_chunks_max = n_tiles_max;
+        f.chunk_tokens = 32;
+        f.p_out = scores_head;
+        f.s_out = scores;
+        if (q_len > 1)
+            launch_scores_finish_rows(f, B, reinterpret_cast<float*>(ctx->ws.base + w.total + tile_bytes), Z, st);
+        else
+            launch_scores_finish_single(f, B, st);
+    }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
+}
+
+extern "C" int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
+                                            const ra_kv_view* layer, const int32_t* sel_idx, const int32_t* n_sel,
+                                            const void* cur_k, const void* cur_v, int cur_len, float scale, float* out,
+                                            float* lse) {
+    return prefill_impl(ctx, stream, q, q_len, Hq, layer, sel_idx, n_sel, cur_k, cur_v, cur_len, scale, out, lse, nullptr,
+                        nullptr);
+}
+
+extern "C" int ra_watershed_attn_prefill(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
+                                         const ra_kv_view* watershed, const void* cur_k, const void* cur_v, int cur_len,
+                                         float scale, float* out, float* lse, float* scores_head, float* scores) {
+    RA_REQUIRE(scores != nullptr, RA_ERR_INVALID_ARG, "watershed prefill: scores is NULL");
+    return prefill_impl(ctx, stream, q, q_len, Hq, watershed, nullptr, nullptr, cur_k, cur_v, cur_len, scale, out, lse,
+                        scores_head, scores);
 }

@@ -435,6 +435,32 @@ static int dispatch_scores(int G, bool paged, dim3 grid, size_t smem, hipStream_
 using namespace ra;
 
 namespace ra {
+// Several query tokens: Z workgroups per (sequence, head) leave partial round masses in p_part
+// [B][Hq][Z][R_max], a second kernel adds, normalises and averages them.
+int scores_finish_splits(int q_len, int B, int Hq) {
+    int Z = q_len / 32 < 1 ? 1 : (q_len / 32 > 8 ? 8 : q_len / 32);
+    while (Z > 1 && (int64_t)B * Hq * Z > 2048) --Z;
+    return Z;
+}
+void launch_scores_finish_rows(const FinishArgs& f, int B, float* p_part, int Z, hipStream_t st) {
+    const int R_max = f.R_max, Hq = f.Hq, n_chunks_max = f.n_chunks_max;
+    const size_t fin_smem = (size_t)(R_max + 2) * sizeof(int) + (size_t)kFinishWaves * R_max * sizeof(float);
+    const dim3 fin_block(kFinishWaves * 64);
+    const bool stage_rows =
+        n_chunks_max <= kRowBufMax && fin_smem + (size_t)kFinishWaves * n_chunks_max * sizeof(float) <= 60 * 1024;
+    const size_t smem = fin_smem + (stage_rows ? (size_t)kFinishWaves * n_chunks_max * sizeof(float) : 0);
+    const dim3 fgrid(B, Hq, Z);
+    if (R_max <= 64)
+        hipLaunchKernelGGL((scores_finish_rows_kernel<1>), fgrid, fin_block, smem, st, f, p_part, stage_rows);
+    else if (R_max <= 256)
+        hipLaunchKernelGGL((scores_finish_rows_kernel<4>), fgrid, fin_block, smem, st, f, p_part, stage_rows);
+    else
+        hipLaunchKernelGGL((scores_finish_rows_kernel<kMaxRounds / 64>), fgrid, fin_block, smem, st, f, p_part,
+                           stage_rows);
+    hipLaunchKernelGGL(scores_heads_kernel, dim3(B), dim3(kHeadsWaves * 64), (size_t)kHeadsWaves * R_max * sizeof(float),
+                       st, p_part, Z, R_max, Hq, f.p_out, f.s_out);
+}
+
 // One query token: the finishing kernel for B sequences (a.q_len must be 1).
 void launch_scores_finish_single(const FinishArgs& f, int B, hipStream_t st) {
     const int R_max = f.R_max, Hq = f.Hq, n_chunks_max = f.n_chunks_max;
@@ -490,8 +516,7 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     const size_t rows = (size_t)B * Hq * q_len;
     const size_t part_bytes = align_up(rows * n_chunks_max * sizeof(float), 256);
     // several query tokens: Z workgroups per head leave partial round masses in a buffer
-    int Z = q_len / 32 < 1 ? 1 : (q_len / 32 > 8 ? 8 : q_len / 32);
-    while (Z > 1 && (int64_t)B * Hq * Z > 2048) --Z;
+    const int Z = scores_finish_splits(q_len, B, Hq);
     const size_t p_bytes = q_len > 1 ? align_up((size_t)B * Hq * Z * R_max * sizeof(float), 256) : 0;
     // more than 16 query rows per KV head on the matrix cores: persistent kernel driven by segment tables
     const bool many_rows = mfma && q_len * G > 16;
@@ -550,26 +575,10 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     f.has_cur = use_cur;
     f.p_out = scores_head;
     f.s_out = scores;
-    const size_t fin_smem = (size_t)(R_max + 2) * sizeof(int) + (size_t)kFinishWaves * R_max * sizeof(float);
-    const dim3 fin_block(kFinishWaves * 64);
-    if (q_len > 1) {
-        float* p_buf = reinterpret_cast<float*>(ctx->ws.base + kWsReserved + part_bytes);
-        const bool stage_rows =
-            n_chunks_max <= kRowBufMax && fin_smem + (size_t)kFinishWaves * n_chunks_max * sizeof(float) <= 60 * 1024;
-        const size_t smem = fin_smem + (stage_rows ? (size_t)kFinishWaves * n_chunks_max * sizeof(float) : 0);
-        const dim3 fgrid(B, Hq, Z);
-        if (R_max <= 64)
-            hipLaunchKernelGGL((scores_finish_rows_kernel<1>), fgrid, fin_block, smem, st, f, p_buf, stage_rows);
-        else if (R_max <= 256)
-            hipLaunchKernelGGL((scores_finish_rows_kernel<4>), fgrid, fin_block, smem, st, f, p_buf, stage_rows);
-        else
-            hipLaunchKernelGGL((scores_finish_rows_kernel<kMaxRounds / 64>), fgrid, fin_block, smem, st, f, p_buf,
-                               stage_rows);
-        hipLaunchKernelGGL(scores_heads_kernel, dim3(B), dim3(kHeadsWaves * 64), (size_t)kHeadsWaves * R_max * sizeof(float),
-                           st, p_buf, Z, R_max, Hq, scores_head, scores);
-    } else {
+    if (q_len > 1)
+        launch_scores_finish_rows(f, B, reinterpret_cast<float*>(ctx->ws.base + kWsReserved + part_bytes), Z, st);
+    else
         launch_scores_finish_single(f, B, st);
-    }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
 }

@@ -33,6 +33,8 @@ struct FinishArgs {
     float* s_out;
 };
 void launch_scores_finish_single(const FinishArgs& f, int B, hipStream_t st);
+int scores_finish_splits(int q_len, int B, int Hq);  // Z of launch_scores_finish_rows
+void launch_scores_finish_rows(const FinishArgs& f, int B, float* p_part, int Z, hipStream_t st);
 
 __device__ __forceinline__ int chunks_of(int len, int chunk_tokens = kChunkTokens) {
     return (len + chunk_tokens - 1) / chunk_tokens;

@@ -51,6 +51,8 @@ def test_null_arguments_are_rejected_before_any_launch():
                                          None, None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_watershed_attn_decode(None, None, None, 4, C.byref(view), None, None, None, 0, 1.0, None, None, None,
                                       None) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_watershed_attn_prefill(None, None, None, 1, 4, C.byref(view), None, None, 0, 1.0, None, None, None,
+                                       None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_round_sparse_attn_prefill(None, None, None, 1, 4, C.byref(view), None, None, None, None, 0, 1.0,
                                           None, None) != ra.RA_OK
     assert L.ra_set_workspace(None, None, 0) == ra.RA_ERR_INVALID_ARG

@@ -574,3 +574,39 @@ def test_watershed_decode_rejects_what_it_cannot_do():
     torch.cuda.synchronize()
     assert np.isnan(S.cpu().numpy()).all()
     eng.close()
+
+
+WATERSHED_PREFILL_CASES = {
+    "q8_cur8_few_rows": dict(B=2, R=5, q_len=8, cur_len=8, length=("uniform", 10, 150)),
+    "q40_cur64": dict(B=2, R=6, q_len=40, cur_len=64, length=("uniform", 20, 600)),
+    "q20_ragged_rounds": dict(B=3, q_len=20, cur_len=23, lens=[[5, 16, 17, 0, 33, 1, 250], [64, 3, 0, 0, 15, 48, 31], [96]]),
+    "q24_history_only_paged_g8": dict(B=2, R=5, q_len=24, cur_len=0, Hq=64, block_size=16, length=("uniform", 5, 300)),
+    "q1_cur9": dict(B=2, R=5, q_len=1, cur_len=9, length=("uniform", 10, 200)),
+    "q128_long": dict(B=1, R=12, q_len=128, cur_len=128, length=("lognormal", 400.0, 0.8, 6000)),
+}
+
+
+@pytest.mark.parametrize("name", list(WATERSHED_PREFILL_CASES))
+def test_watershed_prefill_attention_and_scores_match_oracle(name):
+    w = make_workload("cfg3", **WATERSHED_PREFILL_CASES[name])
+    _say(f"watershed prefill case {name}: B={w.B} q_len={w.q_len} cur_len={w.cur_len} Hq={w.Hq} block={w.block_size}")
+    eng = Engine(w)
+    view = device_view(w, 0)
+    q = to_device(w.q(0), w.dtype)
+    ck = to_device(w.cur_k(0), w.dtype) if w.cur_len else None
+    cv = to_device(w.cur_v(0), w.dtype) if w.cur_len else None
+    out, lse, P, S = ra.ra_watershed_attn_prefill(eng.ctx, q, view, ck, cv, scale=w.scale)
+    out2, lse2 = ra.ra_round_sparse_attn_prefill(eng.ctx, q, view, None, None, ck, cv, scale=w.scale)
+    P2, S2 = ra.ra_round_scores(eng.ctx, q, view, ck, scale=w.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(lse, lse2)
+    out, P, S, P2, S2 = out.cpu().numpy(), P.cpu().numpy(), S.cpu().numpy(), P2.cpu().numpy(), S2.cpu().numpy()
+    assert np.abs(P - P2).max() < SCORE_TOL and np.abs(S - S2).max() < SCORE_TOL
+    for b in range(w.B):
+        R = w.n_rounds(b)
+        rP, rS = pipeline.scores_for_sequence(w, b)
+        assert np.abs(P[b, :, :R] - rP).max() < SCORE_TOL and np.abs(S[b, :R] - rS).max() < SCORE_TOL
+        assert np.all(P[b, :, R:] == 0) and np.all(S[b, R:] == 0)
+        ref_o, _ = pipeline.attention_for_sequence(w, b, 0, list(range(R)))
+        assert ora.row_error(out[b], ref_o) < STREAM_TOL
+    eng.close()
