@@ -489,6 +489,35 @@ def bench_long_context(steps, warmup, lam, order_name):
                             "(the 24 decode launches cycle through them); unselected rounds share one buffer"},
         "input_generation_s": t_gen,
     }
+    # ---- end of the turn: the new round of every sequence goes back to pinned host memory -------------------
+    new_len = 512
+    wb_store = ra.ra_kv_store_create(0, L, w.B, 1, w.Hkv, w.d, ra.RA_BF16,
+                                     w.B * L * 2 * new_len * k_bytes_tok + (1 << 20))
+    g = torch.Generator(device="cuda").manual_seed(4)
+    cur_k = [torch.randn((w.B, new_len, w.Hkv, w.d), generator=g, device="cuda").bfloat16() for _ in range(L)]
+    cur_v = [torch.randn((w.B, new_len, w.Hkv, w.d), generator=g, device="cuda").bfloat16() for _ in range(L)]
+    wb_host = [torch.empty(ra.ra_kv_store_round_bytes(wb_store, new_len) // 2, dtype=torch.int16, pin_memory=True)
+               for _ in range(w.B)]
+    wb_round = torch.zeros(w.B, dtype=torch.int32)
+    wb_len = torch.full((w.B,), new_len, dtype=torch.int32)
+    wb = []
+    for i in range(4):
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        torch.cuda.synchronize()
+        e0.record()
+        ra.ra_kv_store_save_round(wb_store, wb_round, wb_len, cur_k, cur_v, wb_host, None, side)
+        e1.record()
+        e2.record(side)
+        saved = ra.ra_kv_store_save_wait(wb_store)
+        torch.cuda.synchronize()
+        wb.append((e0.elapsed_time(e1), e0.elapsed_time(e2)))
+    pack_ms, total_ms = (float(np.mean([x[j] for x in wb[1:]])) for j in range(2))
+    res["write_back"] = {"new_round_tokens": new_len, "sequences": w.B, "layers": L, "bytes": saved,
+                         "gather_kernels_ms": pack_ms, "gather_GB/s": 2 * saved / (pack_ms * 1e-3) / 1e9,
+                         "until_in_host_memory_ms": total_ms,
+                         "d2h_GB/s": saved / ((total_ms - pack_ms) * 1e-3) / 1e9,
+                         "all_24_layers_extrapolated_ms": total_ms * L_all / L}
+    ra.ra_kv_store_destroy(wb_store)
     ra.ra_kv_store_release(store)
     ra.ra_kv_store_destroy(store)
     eng.close()

@@ -284,6 +284,48 @@ int ra_kv_store_stats(const ra_kv_store* store, uint64_t* staged_bytes, uint64_t
  * The caller must have finished all work that reads the staged views. */
 int ra_kv_store_release(ra_kv_store* store);
 
+/*
+ * End of a turn (Sec. 3.2, last step of the pipeline; Alg. 1, last line): the keys and values that the
+ * post-watershed layers produced for the new round go to host memory, one tensor per sequence in
+ * the host layout above, and are registered as round round_host[b] of sequence b.  (The selected
+ * rounds need no copy back: their host tensors are never modified.)
+ *   round_host   host int32 [B]: the index the new round gets; -1 = nothing to save for this sequence
+ *   len_host     host int32 [B]: tokens of the new round, 0 <= len <= cur_cap
+ *   cur_k_layers, cur_v_layers   host arrays of n_layers DEVICE pointers, one per post-watershed
+ *                layer, each [B][cur_cap][Hkv][d] token-major (the cur_k / cur_v of the attention
+ *                calls), 16-byte aligned
+ *   host_kv      host array of B pointers to PINNED host memory of ra_kv_store_round_bytes(len[b])
+ *                bytes each; written asynchronously, owned by the caller, kept alive while registered
+ * On `compute_stream` (after the work that wrote cur_k / cur_v) a gather kernel per layer packs the
+ * rounds into the device pool behind the staged rounds; `side_stream` waits for it and carries one
+ * device-to-host copy per sequence.  The call returns without waiting; a later ra_kv_store_stage
+ * that selects the new round is ordered behind the copy.  Needs d * element size to be a multiple
+ * of 16 bytes (RA_ERR_UNSUPPORTED otherwise).  RA_ERR_OOM if staged rounds plus the new rounds
+ * exceed the pool; nothing is enqueued or registered on any error found before the first launch.
+ * A second call first waits (on the host) for the previous call's copies.
+ */
+int ra_kv_store_save_round(ra_kv_store* store, const int32_t* round_host, const int32_t* len_host,
+                           const void* const* cur_k_layers, const void* const* cur_v_layers, int cur_cap,
+                           void* const* host_kv, void* compute_stream, void* side_stream);
+/* Block the host until the tensors of the last ra_kv_store_save_round are complete in host memory;
+ * saved_bytes (may be NULL) receives the bytes that call moved. */
+int ra_kv_store_save_wait(ra_kv_store* store, uint64_t* saved_bytes);
+
+/*
+ * KV-cache dropping (Sec. 3.4): rounds that are never selected are deleted rather than kept.
+ * Every ra_kv_store_stage call counts one turn for each registered round of each sequence and one
+ * hit for each round it selects; registering or saving a round resets its two counters.
+ * A dropped round keeps its index as an empty round (length 0, no host tensor): a later selection
+ * that names it stages nothing for it, and the caller may free its host tensor once the drop call
+ * has returned.  Both drop calls return RA_ERR_STATE while rounds are staged.
+ */
+int ra_kv_store_round_activity(const ra_kv_store* store, int seq, int round, uint32_t* turns, uint32_t* hits);
+int ra_kv_store_drop_round(ra_kv_store* store, int seq, int round);
+/* Drops every round with no hit in at least min_turns turns.  dropped_idx host int32 [B][R_max]
+ * receives the dropped rounds of each sequence in ascending order (-1 beyond), n_dropped host int32 [B]
+ * their count.  The paper gives no such threshold; it is the caller's. */
+int ra_kv_store_drop_inactive(ra_kv_store* store, uint32_t min_turns, int32_t* dropped_idx, int32_t* n_dropped);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,7 +31,8 @@ EXPORTS = [
     "ra_round_sparse_attn_prefill", "ra_watershed_attn_prefill",
     "ra_kv_store_create", "ra_kv_store_destroy", "ra_kv_store_register_round", "ra_kv_store_round_bytes",
     "ra_kv_store_stage", "ra_kv_store_wait_layer", "ra_kv_store_layer_view", "ra_kv_store_stats",
-    "ra_kv_store_release",
+    "ra_kv_store_release", "ra_kv_store_save_round", "ra_kv_store_save_wait", "ra_kv_store_round_activity",
+    "ra_kv_store_drop_round", "ra_kv_store_drop_inactive",
 ]
 
 
@@ -109,6 +110,14 @@ def lib() -> C.CDLL:
         L.ra_kv_store_stats.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
                                         C.POINTER(C.c_uint64)]
         L.ra_kv_store_release.argtypes = [C.c_void_p]
+        L.ra_kv_store_save_round.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p),
+                                             C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_void_p), C.c_void_p,
+                                             C.c_void_p]
+        L.ra_kv_store_save_wait.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
+        L.ra_kv_store_round_activity.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_uint32),
+                                                 C.POINTER(C.c_uint32)]
+        L.ra_kv_store_drop_round.argtypes = [C.c_void_p, C.c_int, C.c_int]
+        L.ra_kv_store_drop_inactive.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -379,3 +388,41 @@ def ra_kv_store_stats(store) -> Tuple[int, int, int]:
 
 def ra_kv_store_release(store) -> None:
     _check(lib().ra_kv_store_release(store))
+
+
+def ra_kv_store_save_round(store, round_host: torch.Tensor, len_host: torch.Tensor, cur_k_layers, cur_v_layers,
+                           host_kv, compute_stream=None, side_stream=None) -> None:
+    """cur_k_layers / cur_v_layers: one device tensor [B][cur_cap][Hkv][d] per post-watershed layer;
+    host_kv: one pinned CPU tensor (or None) per sequence; the caller keeps all of them alive."""
+    assert round_host.device.type == "cpu" and len_host.device.type == "cpu"
+    assert round_host.dtype == torch.int32 and len_host.dtype == torch.int32
+    n_layers, B = len(cur_k_layers), len(host_kv)
+    ks = (C.c_void_p * n_layers)(*[_ptr(t) for t in cur_k_layers])
+    vs = (C.c_void_p * n_layers)(*[_ptr(t) for t in cur_v_layers])
+    hs = (C.c_void_p * B)(*[None if t is None else t.data_ptr() for t in host_kv])
+    cur_cap = cur_k_layers[0].shape[1]
+    _check(lib().ra_kv_store_save_round(store, _ptr(round_host), _ptr(len_host), ks, vs, cur_cap, hs,
+                                        _stream(compute_stream), _stream(side_stream)))
+
+
+def ra_kv_store_save_wait(store) -> int:
+    n = C.c_uint64()
+    _check(lib().ra_kv_store_save_wait(store, C.byref(n)))
+    return n.value
+
+
+def ra_kv_store_round_activity(store, seq: int, rnd: int) -> Tuple[int, int]:
+    turns, hits = C.c_uint32(), C.c_uint32()
+    _check(lib().ra_kv_store_round_activity(store, seq, rnd, C.byref(turns), C.byref(hits)))
+    return turns.value, hits.value
+
+
+def ra_kv_store_drop_round(store, seq: int, rnd: int) -> None:
+    _check(lib().ra_kv_store_drop_round(store, seq, rnd))
+
+
+def ra_kv_store_drop_inactive(store, min_turns: int, B: int, R_max: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    idx = torch.empty((B, R_max), dtype=torch.int32)
+    n = torch.empty((B,), dtype=torch.int32)
+    _check(lib().ra_kv_store_drop_inactive(store, min_turns, _ptr(idx), _ptr(n)))
+    return idx, n

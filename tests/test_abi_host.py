@@ -61,4 +61,9 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert L.ra_kv_store_create(None, None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_kv_store_register_round(None, 0, 0, None, 0) == ra.RA_ERR_INVALID_ARG
     assert L.ra_kv_store_stage(None, None, None, 0, None) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_kv_store_save_round(None, None, None, None, None, 16, None, None, None) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_kv_store_save_wait(None, None) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_kv_store_round_activity(None, 0, 0, None, None) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_kv_store_drop_round(None, 0, 0) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_kv_store_drop_inactive(None, 1, None, None) == ra.RA_ERR_INVALID_ARG
     assert b"NULL" in L.ra_last_error()
