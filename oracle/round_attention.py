@@ -114,11 +114,15 @@ def round_scores(q, k_rounds: Sequence[np.ndarray], scale: float,
 
 
 def select_rounds(S: Sequence[float], strategy: int = ADAPTIVE, lam: float = 1.0, fraction: float = 0.10,
-                  threshold: float = 0.10, ddof: int = 0, min_rounds: int = 1, max_rounds: int = 0
-                  ) -> Tuple[List[int], dict]:
+                  threshold: float = 0.10, ddof: int = 0, min_rounds: int = 1, max_rounds: int = 0,
+                  keep_first: int = 0, keep_last: int = 0) -> Tuple[List[int], dict]:
     """Round selection (Sec. 3.3).  Plain Python floats (IEEE double), sums taken sequentially in
     round order, two passes for the variance.  Returns the ascending index list and a dict with
-    the cut value and the relative distance of the closest score to it."""
+    the cut value and the relative distance of the closest score to it.
+
+    keep_first / keep_last are not in the paper: an optional policy that always keeps the first
+    and the most recent rounds.  The rule (statistics, min_rounds, max_rounds) is applied to all
+    rounds exactly as without them; the forced rounds are then added to what the rule kept."""
     S = [float(x) for x in S]
     R = len(S)
     if R == 0:
@@ -151,7 +155,8 @@ def select_rounds(S: Sequence[float], strategy: int = ADAPTIVE, lam: float = 1.0
     if max_rounds > 0:
         n_keep = min(n_keep, max_rounds)
     n_keep = min(n_keep, R)
-    sel = sorted(order[:n_keep])
+    forced = [r for r in range(R) if r < keep_first or r >= R - keep_last]
+    sel = sorted(set(order[:n_keep]) | set(forced))
     margin = None
     if cut is not None and cut != 0.0:
         margin = min(abs(x - cut) for x in S) / abs(cut)
@@ -159,6 +164,36 @@ def select_rounds(S: Sequence[float], strategy: int = ADAPTIVE, lam: float = 1.0
         a, b = S[order[n_keep - 1]], S[order[n_keep]]
         margin = (a - b) / a if a != 0.0 else 0.0
     return sel, {"cut": cut, "margin": margin, "n_pass": n_pass}
+
+
+def mean_kl_to_later_layers(P) -> np.ndarray:
+    """Curve that locates the watershed layer (Sec. 3.1, Observation 2; Fig. 2b).  P [L][R] holds one
+    round distribution per layer; entry l of the result (l = 0 .. L-2) is the mean over the later
+    layers l' > l of KL(P^l || P^l') = sum_r P^l_r ln(P^l_r / P^l'_r), natural logarithm, with the
+    usual conventions: a term with P^l_r = 0 is 0, a term with P^l_r > 0 = P^l'_r is +inf."""
+    P = _f64(P)
+    L, R = P.shape
+    out = np.zeros(max(L - 1, 0))
+    for l in range(L - 1):
+        total = 0.0
+        for l2 in range(l + 1, L):
+            kl = 0.0
+            for r in range(R):
+                p, q = float(P[l, r]), float(P[l2, r])
+                if p > 0.0:
+                    kl += math.inf if q <= 0.0 else p * math.log(p / q)
+            total += kl
+        out[l] = total / (L - 1 - l)
+    return out
+
+
+def selection_coverage(S: Sequence[float], sel: Sequence[int]) -> float:
+    """Share of a round distribution that falls on the selected rounds (drift monitor for a long
+    answer: S is the distribution of the answer tokens so far, Eq. 1 right-hand form)."""
+    total = 0.0
+    for r in sorted(int(x) for x in sel):
+        total += float(S[r])
+    return total
 
 
 def sparse_attention(q, k_rounds: Sequence[np.ndarray], v_rounds: Sequence[np.ndarray], sel: Sequence[int],

@@ -317,3 +317,66 @@ def test_memory_ratio_matches_eq2_and_table5():
             assert abs(ratio - (Lw / L + (K / T) * (1 - Lw / L))) < 1e-12, name
         saving = 1.0 - memory_model.resident_kv_bytes(lens, [], L, Lw, bpt) / memory_model.full_kv_bytes(lens, L, bpt)
         assert int(math.floor(100 * saving + 0.5)) == pct, name
+
+
+# ---- watershed curve, forced rounds, coverage -----------------------------------------------------
+def test_mean_kl_closed_forms_and_direction():
+    P = np.array([[0.5, 0.5], [0.25, 0.75], [0.5, 0.5]])
+    out = ra.mean_kl_to_later_layers(P)
+    kl01 = 0.5 * math.log(4.0 / 3.0)                       # KL([1/2,1/2] || [1/4,3/4])
+    kl12 = 0.25 * math.log(0.5) + 0.75 * math.log(1.5)     # KL([1/4,3/4] || [1/2,1/2]): the other direction
+    assert abs(kl01 - 0.14384103622589045) < 1e-15 and abs(kl12 - 0.13081203594113694) < 1e-15
+    assert np.allclose(out, [(kl01 + 0.0) / 2, kl12], rtol=1e-14, atol=0)
+    # identical layers: zero; uniform target: ln R minus the entropy
+    assert np.all(ra.mean_kl_to_later_layers(np.tile([0.2, 0.3, 0.5], (4, 1))) == 0.0)
+    p = np.array([0.1, 0.2, 0.3, 0.4])
+    H = -(p * np.log(p)).sum()
+    assert abs(ra.mean_kl_to_later_layers(np.stack([p, np.full(4, 0.25)]))[0] - (math.log(4) - H)) < 1e-15
+    # conventions at zero
+    assert ra.mean_kl_to_later_layers(np.array([[0.0, 1.0], [0.5, 0.5]]))[0] == math.log(2.0)
+    assert ra.mean_kl_to_later_layers(np.array([[0.5, 0.5], [0.0, 1.0]]))[0] == math.inf
+
+
+def test_mean_kl_against_library_relative_entropy():
+    from scipy.special import rel_entr
+    rng = np.random.default_rng(11)
+    P = rng.random((6, 37))
+    P /= P.sum(axis=1, keepdims=True)
+    want = [np.mean([rel_entr(P[l], P[m]).sum() for m in range(l + 1, 6)]) for l in range(5)]
+    assert np.allclose(ra.mean_kl_to_later_layers(P), want, rtol=1e-12, atol=0)
+
+
+def test_forced_rounds_join_the_rule_selection():
+    S = [0.05, 0.30, 0.05, 0.05, 0.40, 0.05, 0.05, 0.05]
+    base, info = ra.select_rounds(S, lam=1.0)
+    assert base == [1, 4]
+    sel, info2 = ra.select_rounds(S, lam=1.0, keep_first=1, keep_last=2)
+    assert sel == [0, 1, 4, 6, 7] and info2["cut"] == info["cut"]      # the rule itself is unchanged
+    assert ra.select_rounds(S, lam=1.0, keep_first=2)[0] == [0, 1, 4]  # a forced round that the rule kept anyway
+    assert ra.select_rounds(S, lam=1.0, max_rounds=1, keep_last=1)[0] == [4, 7]   # the cap binds the rule only
+    assert ra.select_rounds(S, lam=1.0, keep_first=5, keep_last=5)[0] == list(range(8))
+    assert abs(ra.selection_coverage(S, [1, 4]) - 0.70) < 1e-15
+    assert ra.selection_coverage(S, []) == 0.0
+
+
+def test_answer_tokens_one_at_a_time_sum_to_eq1_right():
+    """Eq. 1, right-hand form: the answer tokens' masses add up token by token.  Token t of the answer
+    sees the history and the first c0 + t + 1 tokens of the current round; brute-force softmax per token."""
+    rng = np.random.default_rng(5)
+    Hq, Hkv, d, c0, T = 4, 2, 8, 3, 5
+    lens = [4, 1, 6]
+    k_rounds = [rng.standard_normal((n, Hkv, d)) for n in lens]
+    cur = rng.standard_normal((c0 + T, Hkv, d))
+    qa = rng.standard_normal((T, Hq, d))
+    scale = 0.3
+    P, S = ra.round_scores(qa, k_rounds, scale, cur)
+    acc = np.zeros((Hq, len(lens)))
+    for t in range(T):
+        for h in range(Hq):
+            g = h // (Hq // Hkv)
+            e_rounds = [sum(math.exp(scale * float(qa[t, h] @ k[j, g])) for j in range(k.shape[0])) for k in k_rounds]
+            e_cur = sum(math.exp(scale * float(qa[t, h] @ cur[j, g])) for j in range(c0 + t + 1))
+            z = sum(e_rounds) + e_cur
+            acc[h] += np.array(e_rounds) / z
+    assert np.allclose(P, acc / acc.sum(axis=1, keepdims=True), rtol=1e-12, atol=0)
+    assert np.allclose(S, (acc / acc.sum(axis=1, keepdims=True)).mean(axis=0), rtol=1e-12, atol=0)
