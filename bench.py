@@ -64,6 +64,9 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="cfg5 only: measure the key bias alpha in {0.5, 1, 2, 4} x lambda in {0, 0.5, 1} (kept fraction "
                          "from about 5 to 60 %%) and print one JSON line with a `sweep` table instead of the usual line")
+    ap.add_argument("--monitor", action="store_true",
+                    help="time the statistics beside the hot path (answer re-scoring, selection coverage, watershed curve) "
+                         "on cfg2 and cfg5; prints one JSON line with a `monitor` list")
     ap.add_argument("--watershed", action="store_true",
                     help="measure the watershed layer (decode: cfg2, cfg5; question prefill: cfg3): score pass + dense attention as two calls "
                          "against the fused call; prints one JSON line with a `watershed_layer` list")
@@ -524,6 +527,49 @@ def bench_long_context(steps, warmup, lam, order_name):
     return res, w
 
 
+def bench_monitor(name, steps, warmup, n_layers):
+    """The statistics beside the hot path: re-scoring of each decode token into the answer's running round
+    distribution (against the plain score pass), the coverage of the selection, and the watershed curve over
+    `n_layers` layers' score vectors."""
+    import torch
+    import paper_2502_15294_amd as ra
+    from synth import make_workload
+    from synth.device import Engine, device_view, to_device
+
+    w = make_workload(name, cur_len=64)
+    eng = Engine(w)
+    view = device_view(w, 0, with_v=False, threads=16)
+    q = to_device(w.q(0), w.dtype)
+    ck = to_device(w.cur_k(0), w.dtype)
+    P = torch.empty((w.B, w.Hq, view.R_max), dtype=torch.float32, device="cuda")
+    S = torch.empty((w.B, view.R_max), dtype=torch.float32, device="cuda")
+    acc = torch.zeros((w.B, w.Hq, view.R_max), dtype=torch.float32, device="cuda")
+    sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, ra.ra_round_scores(eng.ctx, q, view, scale=w.scale)[1], view.n_rounds,
+                                         ra.make_select_params(lam=0.0))
+    layers = torch.rand((n_layers, w.B, view.R_max), device="cuda") + 0.01
+    layers /= layers.sum(dim=2, keepdim=True)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    res = {"workload": f"{name}: {WORKLOADS[name]}, 64 tokens in the current round",
+           "round_scores_ms": timed(lambda: ra.ra_round_scores(eng.ctx, q, view, scale=w.scale, scores_head=P, scores=S)),
+           "round_scores_accumulate_ms": timed(lambda: ra.ra_round_scores_accumulate(eng.ctx, q, view, acc, cur_k=ck, scale=w.scale,
+                                                                                     scores_head=P, scores=S)),
+           "selection_coverage_ms": timed(lambda: ra.ra_selection_coverage(eng.ctx, S, sel_idx, n_sel)),
+           "layer_divergence_layers": n_layers,
+           "layer_divergence_ms": timed(lambda: ra.ra_layer_divergence(eng.ctx, layers, view.n_rounds))}
+    eng.close()
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -549,6 +595,11 @@ def main():
         rows = [bench_watershed("cfg2", 200, 20), bench_watershed("cfg5", 20, 3), bench_watershed("cfg3", 20, 3)]
         print(json.dumps({"metric": METRIC, "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
                           "watershed_layer": rows}))
+        return
+    if args.monitor:
+        rows = [bench_monitor("cfg2", 200, 20, 36), bench_monitor("cfg5", 20, 3, 28)]
+        print(json.dumps({"metric": METRIC, "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+                          "monitor": rows}))
         return
     if args.sweep:
         table = []

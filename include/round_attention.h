@@ -82,6 +82,10 @@ typedef struct ra_select_params {
                            0.0 gives the "greater than the average" rule of Sec. 4.4)            */
     double fraction;    /* TOP_FRACTION: keep the ceil(fraction * R) best rounds (paper: 0.10)   */
     double threshold;   /* THRESHOLD: keep score > threshold (paper: v = 0.1)                    */
+    int32_t keep_first; /* optional policy, not the paper's: the first keep_first rounds and ...  */
+    int32_t keep_last;  /* ... the most recent keep_last rounds are added to what the rule kept;
+                           the rule (statistics, min_rounds, max_rounds) is applied to all rounds
+                           as without them.  0 = off.                                            */
 } ra_select_params;
 
 /* One layer's round-indexed KV cache.  All pointers are device pointers. */
@@ -156,6 +160,21 @@ int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
                     const void* cur_k, int cur_len, float scale, float* scores_head, float* scores);
 
 /*
+ * Eq. 1, right-hand form (aAtt): the round masses of the answer tokens, added up as the answer is
+ * generated.  Same computation and arguments as ra_round_scores, except that the query tokens'
+ * un-normalised round masses (each token's softmax taken over the history and the keys of the
+ * current round it sees) are first added to `acc`, and scores_head / scores are the normalised
+ * running totals.  Called once per decode step with q_len = 1 and the grown cur_k / cur_len, after
+ * T steps acc holds sum_i sum_{j in round k} Att(a_i, K_j) over the T answer tokens, exactly what one
+ * ra_round_scores call with q_len = T would normalise.  With a single query token the current
+ * round's keys ARE read here (their share no longer cancels).
+ *   acc   device float [B][Hq][R_max], in/out; the caller zeroes it at the start of the answer
+ */
+int ra_round_scores_accumulate(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
+                               const ra_kv_view* watershed, const void* cur_k, int cur_len, float scale,
+                               float* acc, float* scores_head, float* scores);
+
+/*
  * Round selection (Sec. 3.3).  Per sequence, from scores[b][0 .. n_rounds[b]):
  *   ADAPTIVE      keep r with score > mean + lambda * std   (mean/std in double, summed in round order)
  *   TOP_FRACTION  keep the ceil(fraction * R) highest
@@ -227,6 +246,31 @@ int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const void* q, int q
                                  const ra_kv_view* layer, const int32_t* sel_idx, const int32_t* n_sel,
                                  const void* cur_k, const void* cur_v, int cur_len, float scale, float* out,
                                  float* lse);
+
+/*
+ * Sec. 3.1, Observation 2 and Fig. 2b: the curve whose drop marks the watershed layer.  For each
+ * layer l = 0 .. L-2 and each sequence, the mean over the later layers l' > l of
+ * KL(P^l || P^l') = sum_r P^l_r ln(P^l_r / P^l'_r) (natural logarithm; a round with P^l_r = 0 adds
+ * nothing, P^l'_r = 0 < P^l_r gives +inf), computed in double.
+ *   p         device float [L][B][R_max]: per layer the `scores` output of ra_round_scores
+ *   n_rounds  device int32 [B]
+ *   kl        device double [B][L-1]
+ *   kl_mean   device double [L-1] or NULL: mean of kl over the sequences (the plotted curve)
+ * The paper reads L_w off the plot; no rule is given, so none is applied here.
+ */
+int ra_layer_divergence(ra_ctx* ctx, void* stream, const float* p, const int32_t* n_rounds, int L, int B,
+                        int R_max, double* kl, double* kl_mean);
+
+/*
+ * Share of a round distribution that falls on a selection: coverage[b] = sum over the selected
+ * rounds of scores[b][r].  With the running answer distribution of ra_round_scores_accumulate it
+ * tells how much of the answer's attention the rounds chosen from the question still cover
+ * (Sec. 3.1, Observation 1 is the claim that this stays high).
+ *   scores device float [B][R_max]; sel_idx device int32 [B][R_max]; n_sel device int32 [B];
+ *   coverage device float [B]
+ */
+int ra_selection_coverage(ra_ctx* ctx, void* stream, const float* scores, const int32_t* sel_idx,
+                          const int32_t* n_sel, int B, int R_max, float* coverage);
 
 /* ------------------------------------------------------------------------------------------
  * Round-indexed KV store for the post-watershed layers (Sec. 3.2: "u_m" lives in host memory as

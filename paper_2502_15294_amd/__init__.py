@@ -33,6 +33,7 @@ EXPORTS = [
     "ra_kv_store_stage", "ra_kv_store_wait_layer", "ra_kv_store_layer_view", "ra_kv_store_stats",
     "ra_kv_store_release", "ra_kv_store_save_round", "ra_kv_store_save_wait", "ra_kv_store_round_activity",
     "ra_kv_store_drop_round", "ra_kv_store_drop_inactive",
+    "ra_round_scores_accumulate", "ra_layer_divergence", "ra_selection_coverage",
 ]
 
 
@@ -44,7 +45,8 @@ class RaError(RuntimeError):
 
 class ra_select_params(C.Structure):
     _fields_ = [("strategy", C.c_int32), ("ddof", C.c_int32), ("min_rounds", C.c_int32), ("max_rounds", C.c_int32),
-                ("lambda_", C.c_double), ("fraction", C.c_double), ("threshold", C.c_double)]
+                ("lambda_", C.c_double), ("fraction", C.c_double), ("threshold", C.c_double),
+                ("keep_first", C.c_int32), ("keep_last", C.c_int32)]
 
 
 class ra_kv_view(C.Structure):
@@ -87,6 +89,13 @@ def lib() -> C.CDLL:
         L.ra_profile_last_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.ra_round_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(ra_kv_view),
                                       C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p]
+        L.ra_round_scores_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                                 C.POINTER(ra_kv_view), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
+                                                 C.c_void_p, C.c_void_p]
+        L.ra_layer_divergence.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                          C.c_void_p, C.c_void_p]
+        L.ra_selection_coverage.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                            C.c_int, C.c_void_p]
         L.ra_select_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                        C.POINTER(ra_select_params), C.c_void_p, C.c_void_p]
         L.ra_round_sparse_attn_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(ra_kv_view),
@@ -231,11 +240,51 @@ def ra_round_scores(ctx, q: torch.Tensor, view: KVView, cur_k: Optional[torch.Te
     return scores_head, scores
 
 
+def ra_round_scores_accumulate(ctx, q: torch.Tensor, view: KVView, acc: torch.Tensor,
+                               cur_k: Optional[torch.Tensor] = None, scale: Optional[float] = None,
+                               scores_head: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                               stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """acc: float32 [B, Hq, R_max], updated in place; returns the normalised running totals."""
+    B, q_len, Hq, d = q.shape
+    assert acc.dtype == torch.float32 and tuple(acc.shape) == (B, Hq, view.R_max)
+    if scale is None:
+        scale = d ** -0.5
+    if scores_head is None:
+        scores_head = torch.empty((B, Hq, view.R_max), dtype=torch.float32, device=q.device)
+    if scores is None:
+        scores = torch.empty((B, view.R_max), dtype=torch.float32, device=q.device)
+    cur_len = 0 if cur_k is None else cur_k.shape[1]
+    _check(lib().ra_round_scores_accumulate(ctx, _stream(stream), _ptr(q), q_len, Hq, C.byref(view.c), _ptr(cur_k),
+                                            cur_len, scale, _ptr(acc), _ptr(scores_head), _ptr(scores)))
+    return scores_head, scores
+
+
+def ra_layer_divergence(ctx, p: torch.Tensor, n_rounds: torch.Tensor, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """p: float32 [L, B, R_max] -> (kl float64 [B, L-1], its mean over the sequences [L-1])."""
+    L, B, R_max = p.shape
+    assert p.dtype == torch.float32
+    kl = torch.empty((B, L - 1), dtype=torch.float64, device=p.device)
+    kl_mean = torch.empty((L - 1,), dtype=torch.float64, device=p.device)
+    _check(lib().ra_layer_divergence(ctx, _stream(stream), _ptr(p), _ptr(n_rounds), L, B, R_max, _ptr(kl),
+                                     _ptr(kl_mean)))
+    return kl, kl_mean
+
+
+def ra_selection_coverage(ctx, scores: torch.Tensor, sel_idx: torch.Tensor, n_sel: torch.Tensor, stream=None
+                          ) -> torch.Tensor:
+    B, R_max = scores.shape
+    cov = torch.empty((B,), dtype=torch.float32, device=scores.device)
+    _check(lib().ra_selection_coverage(ctx, _stream(stream), _ptr(scores), _ptr(sel_idx), _ptr(n_sel), B, R_max,
+                                       _ptr(cov)))
+    return cov
+
+
 def make_select_params(strategy: int = RA_SEL_ADAPTIVE, lam: float = 1.0, fraction: float = 0.10,
-                       threshold: float = 0.10, ddof: int = 0, min_rounds: int = 1, max_rounds: int = 0
-                       ) -> ra_select_params:
+                       threshold: float = 0.10, ddof: int = 0, min_rounds: int = 1, max_rounds: int = 0,
+                       keep_first: int = 0, keep_last: int = 0) -> ra_select_params:
     return ra_select_params(strategy=strategy, ddof=ddof, min_rounds=min_rounds, max_rounds=max_rounds,
-                            lambda_=lam, fraction=fraction, threshold=threshold)
+                            lambda_=lam, fraction=fraction, threshold=threshold, keep_first=keep_first,
+                            keep_last=keep_last)
 
 
 def ra_select_rounds(ctx, scores: torch.Tensor, n_rounds: torch.Tensor, params: Optional[ra_select_params] = None,

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libround_attention.so")
-SOURCES = ["context.hip", "decode.hip", "attn_mfma.hip", "attn_prefill_mfma.hip", "scores.hip", "scores_mfma.hip", "scores_prefill_mfma.hip", "select.hip", "prefill.hip", "kv_store.hip"]
+SOURCES = ["context.hip", "decode.hip", "attn_mfma.hip", "attn_prefill_mfma.hip", "scores.hip", "scores_mfma.hip", "scores_prefill_mfma.hip", "select.hip", "prefill.hip", "kv_store.hip", "monitor.hip"]
 # packed-fp32 instruction selection is switched off for every device translation unit
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -261,6 +261,17 @@ __global__ __launch_bounds__(W * 64) void scores_finish_kernel(FinishArgs a, boo
 #pragma unroll
             for (int k = 0; k < KPL; ++k) qatt[k] = __builtin_fmaf(e[k], inv, qatt[k]);
         }
+        if (a.acc && !overflow) {
+#pragma unroll
+            for (int k = 0; k < KPL; ++k) {
+                const int r = lane + 64 * k;
+                if (r < R) {
+                    float* slot = a.acc + ((size_t)b * a.Hq + h) * a.R_max + r;
+                    qatt[k] += *slot;
+                    *slot = qatt[k];
+                }
+            }
+        }
         float tot = 0.f;
 #pragma unroll
         for (int k = 0; k < KPL; ++k) tot += qatt[k];
@@ -370,7 +381,7 @@ __global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_rows_kernel(F
 // wave, wave + 16, ... and a lane the rounds lane, lane + 64, ..., so all sums run in a fixed order.
 constexpr int kHeadsWaves = 16;
 __global__ __launch_bounds__(kHeadsWaves * 64) void scores_heads_kernel(const float* p_part, int Z, int R_max, int Hq,
-                                                                        float* p_out, float* s_out) {
+                                                                        float* p_out, float* s_out, float* acc) {
     extern __shared__ __align__(16) char smem[];
     float* sacc = reinterpret_cast<float*>(smem);  // [kHeadsWaves][R_max]
     constexpr int KPL = kMaxRounds / 64;
@@ -387,6 +398,11 @@ __global__ __launch_bounds__(kHeadsWaves * 64) void scores_heads_kernel(const fl
             tot[k] = 0.f;
             if (r < R_max)
                 for (int z = 0; z < Z; ++z) tot[k] += ph[(size_t)z * R_max + r];
+            if (acc && r < R_max && tot[k] == tot[k]) {  // (an undersized pass leaves the running masses alone)
+                float* slot = acc + ((size_t)b * Hq + h) * R_max + r;
+                tot[k] += *slot;
+                *slot = tot[k];
+            }
             all += tot[k];
         }
         all = wave_sum(all);
@@ -458,7 +474,7 @@ void launch_scores_finish_rows(const FinishArgs& f, int B, float* p_part, int Z,
         hipLaunchKernelGGL((scores_finish_rows_kernel<kMaxRounds / 64>), fgrid, fin_block, smem, st, f, p_part,
                            stage_rows);
     hipLaunchKernelGGL(scores_heads_kernel, dim3(B), dim3(kHeadsWaves * 64), (size_t)kHeadsWaves * R_max * sizeof(float),
-                       st, p_part, Z, R_max, Hq, f.p_out, f.s_out);
+                       st, p_part, Z, R_max, Hq, f.p_out, f.s_out, f.acc);
 }
 
 // One query token: the finishing kernel for B sequences (a.q_len must be 1).
@@ -486,9 +502,8 @@ void launch_scores_finish_single(const FinishArgs& f, int B, hipStream_t st) {
 }
 }  // namespace ra
 
-extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
-                               const ra_kv_view* watershed, const void* cur_k, int cur_len, float scale,
-                               float* scores_head, float* scores) {
+static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq, const ra_kv_view* watershed,
+                       const void* cur_k, int cur_len, float scale, float* acc, float* scores_head, float* scores) {
     RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "round_scores: ctx is NULL");
     RA_REQUIRE(q != nullptr && scores != nullptr, RA_ERR_INVALID_ARG, "round_scores: q or scores is NULL");
     if (int rc = check_view(watershed, false, "round_scores")) return rc;
@@ -506,8 +521,9 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     RA_REQUIRE((int64_t)B * q_len <= 65535, RA_ERR_UNSUPPORTED, "round_scores: B * q_len exceeds 65535");
 
     // With a single query token the current round's share of the softmax cancels in the
-    // normalisation over history rounds, so its keys need not be read at all.
-    const bool use_cur = cur_k != nullptr && q_len > 1;
+    // normalisation over history rounds, so its keys need not be read at all -- unless the masses are
+    // added to those of other tokens, each with its own share.
+    const bool use_cur = cur_k != nullptr && (q_len > 1 || acc != nullptr);
     const bool mfma = watershed->dtype == RA_BF16 && D == 128;
     const int chunk_tokens = kChunkTokens;
     const int64_t nc64 = watershed->max_tokens / chunk_tokens + R_max + (use_cur ? (cur_len + chunk_tokens - 1) / chunk_tokens : 0);
@@ -575,10 +591,24 @@ extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_l
     f.has_cur = use_cur;
     f.p_out = scores_head;
     f.s_out = scores;
+    f.acc = acc;
     if (q_len > 1)
         launch_scores_finish_rows(f, B, reinterpret_cast<float*>(ctx->ws.base + kWsReserved + part_bytes), Z, st);
     else
         launch_scores_finish_single(f, B, st);
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
+}
+
+extern "C" int ra_round_scores(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
+                               const ra_kv_view* watershed, const void* cur_k, int cur_len, float scale,
+                               float* scores_head, float* scores) {
+    return scores_impl(ctx, stream, q, q_len, Hq, watershed, cur_k, cur_len, scale, nullptr, scores_head, scores);
+}
+
+extern "C" int ra_round_scores_accumulate(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
+                                          const ra_kv_view* watershed, const void* cur_k, int cur_len, float scale,
+                                          float* acc, float* scores_head, float* scores) {
+    RA_REQUIRE(acc != nullptr, RA_ERR_INVALID_ARG, "round_scores_accumulate: acc is NULL");
+    return scores_impl(ctx, stream, q, q_len, Hq, watershed, cur_k, cur_len, scale, acc, scores_head, scores);
 }

@@ -31,6 +31,8 @@ struct FinishArgs {
     bool has_cur;
     float* p_out;  // may be null
     float* s_out;
+    float* acc = nullptr;  // [B][Hq][R_max] running round masses of earlier calls (Eq. 1 over a growing set of
+                           // query tokens): added to this call's masses before normalising, then updated
 };
 void launch_scores_finish_single(const FinishArgs& f, int B, hipStream_t st);
 int scores_finish_splits(int q_len, int B, int Hq);  // Z of launch_scores_finish_rows

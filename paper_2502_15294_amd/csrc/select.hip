@@ -5,6 +5,8 @@
 //   TOP_FRACTION          n = ceil(fraction * R)
 // then n is clamped by min_rounds / max_rounds.  Ranks are found by counting in LDS, the kept rounds
 // are compacted in ascending order with wavefront ballots and a prefix over the four waves.
+// keep_first / keep_last (an optional policy, not the paper's) add the first and the most recent
+// rounds to whatever the rule kept; the rule itself is evaluated as without them.
 #include "common.hpp"
 
 namespace ra {
@@ -86,7 +88,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
                 const float y = s[j];
                 rank += (y > x || (y == x && j < r)) ? 1 : 0;
             }
-            keep = rank < n_keep;
+            keep = rank < n_keep || r < a.p.keep_first || r >= R - a.p.keep_last;
         }
         const unsigned long long mask = __ballot(keep);
         if (lane == 0) wave_cnt[wave] = __popcll(mask);
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
         base += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
         __syncthreads();
     }
-    if (tid == 0) a.n_sel[b] = n_keep;
+    if (tid == 0) a.n_sel[b] = base;
 }
 
 }  // namespace ra
@@ -114,6 +116,8 @@ extern "C" int ra_select_rounds(ra_ctx* ctx, void* stream, const float* scores, 
                "select_rounds: unknown strategy %d", params->strategy);
     RA_REQUIRE(params->min_rounds >= 0 && params->max_rounds >= 0 && params->ddof >= 0, RA_ERR_INVALID_ARG,
                "select_rounds: min_rounds, max_rounds and ddof must be non-negative");
+    RA_REQUIRE(params->keep_first >= 0 && params->keep_last >= 0, RA_ERR_INVALID_ARG,
+               "select_rounds: keep_first and keep_last must be non-negative");
     RA_REQUIRE(params->lambda == params->lambda && params->fraction == params->fraction &&
                    params->threshold == params->threshold,
                RA_ERR_INVALID_ARG, "select_rounds: NaN parameter");

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_the_header_layout():
-    assert C.sizeof(ra.ra_select_params) == 40
+    assert C.sizeof(ra.ra_select_params) == 48
     assert C.sizeof(ra.ra_kv_view) == 7 * 8 + 8 * 4 + 8
     assert C.sizeof(ra.ra_problem) == 8 * 4 + 8
     assert C.sizeof(ra.ra_store_cfg) == 8 * 4 + 8
@@ -55,6 +55,10 @@ def test_null_arguments_are_rejected_before_any_launch():
                                        None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_round_sparse_attn_prefill(None, None, None, 1, 4, C.byref(view), None, None, None, None, 0, 1.0,
                                           None, None) != ra.RA_OK
+    assert L.ra_round_scores_accumulate(None, None, None, 1, 4, C.byref(view), None, 0, 1.0, None, None,
+                                        None) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_layer_divergence(None, None, None, None, 2, 1, 8, None, None) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_selection_coverage(None, None, None, None, None, 1, 8, None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_set_workspace(None, None, 0) == ra.RA_ERR_INVALID_ARG
     assert L.ra_profile_kernels(None, 1) == ra.RA_ERR_INVALID_ARG
     assert L.ra_profile_last_ms(None, None) == ra.RA_ERR_INVALID_ARG

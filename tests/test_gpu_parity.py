@@ -169,6 +169,9 @@ SELECT_PARAMS = [
     dict(strategy=ora.TOP_FRACTION, fraction=0.33),
     dict(strategy=ora.THRESHOLD),
     dict(strategy=ora.THRESHOLD, threshold=0.02, min_rounds=0),
+    dict(strategy=ora.ADAPTIVE, keep_first=1, keep_last=2),
+    dict(strategy=ora.ADAPTIVE, lam=2.0, max_rounds=3, keep_last=70),
+    dict(strategy=ora.TOP_FRACTION, fraction=0.05, keep_first=300),
 ]
 
 
@@ -194,7 +197,8 @@ def test_select_function_parity_is_bit_exact(pi):
     p = ra.make_select_params(strategy=params["strategy"], lam=params.get("lam", 1.0),
                               fraction=params.get("fraction", 0.10), threshold=params.get("threshold", 0.10),
                               ddof=params.get("ddof", 0), min_rounds=params.get("min_rounds", 1),
-                              max_rounds=params.get("max_rounds", 0))
+                              max_rounds=params.get("max_rounds", 0), keep_first=params.get("keep_first", 0),
+                              keep_last=params.get("keep_last", 0))
     sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, torch.from_numpy(S).cuda(), torch.from_numpy(n_rounds).cuda(), p)
     torch.cuda.synchronize()
     sel_idx, n_sel = sel_idx.cpu().numpy(), n_sel.cpu().numpy()
