@@ -212,6 +212,25 @@ def bench_step(name, steps, warmup, lam, alpha, replicas):
             attend(v1)
             kern_ms[1].append(ra.ra_profile_last_ms(eng.ctx))
         ra.ra_profile_kernels(eng.ctx, False)
+        # The paper's comparison (Sec. 4.3, Fig. 3: Round Attention against dense attention), at the level of one
+        # post-watershed layer's attention call: all rounds against the selected ones, same kernel, same inputs.
+        def wall(fn):
+            for i in range(warmup):
+                fn(reps[i % n_rep][1])
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                fn(reps[i % n_rep][1])
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps * 1e3
+
+        def attend_dense(v1):
+            if prefill:
+                ra.ra_round_sparse_attn_prefill(eng.ctx, q1, v1, None, None, ck1, cv1, scale=w.scale, out=out, lse=lse)
+            else:
+                ra.ra_round_sparse_attn_decode(eng.ctx, q1, v1, None, None, ck1, cv1, cl1, scale=w.scale, out=out, lse=lse)
+
+        dense_ms, sparse_ms = wall(attend_dense), wall(attend)
         many_rows = w.q_len * (w.Hq // w.Hkv) > 16
         mfma = w.dtype == "bf16" and w.d == 128
         scores_kernel = ("scores_prefill_mfma_kernel" if many_rows else "scores_mfma_kernel") if mfma else "scores_stream_kernel"
@@ -245,6 +264,12 @@ def bench_step(name, steps, warmup, lam, alpha, replicas):
                        "step": f"ra_round_scores -> ra_select_rounds -> {attn_name}"},
             "roofline": _roofline(groups, dom, prefill, w, hist_tokens, sel_tokens),
             "kernel_groups": groups,
+            "dense_comparison": {"dense_attention_ms": dense_ms, "round_sparse_attention_ms": sparse_ms,
+                                 "attention_speedup": dense_ms / sparse_ms,
+                                 "step_with_scoring_vs_dense": dense_ms / (total / steps * 1e3),
+                                 "note": "one post-watershed layer: attention over all rounds against attention over the "
+                                         "selected rounds (the score pass and the selection run once per question, "
+                                         "not per layer or per decoded token)"},
             "input_generation_s": t_gen,
         }
         return res
@@ -632,6 +657,7 @@ def main():
         # target of the decode kernel is measured on the large paged workload (8.5 GB of KV)
         big, _ = bench_step("cfg5", 20, 3, 0.0, None, 0)
         result["large_workload"] = {"config": big["config"], "kernel_groups": big["kernel_groups"],
+                                    "dense_comparison": big["dense_comparison"],
                                     "ms_per_step": big["ms_per_step"], "tokens/s": big["value"],
                                     "roofline": big["roofline"],
                                     "decode_frac_of_hbm_peak": big["kernel_groups"]["ra_round_sparse_attn_decode"]["GB/s"] / HBM_PEAK_GBS,
