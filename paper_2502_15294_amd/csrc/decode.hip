@@ -411,8 +411,9 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
     RA_REQUIRE(!with_scores || n_tiles64 <= (int64_t)1 << 24, RA_ERR_UNSUPPORTED, "watershed decode: max_tokens too large");
     const int n_tiles_max = (int)n_tiles64;
     const size_t tile_bytes = with_scores ? align_up(rows * n_tiles_max * sizeof(float), 256) : 0;
-    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total + tile_bytes, RA_ERR_WORKSPACE,
-               "decode: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total + tile_bytes);
+    const size_t p_bytes = with_scores ? scores_finish_part_bytes(1, B, Hq, layer->R_max, n_tiles_max) : 0;
+    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total + tile_bytes + p_bytes, RA_ERR_WORKSPACE,
+               "decode: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total + tile_bytes + p_bytes);
 
     AttnArgs a;
     a.view = to_dev(layer);
@@ -478,7 +479,7 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
         f.has_cur = false;
         f.p_out = scores_head;
         f.s_out = scores;
-        launch_scores_finish_single(f, B, st);
+        launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + w.total + tile_bytes), st);
     }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;

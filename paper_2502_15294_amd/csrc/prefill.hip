@@ -43,9 +43,8 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
     const int64_t n_tiles64 = layer->max_tokens / 32 + layer->R_max + cur_len / 32 + 1;
     RA_REQUIRE(!with_scores || n_tiles64 <= (int64_t)1 << 24, RA_ERR_UNSUPPORTED, "watershed prefill: max_tokens too large");
     const int n_tiles_max = (int)n_tiles64;
-    const int Z = scores_finish_splits(q_len, B, Hq);
     const size_t tile_bytes = with_scores ? align_up(rows * n_tiles_max * sizeof(float), 256) : 0;
-    const size_t p_bytes = with_scores && q_len > 1 ? align_up((size_t)B * Hq * Z * layer->R_max * sizeof(float), 256) : 0;
+    const size_t p_bytes = with_scores ? scores_finish_part_bytes(q_len, B, Hq, layer->R_max, n_tiles_max) : 0;
     RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total + tile_bytes + p_bytes, RA_ERR_WORKSPACE,
                "prefill: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total + tile_bytes + p_bytes);
 
@@ -104,10 +103,7 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
         f.chunk_tokens = 32;
         f.p_out = scores_head;
         f.s_out = scores;
-        if (q_len > 1)
-            launch_scores_finish_rows(f, B, reinterpret_cast<float*>(ctx->ws.base + w.total + tile_bytes), Z, st);
-        else
-            launch_scores_finish_single(f, B, st);
+        launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + w.total + tile_bytes), st);
     }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;

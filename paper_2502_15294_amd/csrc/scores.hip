@@ -500,6 +500,12 @@ void launch_scores_finish_single(const FinishArgs& f, int B, hipStream_t st) {
         hipLaunchKernelGGL((scores_finish_kernel<kMaxRounds / 64, kFinishWaves>), dim3(B), fin_block, smem, st, f,
                            stage_rows);
 }
+void launch_scores_finish(const FinishArgs& f, int B, float* p_part, hipStream_t st) {
+    if (scores_finish_by_rows(f.q_len, f.Hq, f.n_chunks_max))
+        launch_scores_finish_rows(f, B, p_part, scores_finish_splits(f.q_len, B, f.Hq), st);
+    else
+        launch_scores_finish_single(f, B, st);
+}
 }  // namespace ra
 
 static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq, const ra_kv_view* watershed,
@@ -531,9 +537,8 @@ static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int 
     const int n_chunks_max = (int)(nc64 < 1 ? 1 : nc64);
     const size_t rows = (size_t)B * Hq * q_len;
     const size_t part_bytes = align_up(rows * n_chunks_max * sizeof(float), 256);
-    // several query tokens: Z workgroups per head leave partial round masses in a buffer
-    const int Z = scores_finish_splits(q_len, B, Hq);
-    const size_t p_bytes = q_len > 1 ? align_up((size_t)B * Hq * Z * R_max * sizeof(float), 256) : 0;
+    // several query tokens (or many chunks): Z workgroups per head leave partial round masses in a buffer
+    const size_t p_bytes = scores_finish_part_bytes(q_len, B, Hq, R_max, n_chunks_max);
     // more than 16 query rows per KV head on the matrix cores: persistent kernel driven by segment tables
     const bool many_rows = mfma && q_len * G > 16;
     const size_t plan_bytes = many_rows ? align_up((size_t)B * plan_stride(R_max + 1), 256) : 0;
@@ -592,10 +597,7 @@ static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int 
     f.p_out = scores_head;
     f.s_out = scores;
     f.acc = acc;
-    if (q_len > 1)
-        launch_scores_finish_rows(f, B, reinterpret_cast<float*>(ctx->ws.base + kWsReserved + part_bytes), Z, st);
-    else
-        launch_scores_finish_single(f, B, st);
+    launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + kWsReserved + part_bytes), st);
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
 }

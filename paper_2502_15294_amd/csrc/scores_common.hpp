@@ -37,6 +37,18 @@ struct FinishArgs {
 void launch_scores_finish_single(const FinishArgs& f, int B, hipStream_t st);
 int scores_finish_splits(int q_len, int B, int Hq);  // Z of launch_scores_finish_rows
 void launch_scores_finish_rows(const FinishArgs& f, int B, float* p_part, int Z, hipStream_t st);
+// Whether the finishing pass runs as one workgroup per (sequence, head, split) plus a head-mean kernel (several
+// query tokens, or one token whose heads have many partial values to fold) rather than one workgroup per sequence.
+inline bool scores_finish_by_rows(int q_len, int Hq, int n_chunks_max) {
+    return q_len > 1 || (int64_t)Hq * n_chunks_max >= 16384;
+}
+// Bytes of the partial round masses the by-rows pass needs ([B][Hq][Z][R_max] floats), 0 for the other pass.
+inline size_t scores_finish_part_bytes(int q_len, int B, int Hq, int R_max, int n_chunks_max) {
+    if (!scores_finish_by_rows(q_len, Hq, n_chunks_max)) return 0;
+    return ((size_t)B * Hq * scores_finish_splits(q_len, B, Hq) * R_max * sizeof(float) + 255) & ~(size_t)255;
+}
+// Picks the pass; p_part must hold scores_finish_part_bytes() bytes when that is not 0.
+void launch_scores_finish(const FinishArgs& f, int B, float* p_part, hipStream_t st);
 
 __device__ __forceinline__ int chunks_of(int len, int chunk_tokens = kChunkTokens) {
     return (len + chunk_tokens - 1) / chunk_tokens;

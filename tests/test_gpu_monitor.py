@@ -25,6 +25,8 @@ ACC_CASES = [
     ("bf16_many_rows", ("cfg3", dict(B=2, R=5, q_len=48, cur_len=50, length=("uniform", 40, 400))), 2, [24, 24]),
     ("bf16_many_rounds", ("cfg5", dict(B=2, R=150, q_len=3, cur_len=3, length=("uniform", 1, 40), block_size=0)), 0,
      [1, 1, 1]),
+    ("bf16_finish_head_by_head", ("cfg5", dict(B=2, R=300, q_len=2, cur_len=5, length=("uniform", 1, 40), block_size=0)), 3,
+     [1, 1]),
 ]
 
 

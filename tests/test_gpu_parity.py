@@ -129,6 +129,9 @@ SCORE_CASES = {
     "bf16_qlen3_cur": ("cfg2", dict(B=2, R=5, q_len=3, cur_len=9, length=("uniform", 10, 150))),
     "bf16_qlen4_nocur": ("cfg2", dict(B=2, R=5, q_len=4, cur_len=0, length=("uniform", 10, 150))),
     "bf16_qlen1_cur_cancels": ("cfg2", dict(B=2, R=5, q_len=1, cur_len=6, length=("uniform", 10, 150))),
+    # one query token, 64 heads x more than 256 partial values each: finished head by head, then averaged
+    "bf16_g8_many_chunks": ("cfg5", dict(B=2, R=300, block_size=0, length=("uniform", 1, 40))),
+    "bf16_g8_many_chunks_paged": ("cfg5", dict(B=3, R=270, length=("uniform", 1, 40))),
 }
 
 
@@ -528,6 +531,7 @@ WATERSHED_CASES = {
     "bf16_uneven_round_counts": ("cfg2", dict(B=3, lens=[[30, 40], [10, 20, 30, 40, 50], [700]])),
     "bf16_many_rounds": ("cfg2", dict(B=2, R=300, length=("uniform", 1, 40))),
     "bf16_cfg2_full": ("cfg2", dict()),
+    "bf16_g8_many_tiles": ("cfg5", dict(B=2, R=300, block_size=0, length=("uniform", 1, 40))),
 }
 
 
