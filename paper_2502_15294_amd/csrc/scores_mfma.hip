@@ -37,18 +37,26 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     constexpr int NT = 1, RB = 16;
 
     // ---- which round does chunk c belong to? -------------------------------------------------------
-    const int n_hist = min(max(vw.n_rounds[b], 0), vw.R_max);
-    const int n_slots = n_hist + (a.cur_k && a.cur_len > 0 ? 1 : 0);
     const int cap = vw.R_max + 1;
     long long* t_off = reinterpret_cast<long long*>(smem);
     int* t_len = reinterpret_cast<int*>(t_off + cap);
     int* t_cum = t_len + cap;
+    // The first 256 table entries are asked for before the round count has arrived (entries past it are
+    // dropped): one memory round trip instead of two at the start of every workgroup.
+    int len0 = 0;
+    long long off0 = 0;
+    if (tid < vw.R_max) {
+        len0 = vw.seg_len[(size_t)b * vw.R_max + tid];
+        off0 = vw.seg_off[(size_t)b * vw.R_max + tid];
+    }
+    const int n_hist = min(max(vw.n_rounds[b], 0), vw.R_max);
+    const int n_slots = n_hist + (a.cur_k && a.cur_len > 0 ? 1 : 0);
     for (int s = tid; s < n_slots; s += 256) {
         int len = a.cur_len;
         long long off = 0;
         if (s < n_hist) {
-            len = max(vw.seg_len[(size_t)b * vw.R_max + s], 0);
-            off = vw.seg_off[(size_t)b * vw.R_max + s];
+            len = max(s < 256 ? len0 : vw.seg_len[(size_t)b * vw.R_max + s], 0);
+            off = s < 256 ? off0 : vw.seg_off[(size_t)b * vw.R_max + s];
         }
         t_len[s] = len;
         t_off[s] = off;
