@@ -38,7 +38,9 @@ struct KVTile {
     uint2 v[8][2];  // [dt][half]: tokens 4*(lane/16) .. +3 of that half, channel dt*16 + lane%16
 };
 
-template <bool PAGED, bool TILE_LSE>
+// TILE_LSE: 0 = attention only; 1 = also one log-sum-exp per (query row, key tile), stored as it is produced;
+// 2 = the same, staged in LDS and written out in blocks of 64 tiles (pays when a piece has many tiles).
+template <bool PAGED, int TILE_LSE>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
@@ -56,6 +58,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
     SlotTable tab;
     tab.carve(smem, cap);
     float* red = reinterpret_cast<float*>(smem + ((SlotTable::bytes(cap) + 15) & ~(size_t)15));
+    constexpr int kLsePitch = 65, kLseBlock = 16 * kLsePitch;
+    float* lse_buf = red + 128;  // [2][16][65] tile log-sum-exps on their way out; reused by the merge afterwards
 
     // ---- the batch's schedule, identical in every workgroup --------------------------------------------
     const int inner = Hkv * n_rowblocks;  // work items per piece
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                     for (int i = 0; i < 4; ++i) p[h * 4 + i] = fast_exp2(__builtin_fmaf(sc[h][i], a.c, -mc));
                 const float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
                 l[nt] += ps;
-                if constexpr (TILE_LSE) {  // the tile's share of the softmax normaliser: the round scores' raw material
+                if constexpr (TILE_LSE == 1) {  // the tile's share of the softmax normaliser: the round scores' raw material
                     const float pt = xrow_sum4(ps);
                     if (q4 == 0 && row_ok[nt] && u_seq < a.n_tiles_max) {
                         // row order of the score pass: [B][Hq][q_len]
@@ -219,6 +223,14 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                         a.tile_lse[srow * a.n_tiles_max + u_seq] =
                             pt > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(pt)) : -__builtin_inff();
                     }
+                } else if constexpr (TILE_LSE == 2) {
+                    // Staged in LDS, [2 blocks of 64 tiles][16 rows][64 + 1]; flush_tile_lse writes a block out in
+                    // whole runs per row (one scattered 4-byte store per row and tile costs 14 % of a long pass).
+                    const float pt = xrow_sum4(ps);
+                    const int ut = u_seq - u_lo;
+                    if (q4 == 0)
+                        lse_buf[((ut >> 6) & 1) * kLseBlock + n * kLsePitch + (ut & 63)] =
+                            pt > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(pt)) : -__builtin_inff();
                 }
                 uint4 phi, plo;
                 phi.x = pack_trunc(p[0], p[1]);
@@ -235,6 +247,23 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                     acc[nt][dt] = mfma16(vf, phi, acc[nt][dt]);
                     acc[nt][dt] = mfma16(vf, plo, acc[nt][dt]);
                 }
+            }
+        };
+
+        // Block k of the staged tile log-sum-exps (tiles u_lo + 64 k ...) to tile_lse, rows in the score pass's
+        // order [B][Hq][q_len]: 16 consecutive lanes write 16 consecutive tiles of one row.
+        auto flush_tile_lse = [&](int k) {
+            const int r = tid >> 4, rr = rowblock * RB + r;
+            if (rr >= rows_total) return;
+            const int qt = rr / G;
+            const size_t head = (size_t)g * G + (rr - qt * G);
+            float* dst = a.tile_lse + (((size_t)b * a.Hq + head) * q_len + qt) * a.n_tiles_max;
+            const float* src = lse_buf + (k & 1) * kLseBlock + r * kLsePitch;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int col = (tid & 15) + 16 * i;
+                const int ut = u_lo + 64 * k + col;
+                if (ut < u_hi && ut < a.n_tiles_max) dst[ut] = src[col];
             }
         };
 
@@ -255,6 +284,42 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                 us_a = u;
                 issue(uin_a, slot, ta, len_a, cur_a);
             }
+            if constexpr (TILE_LSE == 2) {
+                // Same walk, but with a trip count every wave shares (a pair of tiles per wave and trip, eight
+                // tiles per workgroup), so that the workgroup can meet at a barrier after each block of 64 tiles
+                // and write that block out while the next one is computed into the other half of the buffer.
+                const int n_trips = (u_hi - u_lo + 7) >> 3;
+                for (int trip = 0; trip < n_trips; ++trip) {
+                    if (have) {
+                        u += step;
+                        const bool have_b = u < u_hi;
+                        if (have_b) {
+                            while (u >= tab.cum[slot + 1]) ++slot;
+                            uin_b = u - tab.cum[slot];
+                            us_b = u;
+                            issue(uin_b, slot, tb, len_b, cur_b);
+                        }
+                        consume(ta, uin_a, len_a, cur_a, us_a);
+                        have = false;
+                        if (have_b) {
+                            u += step;
+                            have = u < u_hi;
+                            if (have) {
+                                while (u >= tab.cum[slot + 1]) ++slot;
+                                uin_a = u - tab.cum[slot];
+                                us_a = u;
+                                issue(uin_a, slot, ta, len_a, cur_a);
+                            }
+                            consume(tb, uin_b, len_b, cur_b, us_b);
+                        }
+                    }
+                    if ((trip & 7) == 7 || trip == n_trips - 1) {
+                        __syncthreads();  // every wave's values of this block are in LDS
+                        flush_tile_lse(trip >> 3);
+                    }
+                }
+                __syncthreads();  // the staging buffer shares its memory with the merge below
+            } else
             while (have) {
                 u += step;
                 const bool have_b = u < u_hi;
@@ -350,15 +415,25 @@ int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) 
     if (grid < 1) grid = 1;
     const size_t smem = tab_bytes + (128 + 4 * 16 * 128) * sizeof(float);
     if (a.tile_lse) {
-        if (paged)
-            RA_LAUNCH_TIMED((attn_mfma_kernel<true, true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        // tiles a piece is expected to hold: a sequence's tiles over the pieces it gets when the work is spread
+        // over the grid (at most S)
+        const long long tiles_seq = a.max_tokens / kTile + 1;
+        long long pieces_seq = grid * kPiecesPerWorkgroup / ((long long)B * Hkv * n_rowblocks);
+        pieces_seq = pieces_seq < 1 ? 1 : (pieces_seq > a.S ? a.S : pieces_seq);
+        const bool staged = tiles_seq / pieces_seq >= 128;
+        if (paged && staged)
+            RA_LAUNCH_TIMED((attn_mfma_kernel<true, 2>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        else if (paged)
+            RA_LAUNCH_TIMED((attn_mfma_kernel<true, 1>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+        else if (staged)
+            RA_LAUNCH_TIMED((attn_mfma_kernel<false, 2>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
         else
-            RA_LAUNCH_TIMED((attn_mfma_kernel<false, true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+            RA_LAUNCH_TIMED((attn_mfma_kernel<false, 1>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
     } else {
         if (paged)
-            RA_LAUNCH_TIMED((attn_mfma_kernel<true, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+            RA_LAUNCH_TIMED((attn_mfma_kernel<true, 0>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
         else
-            RA_LAUNCH_TIMED((attn_mfma_kernel<false, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+            RA_LAUNCH_TIMED((attn_mfma_kernel<false, 0>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
     }
     return RA_OK;
 }

@@ -47,6 +47,32 @@ def test_config5_full_size_paged_decode_sampled_sequences():
     eng.close()
 
 
+@pytest.mark.parametrize("block_size", [16, 0], ids=["paged", "contiguous"])
+def test_config5_full_size_watershed_decode_with_scores_sampled_sequences(block_size):
+    """Dense decode attention with the round scores from the same pass at the size where the per-tile
+    log-sum-exps go out in staged blocks; attention and scores of sampled sequences against the oracle, the
+    scores of every sequence against the stand-alone score pass."""
+    w = make_workload("cfg5", block_size=block_size)
+    eng = Engine(w)
+    v1 = device_view(w, 1, threads=16)
+    q = to_device(w.q(1), w.dtype)
+    out, _, P, S = ra.ra_watershed_attn_decode(eng.ctx, q[:, 0].contiguous(), v1, scale=w.scale)
+    P2, S2 = ra.ra_round_scores(eng.ctx, q, v1, scale=w.scale)
+    torch.cuda.synchronize()
+    assert (S - S2).abs().max().item() < SCORE_TOL and (P - P2).abs().max().item() < SCORE_TOL
+    out, S = out.cpu().numpy(), S.cpu().numpy()
+    for b in (3, 62):
+        R = w.n_rounds(b)
+        ks = [w.k_round(b, 1, r) for r in range(R)]
+        vs = [w.v_round(b, 1, r) for r in range(R)]
+        _, Sr = ora.round_scores(w.q(1)[b], ks, w.scale)
+        ro, _ = ora.sparse_attention(w.q(1)[b], ks, vs, list(range(R)), w.scale)
+        err = ora.row_error(out[b], ro[0])
+        _say(f"  seq {b}: dense row error {err:.2e}, score error {np.abs(S[b, :R] - Sr).max():.2e}")
+        assert np.abs(S[b, :R] - Sr).max() < SCORE_TOL and err < STREAM_TOL
+    eng.close()
+
+
 @pytest.mark.parametrize("alpha", [0.5, 1.0, 4.0])
 def test_config5_bias_sweep_reduced_batch(alpha):
     """The kept fraction is swept by the bias strength (and by lambda); every point must match the oracle."""

@@ -535,15 +535,23 @@ WATERSHED_CASES = {
 }
 
 
+@pytest.mark.parametrize("staged", [False, True], ids=["direct", "staged"])
 @pytest.mark.parametrize("name", list(WATERSHED_CASES))
-def test_watershed_decode_attention_and_scores_match_oracle(name):
+def test_watershed_decode_attention_and_scores_match_oracle(name, staged):
     """Dense decode attention at the watershed layer with the round scores from the same pass: both against the
     oracle, the scores also against the stand-alone score pass, the output bitwise against the plain decode call."""
     cfg, over = WATERSHED_CASES[name]
     w = make_workload(cfg, **over)
     _say(f"watershed decode case {name}: B={w.B} R_max={w.R_max} cur_len={w.cur_len} block={w.block_size}")
-    eng = Engine(w)
+    # A generous bound on the history length makes the library expect long pieces and write the per-tile
+    # values out in staged blocks; with the true bound it stores them one by one.
+    extra = (1 << 20) if staged else 0
+    eng = Engine(w, extra_tokens=extra)
     view = device_view(w, 0)                      # watershed layer with values
+    if staged:
+        k, v, seg_off, seg_len, n_rounds, bt, seg_off_v = view.tensors
+        view = ra.KVView(k, v, seg_off, seg_len, n_rounds, view.Hkv, view.d, view.c.max_tokens + extra,
+                         block_table=bt, block_size=view.c.block_size, seg_off_v=seg_off_v)
     q = to_device(w.q(0)[:, 0], w.dtype)
     ck = to_device(w.cur_k(0), w.dtype) if w.cur_len else None
     cv = to_device(w.cur_v(0), w.dtype) if w.cur_len else None
