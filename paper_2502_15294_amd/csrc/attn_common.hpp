@@ -60,6 +60,11 @@ int attn_min_units();  // tuning knob (environment RA_ATTN_MIN_UNITS), default 8
 int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st);
 // Same operands, many query rows per KV head: the waves own different rows and share key tiles through LDS.
 int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st);
+// Small batches: the 16-row matrix-core kernel resolves the selection itself (every workgroup reads the whole
+// batch's segment lists in one memory round trip and builds its sequences' tables in LDS), so that no planning
+// kernel runs before it.
+inline bool attn_mfma_plans_inline(int B, int R_max) { return B <= 64 && (long long)B * R_max <= 1024; }
+inline size_t attn_mfma_inline_bytes(int B, int R_max) { return (size_t)B * R_max * 24 + (size_t)B * 12 + 16; }
 // Most pieces one sequence can be cut into by the matrix-core kernel (row length of the piece buffers).
 inline int mfma_max_pieces(int64_t max_tokens, int min_units, int cap) {
     int64_t s = max_tokens / (32 * (int64_t)min_units);

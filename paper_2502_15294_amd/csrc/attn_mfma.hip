@@ -40,7 +40,8 @@ struct KVTile {
 
 // TILE_LSE: 0 = attention only; 1 = also one log-sum-exp per (query row, key tile), stored as it is produced;
 // 2 = the same, staged in LDS and written out in blocks of 64 tiles (pays when a piece has many tiles).
-template <bool PAGED, int TILE_LSE>
+// INLINE_PLAN: the workgroup resolves the batch's selections itself instead of reading the planning kernel's tables.
+template <bool PAGED, int TILE_LSE, bool INLINE_PLAN>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
@@ -64,7 +65,59 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
     // ---- the batch's schedule, identical in every workgroup --------------------------------------------
     const int inner = Hkv * n_rowblocks;  // work items per piece
     const long long slots = ((long long)gridDim.x * kPiecesPerWorkgroup + inner - 1) / inner;
-    const int P = build_schedule(a.plan, cap, vw.B, a.S, a.min_units, slots, sU, sps);
+    // Without a planning kernel: the raw segment lists of the whole batch, by round index, in LDS.
+    const int BR = vw.B * vw.R_max;
+    long long* raw_ok = reinterpret_cast<long long*>(red + 128 + 4 * 16 * 128);  // [B][R_max]
+    long long* raw_ov = raw_ok + BR;
+    int* raw_len = reinterpret_cast<int*>(raw_ov + BR);
+    int* raw_sel = raw_len + BR;
+    int* meta = raw_sel + BR;  // [B][3]: rounds of the sequence, listed rounds, length of the current round
+    // Segment i of sequence b's table, as the planning kernel defines it: the i-th listed round (entries that are
+    // not rounds of the sequence count as empty), then the current round.
+    auto plan_entry = [&](int b, int i, int& len, long long& ok, long long& ov) {
+        const int n_rounds = meta[3 * b], n_hist = meta[3 * b + 1], cur_len = meta[3 * b + 2];
+        len = 0;
+        ok = ov = 0;
+        if (i < n_hist) {
+            const int r = raw_sel[b * vw.R_max + i];
+            if (r >= 0 && r < n_rounds) {
+                len = max(raw_len[b * vw.R_max + r], 0);
+                ok = raw_ok[b * vw.R_max + r];
+                ov = raw_ov[b * vw.R_max + r];
+            }
+        } else if (i == n_hist && cur_len > 0) {
+            len = cur_len;
+        }
+    };
+    int P;
+    if constexpr (INLINE_PLAN) {
+        for (int idx = tid; idx < BR; idx += 256) {
+            raw_len[idx] = vw.seg_len[idx];
+            raw_ok[idx] = vw.seg_off[idx];
+            raw_ov[idx] = vw.seg_off_v[idx];
+            raw_sel[idx] = a.sel_idx ? a.sel_idx[idx] : idx % vw.R_max;
+        }
+        for (int b = tid; b < vw.B; b += 256) {
+            const int n_rounds = min(max(vw.n_rounds[b], 0), vw.R_max);
+            meta[3 * b] = n_rounds;
+            meta[3 * b + 1] = a.sel_idx ? min(max(a.n_sel[b], 0), vw.R_max) : n_rounds;
+            meta[3 * b + 2] = a.cur_k ? min(max(a.cur_len_dev ? a.cur_len_dev[b] : a.cur_len_host, 0), a.cur_cap) : 0;
+        }
+        __syncthreads();
+        for (int b = tid; b < vw.B; b += 256) {
+            int U = 0;
+            for (int i = 0; i <= meta[3 * b + 1]; ++i) {
+                int len;
+                long long ok, ov;
+                plan_entry(b, i, len, ok, ov);
+                U += (len + kTile - 1) / kTile;
+            }
+            sU[b] = U;
+        }
+        P = schedule_from_counts(vw.B, a.S, a.min_units, slots, sU, sps);
+    } else {
+        P = build_schedule(a.plan, cap, vw.B, a.S, a.min_units, slots, sU, sps);
+    }
     if (blockIdx.x == 0)
         for (int b = tid; b < vw.B; b += 256) a.n_parts[b] = sps[b + 1] - sps[b];
 
@@ -87,9 +140,26 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
         const int u_hi = (int)(((long long)U * (s + 1)) / S_eff);
 
         __syncthreads();  // the previous item's readers of tab / red are done
-        const PlanHeader hdr = load_plan(a.plan + (size_t)b * plan_stride(cap), cap, tab);
-        const int n_slots = hdr.n_slots, n_hist = hdr.n_hist;
-        __syncthreads();
+        int n_slots, n_hist;
+        if constexpr (INLINE_PLAN) {
+            n_hist = meta[3 * b + 1];
+            n_slots = n_hist + (meta[3 * b + 2] > 0 ? 1 : 0);
+            for (int i = tid; i < cap; i += 256) {
+                int len;
+                long long ok, ov;
+                plan_entry(b, i, len, ok, ov);
+                tab.len[i] = len;
+                tab.off_k[i] = ok;
+                tab.off_v[i] = ov;
+                tab.cum[i] = (len + kTile - 1) / kTile;
+            }
+            exclusive_scan_units(tab.cum, cap);
+        } else {
+            const PlanHeader hdr = load_plan(a.plan + (size_t)b * plan_stride(cap), cap, tab);
+            n_slots = hdr.n_slots;
+            n_hist = hdr.n_hist;
+            __syncthreads();
+        }
 
         RA_TS(2);
         // ---- this wave's query rows -------------------------------------------------------------------
@@ -413,28 +483,25 @@ int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) 
     long long grid = (long long)2 * num_cu;
     if (grid > max_pieces * Hkv * n_rowblocks) grid = max_pieces * Hkv * n_rowblocks;
     if (grid < 1) grid = 1;
-    const size_t smem = tab_bytes + (128 + 4 * 16 * 128) * sizeof(float);
-    if (a.tile_lse) {
-        // tiles a piece is expected to hold: a sequence's tiles over the pieces it gets when the work is spread
-        // over the grid (at most S)
-        const long long tiles_seq = a.max_tokens / kTile + 1;
-        long long pieces_seq = grid * kPiecesPerWorkgroup / ((long long)B * Hkv * n_rowblocks);
-        pieces_seq = pieces_seq < 1 ? 1 : (pieces_seq > a.S ? a.S : pieces_seq);
-        const bool staged = tiles_seq / pieces_seq >= 128;
-        if (paged && staged)
-            RA_LAUNCH_TIMED((attn_mfma_kernel<true, 2>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-        else if (paged)
-            RA_LAUNCH_TIMED((attn_mfma_kernel<true, 1>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-        else if (staged)
-            RA_LAUNCH_TIMED((attn_mfma_kernel<false, 2>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-        else
-            RA_LAUNCH_TIMED((attn_mfma_kernel<false, 1>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-    } else {
-        if (paged)
-            RA_LAUNCH_TIMED((attn_mfma_kernel<true, 0>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-        else
-            RA_LAUNCH_TIMED((attn_mfma_kernel<false, 0>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    const bool inline_plan = attn_mfma_plans_inline(B, a.view.R_max);
+    // tiles a piece is expected to hold: a sequence's tiles over the pieces it gets when the work is spread
+    // over the grid (at most S)
+    const long long tiles_seq = a.max_tokens / kTile + 1;
+    long long pieces_seq = grid * kPiecesPerWorkgroup / ((long long)B * Hkv * n_rowblocks);
+    pieces_seq = pieces_seq < 1 ? 1 : (pieces_seq > a.S ? a.S : pieces_seq);
+    const int lse_mode = !a.tile_lse ? 0 : (tiles_seq / pieces_seq >= 128 ? 2 : 1);
+    const size_t smem = tab_bytes + (128 + 4 * 16 * 128) * sizeof(float) +
+                        (inline_plan ? attn_mfma_inline_bytes(B, a.view.R_max) : 0);
+    const dim3 g((unsigned)grid), blk(256);
+#define RA_ATTN_CASE(P_, L_, I_)                                                                          \
+    if (paged == P_ && lse_mode == L_ && inline_plan == I_) {                                             \
+        RA_LAUNCH_TIMED((attn_mfma_kernel<P_, L_, I_>), g, blk, smem, st, a, n_rowblocks);                \
+        return RA_OK;                                                                                     \
     }
+    RA_ATTN_CASE(false, 0, false) RA_ATTN_CASE(false, 0, true) RA_ATTN_CASE(true, 0, false) RA_ATTN_CASE(true, 0, true)
+    RA_ATTN_CASE(false, 1, false) RA_ATTN_CASE(false, 1, true) RA_ATTN_CASE(true, 1, false) RA_ATTN_CASE(true, 1, true)
+    RA_ATTN_CASE(false, 2, false) RA_ATTN_CASE(false, 2, true) RA_ATTN_CASE(true, 2, false) RA_ATTN_CASE(true, 2, true)
+#undef RA_ATTN_CASE
     return RA_OK;
 }
 

@@ -446,7 +446,7 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool paged = layer->block_size != 0;
     int rc;
-    launch_plan(a, mfma ? 32 : kUnitTokens, st);
+    if (!(mfma && attn_mfma_plans_inline(B, layer->R_max))) launch_plan(a, mfma ? 32 : kUnitTokens, st);
     {
         KernelTimer timer(ctx, st);
         if (mfma) {

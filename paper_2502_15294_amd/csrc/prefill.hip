@@ -76,10 +76,10 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
     a.tile_lse = with_scores ? reinterpret_cast<float*>(ctx->ws.base + w.total) : nullptr;
     a.n_tiles_max = with_scores ? n_tiles_max : 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    launch_plan(a, 32, st);
     // Few query rows per KV head: the decode kernel's token split keeps all four waves busy; otherwise
     // the kernel whose waves own different rows and share each key tile through LDS.
     const bool few_rows = q_len * G <= 32;
+    if (!(few_rows && attn_mfma_plans_inline(B, layer->R_max))) launch_plan(a, 32, st);
     {
         KernelTimer timer(ctx, st);
         if (int rc = few_rows ? launch_attn_mfma(a, layer->block_size != 0, ctx->num_cu, st)
