@@ -102,17 +102,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             meta[3 * b] = n_rounds;
             meta[3 * b + 1] = a.sel_idx ? min(max(a.n_sel[b], 0), vw.R_max) : n_rounds;
             meta[3 * b + 2] = a.cur_k ? min(max(a.cur_len_dev ? a.cur_len_dev[b] : a.cur_len_host, 0), a.cur_cap) : 0;
+            sU[b] = 0;
         }
         __syncthreads();
-        for (int b = tid; b < vw.B; b += 256) {
-            int U = 0;
-            for (int i = 0; i <= meta[3 * b + 1]; ++i) {
-                int len;
-                long long ok, ov;
-                plan_entry(b, i, len, ok, ov);
-                U += (len + kTile - 1) / kTile;
-            }
-            sU[b] = U;
+        // work units of every sequence: one table entry per thread, integer adds in LDS (order does not matter)
+        for (int idx = tid; idx < vw.B * cap; idx += 256) {
+            const int b = idx / cap, i = idx - b * cap;
+            int len;
+            long long ok, ov;
+            plan_entry(b, i, len, ok, ov);
+            if (len > 0) atomicAdd(&sU[b], (len + kTile - 1) / kTile);
         }
         P = schedule_from_counts(vw.B, a.S, a.min_units, slots, sU, sps);
     } else {
