@@ -40,10 +40,10 @@ WORKLOADS = {
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled
 # by a copy kernel of known size); see profiles/.  None where no counter run has been recorded.
 MEASURED_TRAFFIC = {
-    ("cfg2", "ra_round_scores"): 199_779_636,
-    ("cfg2", "ra_round_sparse_attn_decode"): 50_349_465,
-    ("cfg5", "ra_round_scores"): 4_297_999_258,
-    ("cfg5", "ra_round_sparse_attn_decode"): 5_122_598_400,
+    ("cfg2", "ra_round_scores"): 199_785_267,
+    ("cfg2", "ra_round_sparse_attn_decode"): 50_413_773,
+    ("cfg5", "ra_round_scores"): 4_297_836_237,
+    ("cfg5", "ra_round_sparse_attn_decode"): 5_122_599_322,
 }
 
 
