@@ -228,7 +228,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(AttnArgs a) {
             mx = xrow_max4(mx);
             const float m_new = fmaxf(m[h], mx);
             const float mc = m_new * a.c;
-            const float alpha = fast_exp2(__builtin_fmaf(m[h], a.c, -mc));
+            const float alpha = fast_exp2((m[h] - m_new) * a.c);  // exactly 1 when the maximum did not move
             m[h] = m_new;
             float ps = 0.f;
 #pragma unroll

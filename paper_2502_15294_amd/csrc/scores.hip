@@ -139,7 +139,9 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(ScoreArgs a) {
                 float ps = 0.f;
 #pragma unroll
                 for (int t4 = 0; t4 < 4; ++t4) ps += fast_exp2(__builtin_fmaf(sc[t4][h], a.c, -mc));
-                l[h] = __builtin_fmaf(l[h], fast_exp2(__builtin_fmaf(m[h], a.c, -mc)), ps);
+                // (m - m_new) * c, not fma(m, c, -mc): a lane row that has seen no token yet keeps m = m_new = the
+                // finite stand-in, and the fused form would leave the rounding residue of its huge product in the exponent
+                l[h] = __builtin_fmaf(l[h], fast_exp2((m[h] - m_new) * a.c), ps);
                 m[h] = m_new;
             }
         }

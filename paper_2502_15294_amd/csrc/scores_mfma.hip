@@ -150,7 +150,9 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) ps += fast_exp2(__builtin_fmaf(sc[h][i], a.c, -mc));
-            l[nt] = __builtin_fmaf(l[nt], fast_exp2(__builtin_fmaf(m[nt], a.c, -mc)), ps);
+            // (m - m_new) * c, not fma(m, c, -mc): a lane that has seen no token yet keeps m = m_new = the finite
+            // stand-in, and the fused form would then leave the rounding residue of its huge product in the exponent
+            l[nt] = __builtin_fmaf(l[nt], fast_exp2((m[nt] - m_new) * a.c), ps);
             m[nt] = m_new;
         }
     };

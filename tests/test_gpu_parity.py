@@ -162,6 +162,25 @@ def _oracle_select_on(S_row, R, params):
     return ora.select_rounds([float(x) for x in S_row[:R]], **params)[0]
 
 
+@pytest.mark.parametrize("cfg,over", [("cfg2", dict(B=1)), ("cfg5", dict(B=1, block_size=0)),
+                                      ("cfg1", dict(B=1, Hq=4, Hkv=2)), ("cfg1", dict(B=1, Hq=8, Hkv=1))])
+@pytest.mark.parametrize("scale", [0.03, 0.05, 0.0884, 0.1, 0.125, 0.2, 0.31])
+def test_round_scores_with_lanes_that_see_no_token_at_any_scale(cfg, over, scale):
+    """Rounds of 1, 2, 17 or 33 tokens leave lane groups of the streaming kernels without a single token in the
+    first tile they process; their running maximum then stays at its finite stand-in and the rescaling factor must
+    come out as exactly one whatever the softmax scale is (a fused multiply-add of the stand-in once left its
+    rounding residue in the exponent, for some scales only)."""
+    w = make_workload(cfg, lens=[[1, 64, 2, 17, 33, 3, 16, 145]], **over)
+    eng = Engine(w)
+    view = device_view(w, 0, with_v=False)
+    P, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), view, scale=scale)
+    torch.cuda.synchronize()
+    ks = [w.k_round(0, 0, r) for r in range(w.n_rounds(0))]
+    rP, rS = ora.round_scores(w.q(0)[0], ks, scale)
+    assert np.abs(P[0].cpu().numpy() - rP).max() < SCORE_TOL and np.abs(S[0].cpu().numpy() - rS).max() < SCORE_TOL
+    eng.close()
+
+
 SELECT_PARAMS = [
     dict(strategy=ora.ADAPTIVE),
     dict(strategy=ora.ADAPTIVE, lam=0.0),
