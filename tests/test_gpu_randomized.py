@@ -16,7 +16,7 @@ OUT_TOL, STREAM_TOL, SCORE_TOL = 2e-3, 5e-5, 1e-5
 EDGE_LENS = [0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 255, 256, 257]
 
 
-def _draw_case(seed):
+def _draw_case(seed, max_rounds=12):
     rng = np.random.default_rng(7000 + seed)
     f32 = seed % 5 == 4                       # every fifth case on the generic fp32 / d = 64 kernels
     B = int(rng.integers(1, 5))
@@ -29,7 +29,7 @@ def _draw_case(seed):
     cur_len = q_len + int(rng.integers(0, 30)) if (prefill or rng.random() < 0.5) else 0
     lens = []
     for _ in range(B):
-        R = int(rng.integers(0, 13))
+        R = int(rng.integers(0, max_rounds + 1))
         lens.append([int(rng.choice(EDGE_LENS)) if rng.random() < 0.5 else int(rng.integers(1, 400)) for _ in range(R)])
     if max(len(l) for l in lens) == 0:
         lens[0] = [33]
@@ -104,4 +104,58 @@ def test_random_shape_whole_path(seed):
             if w.total_tokens(b) + w.cur_len:
                 ro, _ = pipeline.attention_for_sequence(w, b, 0, list(range(R)))
                 assert ora.row_error(o2[b] if prefill else o2[b][None], ro) < STREAM_TOL, b
+    eng.close()
+
+
+@pytest.mark.parametrize("seed", range(100, 130))
+def test_random_shape_random_softmax_scale_and_bias(seed):
+    """The same walk with a softmax scale drawn log-uniformly from [0.02, 0.4], a stronger or absent relevance
+    bias on the keys and up to 40 rounds: nothing in the kernels may depend on the scale being 1/sqrt(d)."""
+    base, over, sels, prefill = _draw_case(seed, max_rounds=40)
+    rng = np.random.default_rng(seed)
+    scale = float(np.exp(rng.uniform(np.log(0.02), np.log(0.4))))
+    over["alpha"] = float(rng.choice([0.0, 2.0, 6.0]))
+    w = make_workload(base, **over)
+    print(f"random case {seed}: scale={scale:.4f} {over} sels={sels}", flush=True)
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0), device_view(w, 1)
+    dev = lambda x: to_device(x, w.dtype) if x is not None else None
+    ck0, cv0, ck1, cv1 = dev(w.cur_k(0)), dev(w.cur_v(0)), dev(w.cur_k(1)), dev(w.cur_v(1))
+    cl = torch.full((w.B,), w.cur_len, dtype=torch.int32, device="cuda") if w.cur_len else None
+    P, S = ra.ra_round_scores(eng.ctx, dev(w.q(0)), v0, ck0, scale=scale)
+    si, ns = sel_to_device(sels, v1.R_max)
+    if prefill:
+        out, lse = ra.ra_round_sparse_attn_prefill(eng.ctx, dev(w.q(1)), v1, si, ns, ck1, cv1, scale=scale)
+        o2, _, _, S2 = ra.ra_watershed_attn_prefill(eng.ctx, dev(w.q(0)), v0, ck0, cv0, scale=scale)
+    else:
+        out, lse = ra.ra_round_sparse_attn_decode(eng.ctx, dev(w.q(1)[:, 0]), v1, si, ns, ck1, cv1, cl, scale=scale)
+        o2, S2 = None, None
+        if w.dtype == "bf16":
+            o2, _, _, S2 = ra.ra_watershed_attn_decode(eng.ctx, dev(w.q(0)[:, 0]), v0, ck0, cv0, cl, scale=scale)
+    torch.cuda.synchronize()
+    P, S, out, lse = P.cpu().numpy(), S.cpu().numpy(), out.cpu().numpy(), lse.cpu().numpy()
+    for b in range(w.B):
+        R = w.n_rounds(b)
+        cur = lambda layer, f: None if w.cur_len == 0 else f(layer)[b]
+        k0 = [w.k_round(b, 0, r) for r in range(R)]
+        if R:
+            rP, rS = ora.round_scores(w.q(0)[b], k0, scale, cur(0, w.cur_k))
+            assert np.abs(P[b, :, :R] - rP).max() < SCORE_TOL and np.abs(S[b, :R] - rS).max() < SCORE_TOL, b
+            if S2 is not None and w.total_tokens(b):
+                assert np.abs(S2[b, :R].cpu().numpy() - rS).max() < SCORE_TOL, b
+        go, gl = (out[b], lse[b]) if prefill else (out[b][None], lse[b][None])
+        if sum(int(w.lens[b][r]) for r in sels[b]) + w.cur_len == 0:
+            assert np.all(go == 0) and np.all(np.isneginf(gl)), b
+        else:
+            kr = [w.k_round(b, 1, r) if r in sels[b] else None for r in range(R)]
+            vr = [w.v_round(b, 1, r) if r in sels[b] else None for r in range(R)]
+            ro, rl = ora.sparse_attention(w.q(1)[b], kr, vr, sels[b], scale, cur(1, w.cur_k), cur(1, w.cur_v))
+            err = ora.row_error(go, ro)
+            assert err < OUT_TOL and err < STREAM_TOL, (b, err)
+            assert np.allclose(gl, rl, rtol=0, atol=2e-5 * max(1.0, np.abs(rl).max())), b
+        if o2 is not None and w.total_tokens(b) + w.cur_len:
+            v0r = [w.v_round(b, 0, r) for r in range(R)]
+            ro, _ = ora.sparse_attention(w.q(0)[b], k0, v0r, list(range(R)), scale, cur(0, w.cur_k), cur(0, w.cur_v))
+            g2 = o2[b].cpu().numpy()
+            assert ora.row_error(g2 if prefill else g2[None], ro) < STREAM_TOL, b
     eng.close()
