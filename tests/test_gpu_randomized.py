@@ -159,3 +159,51 @@ def test_random_shape_random_softmax_scale_and_bias(seed):
             g2 = o2[b].cpu().numpy()
             assert ora.row_error(g2 if prefill else g2[None], ro) < STREAM_TOL, b
     eng.close()
+
+
+@pytest.mark.parametrize("seed", range(200, 208))
+def test_random_many_sequences_decode(seed):
+    """Batches past the size up to which the decode kernel plans a batch by itself (B * R_max > 1024): the planning
+    kernel's tables, uneven round counts, short ragged rounds, random selections, per-sequence current lengths."""
+    rng = np.random.default_rng(seed)
+    B = int(rng.integers(20, 33))
+    G = int(rng.choice([1, 4, 8]))
+    lens = [[int(rng.choice(EDGE_LENS[:11])) if rng.random() < 0.4 else int(rng.integers(1, 90))
+             for _ in range(int(rng.integers(0, 61)))] for _ in range(B)]
+    lens[0] = [int(rng.integers(1, 90)) for _ in range(60)]          # R_max = 60 for certain
+    cur_cap = int(rng.choice([0, 24]))
+    w = make_workload("cfg2", B=B, Hq=8 * G, Hkv=8, q_len=1, cur_len=cur_cap, lens=lens,
+                      block_size=int(rng.choice([0, 16])), n_relevant=2)
+    assert w.B * w.R_max > 1024
+    sels = [sorted(rng.choice(len(l), size=int(rng.integers(0, len(l) + 1)), replace=False).tolist()) if l else []
+            for l in lens]
+    cur_lens = [int(rng.integers(0, cur_cap + 1)) for _ in range(B)] if cur_cap else [0] * B
+    print(f"many-sequence case {seed}: B={B} G={G} cur_cap={cur_cap} block={w.block_size}", flush=True)
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0, with_v=False), device_view(w, 1)
+    P, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, scale=w.scale)
+    si, ns = sel_to_device(sels, v1.R_max)
+    ck = to_device(w.cur_k(1), w.dtype) if cur_cap else None
+    cv = to_device(w.cur_v(1), w.dtype) if cur_cap else None
+    cl = torch.tensor(cur_lens, dtype=torch.int32, device="cuda") if cur_cap else None
+    out, lse = ra.ra_round_sparse_attn_decode(eng.ctx, to_device(w.q(1)[:, 0], w.dtype), v1, si, ns, ck, cv, cl,
+                                              scale=w.scale)
+    torch.cuda.synchronize()
+    S, out, lse = S.cpu().numpy(), out.cpu().numpy(), lse.cpu().numpy()
+    for b in range(B):
+        R = w.n_rounds(b)
+        if R:
+            _, rS = ora.round_scores(w.q(0)[b], [w.k_round(b, 0, r) for r in range(R)], w.scale)
+            assert np.abs(S[b, :R] - rS).max() < SCORE_TOL, b
+        n_cur = cur_lens[b]
+        if sum(int(w.lens[b][r]) for r in sels[b]) + n_cur == 0:
+            assert np.all(out[b] == 0) and np.all(np.isneginf(lse[b])), b
+            continue
+        kr = [w.k_round(b, 1, r) if r in sels[b] else None for r in range(R)]
+        vr = [w.v_round(b, 1, r) if r in sels[b] else None for r in range(R)]
+        ro, rl = ora.sparse_attention(w.q(1)[b], kr, vr, sels[b], w.scale,
+                                      w.cur_k(1)[b, :n_cur] if n_cur else None, w.cur_v(1)[b, :n_cur] if n_cur else None)
+        err = ora.row_error(out[b][None], ro)
+        assert err < OUT_TOL and err < STREAM_TOL, (b, err)
+        assert np.allclose(lse[b][None], rl, rtol=0, atol=2e-5 * max(1.0, np.abs(rl).max())), b
+    eng.close()
