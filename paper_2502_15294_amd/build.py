@@ -14,6 +14,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libround_attention.so")
+EXAMPLE_SRC = os.path.join(HERE, "examples", "decode_step.c")
+EXAMPLE = os.path.join(HERE, "ra_decode_step")  # plain C program driving the library through the C boundary alone
 SOURCES = ["context.hip", "decode.hip", "attn_mfma.hip", "attn_prefill_mfma.hip", "scores.hip", "scores_mfma.hip", "scores_prefill_mfma.hip", "select.hip", "prefill.hip", "kv_store.hip", "monitor.hip"]
 # packed-fp32 instruction selection is switched off for every device translation unit
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -50,7 +52,21 @@ def build(force: bool = True, jobs: int = 6) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr[-4000:]}")
+    build_example()
     return LIB
+
+
+def build_example() -> str:
+    """The C example, compiled as C11 by the host C compiler (it includes round_attention.h as C)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.environ.get("CC", "gcc"), "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"), EXAMPLE_SRC, "-o", EXAMPLE,
+           "-L", HERE, "-lround_attention", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"C example failed to build:\n{r.stderr[-4000:]}")
+    return EXAMPLE
 
 
 if __name__ == "__main__":

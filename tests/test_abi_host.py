@@ -71,3 +71,16 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert L.ra_kv_store_drop_round(None, 0, 0) == ra.RA_ERR_INVALID_ARG
     assert L.ra_kv_store_drop_inactive(None, 1, None, None) == ra.RA_ERR_INVALID_ARG
     assert b"NULL" in L.ra_last_error()
+
+
+def test_header_is_plain_c():
+    """round_attention.h declares a C boundary: a C11 compiler must accept it on its own, with all warnings on."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no host C compiler")
+    hdr = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "round_attention.h")
+    r = subprocess.run([gcc, "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c", hdr],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
