@@ -645,3 +645,50 @@ def test_watershed_prefill_attention_and_scores_match_oracle(name):
         ref_o, _ = pipeline.attention_for_sequence(w, b, 0, list(range(R)))
         assert ora.row_error(out[b], ref_o) < STREAM_TOL
     eng.close()
+
+
+def test_one_very_long_round_next_to_a_tiny_one():
+    """A single round of 100 000 tokens (thousands of tiles and hundreds of score chunks in one segment) beside
+    rounds of 7 and 1 tokens: scores, selection-free decode and a short question prefill."""
+    w = make_workload("cfg2", B=1, R=3, q_len=3, cur_len=5, lens=[[100000, 7, 1]])
+    _say(f"long-round case: tokens={w.total_tokens(0)}")
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0, with_v=False, threads=8), device_view(w, 1, threads=8)
+    ck0, ck1, cv1 = (to_device(x, w.dtype) for x in (w.cur_k(0), w.cur_k(1), w.cur_v(1)))
+    P, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, ck0, scale=w.scale)
+    po, pl = ra.ra_round_sparse_attn_prefill(eng.ctx, to_device(w.q(1), w.dtype), v1, None, None, ck1, cv1, scale=w.scale)
+    cl = torch.full((1,), w.cur_len, dtype=torch.int32, device="cuda")
+    do, dl = ra.ra_round_sparse_attn_decode(eng.ctx, to_device(w.q(1)[:, -1], w.dtype), v1, None, None, ck1, cv1, cl,
+                                            scale=w.scale)
+    torch.cuda.synchronize()
+    rP, rS = pipeline.scores_for_sequence(w, 0)
+    assert np.abs(P[0].cpu().numpy() - rP).max() < SCORE_TOL and np.abs(S[0].cpu().numpy() - rS).max() < SCORE_TOL
+    ro, rl = pipeline.attention_for_sequence(w, 0, 1, [0, 1, 2])
+    assert ora.row_error(po[0].cpu().numpy(), ro) < STREAM_TOL
+    assert np.allclose(pl[0].cpu().numpy(), rl, rtol=0, atol=2e-5 * np.abs(rl).max())
+    # the last question token sees the whole current round: the decode call must give the prefill's last row
+    assert ora.row_error(do[0].cpu().numpy()[None], ro[-1:]) < STREAM_TOL
+    eng.close()
+
+
+def test_calls_on_a_side_stream_are_ordered_on_that_stream():
+    """Every compute call only enqueues on the caller's stream: a whole step issued on a non-default stream, with
+    the inputs produced on that stream just before, matches the oracle."""
+    w = make_workload("cfg2", B=2, R=6, length=("uniform", 20, 300))
+    eng = Engine(w)
+    v0, v1 = device_view(w, 0, with_v=False), device_view(w, 1)
+    q0_host, q1_host = to_device(w.q(0), w.dtype).cpu().pin_memory(), to_device(w.q(1)[:, 0], w.dtype).cpu().pin_memory()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        q0 = q0_host.to("cuda", non_blocking=True)        # the copies are ordered before the kernels on `side` only
+        q1 = q1_host.to("cuda", non_blocking=True)
+        P, S = ra.ra_round_scores(eng.ctx, q0, v0, scale=w.scale, stream=side)
+        sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, v0.n_rounds, ra.make_select_params(lam=0.5), stream=side)
+        out, lse = ra.ra_round_sparse_attn_decode(eng.ctx, q1, v1, sel_idx, n_sel, scale=w.scale, stream=side)
+    side.synchronize()
+    ref = pipeline.run(w, select_params=dict(lam=0.5))
+    for b, r in enumerate(ref):
+        assert sel_idx[b, :n_sel[b]].tolist() == r.sel
+        assert ora.row_error(out[b].cpu().numpy()[None], r.out[1]) < STREAM_TOL
+    eng.close()
