@@ -13,6 +13,12 @@
 //     the barrier that every wave passes once it has finished reading X.
 // The launch is persistent with the balanced schedule of the decode kernel; pieces are merged by the same
 // merge kernel.
+//
+// At the watershed layer the same pass also yields the round scores' raw material (TILE_LSE): one log-sum-exp
+// per (query row, 256-token chunk of a round), the unit of the stand-alone score pass.  A row's running sum is
+// never restarted for that: the chunk's share is the difference of the running sum between the chunk's ends (a
+// mark that is rescaled together with the sum), exact to a few ulp of the sum, i.e. far below the 1e-5 the
+// normalised scores are held to.  Pieces then begin and end on chunk boundaries, so that one piece owns a chunk.
 #include "attn_common.hpp"
 #include "mfma_util.hpp"
 #include "stream_kv.hpp"
@@ -49,6 +55,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
     SlotTable tab;
     tab.carve(smem, cap);
     char* tiles = smem + ((SlotTable::bytes(cap) + 15) & ~(size_t)15);  // two tile buffers
+    int* ccum = reinterpret_cast<int*>(tiles + 2 * kTileBytes);        // [cap + 1] chunk prefix (score output only)
 
     const int inner = Hkv * n_rowblocks;
     const long long slots = ((long long)gridDim.x * kPiecesPerWorkgroupP + inner - 1) / inner;
@@ -72,13 +79,26 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
         const int s = piece - sps[b];
         const int S_eff = sps[b + 1] - sps[b];
         const int U = sU[b];
-        const int u_lo = (int)(((long long)U * s) / S_eff);
-        const int u_hi = (int)(((long long)U * (s + 1)) / S_eff);
+        int u_lo = (int)(((long long)U * s) / S_eff);
+        int u_hi = (int)(((long long)U * (s + 1)) / S_eff);
 
         __syncthreads();  // the previous item's readers of the table and the tile buffers are done
         const PlanHeader hdr = load_plan(a.plan + (size_t)b * plan_stride(cap), cap, tab);
         const int n_slots = __builtin_amdgcn_readfirstlane(hdr.n_slots), n_hist = __builtin_amdgcn_readfirstlane(hdr.n_hist);
         __syncthreads();
+        if constexpr (TILE_LSE) {
+            // chunk prefix of the sequence's segments (a chunk = 256 tokens = 8 tiles, never crossing a segment)
+            for (int i = tid; i < cap; i += 256) ccum[i] = i < n_slots ? (tab.len[i] + 255) >> 8 : 0;
+            exclusive_scan_units(ccum, cap);
+            // a piece owns whole chunks: its ends move down to the chunk start at or before them
+            auto snap = [&](int u) {
+                if (u <= 0 || u >= U) return u <= 0 ? 0 : U;
+                const int sl = find_slot(tab.cum, n_slots, u);
+                return tab.cum[sl] + ((u - tab.cum[sl]) & ~7);
+            };
+            u_lo = __builtin_amdgcn_readfirstlane(snap(u_lo));
+            u_hi = __builtin_amdgcn_readfirstlane(snap(u_hi));
+        }
 
         // ---- this wave's query rows -------------------------------------------------------------------
         int qtok[kNTP];
@@ -98,11 +118,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
         }
         floatx4_t acc[kNTP][8];
         float m[kNTP], l[kNTP];
+        float l_mark[kNTP];  // the running sum as it stood at the start of the current chunk (score output only)
         const float slack = 16.f / a.c;
 #pragma unroll
         for (int nt = 0; nt < kNTP; ++nt) {
             m[nt] = kNegBig;
             l[nt] = 0.f;
+            l_mark[nt] = 0.f;
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) acc[nt][dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
         }
@@ -267,6 +289,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                     const float m_new = vmax(m[nt], r);
                     const float alpha = fast_exp2((m[nt] - m_new) * a.c);
                     l[nt] *= alpha;
+                    if constexpr (TILE_LSE) l_mark[nt] *= alpha;
 #pragma unroll
                     for (int dt = 0; dt < 8; ++dt) acc[nt][dt] *= alpha;
                     m[nt] = m_new;
@@ -287,16 +310,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                     for (int i = 0; i < 4; ++i) p[h * 4 + i] = fast_exp2(__builtin_fmaf(sc[nt][h][i], a.c, -mc));
                 const float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
                 l[nt] += ps;
-                if constexpr (TILE_LSE) {  // the tile's share of the softmax normaliser: the round scores' raw material
-                    const float pt = xrow_sum4(ps);
-                    if (q4 == 0 && row_ok[nt] && u_seq < a.n_tiles_max) {
-                        // row order of the score pass: [B][Hq][q_len]
-                        const size_t head = rowid[nt] - ((size_t)b * q_len + qtok[nt]) * a.Hq;
-                        const size_t srow = ((size_t)b * a.Hq + head) * q_len + qtok[nt];
-                        a.tile_lse[srow * a.n_tiles_max + u_seq] =
-                            pt > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(pt)) : -__builtin_inff();
-                    }
-                }
                 phi.x = pack_hi16(p[0], p[1]);
                 phi.y = pack_hi16(p[2], p[3]);
                 phi.z = pack_hi16(p[4], p[5]);
@@ -337,6 +350,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                 store_share(buf, sh);
                 const int len = seg_len, tok0 = c_tok0;  // of the tile just stored
                 const bool is_cur = seg_cur;
+                const int t_slot = slot, t_first = seg_first, t_end = seg_end;
                 __syncthreads();
                 RA_LAP(0);
                 if (u + 1 < u_hi) {
@@ -350,6 +364,24 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                 RA_LAP(1);
                 consume(buf, tok0, len, is_cur, u);
                 RA_LAP(5);
+                if constexpr (TILE_LSE) {
+                    const int uin = u - t_first;
+                    if ((uin & 7) == 7 || u + 1 == t_end || u + 1 == u_hi) {  // the chunk ends with this tile
+                        const int chunk = ccum[t_slot] + (uin >> 3);
+#pragma unroll
+                        for (int nt = 0; nt < kNTP; ++nt) {
+                            const float share = xrow_sum4(l[nt] - l_mark[nt]);
+                            l_mark[nt] = l[nt];
+                            if (q4 == 0 && row_ok[nt] && chunk < a.n_tiles_max) {
+                                // row order of the score pass: [B][Hq][q_len]
+                                const size_t head = rowid[nt] - ((size_t)b * q_len + qtok[nt]) * a.Hq;
+                                const size_t srow = ((size_t)b * a.Hq + head) * q_len + qtok[nt];
+                                a.tile_lse[srow * a.n_tiles_max + chunk] =
+                                    share > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(share)) : -__builtin_inff();
+                            }
+                        }
+                    }
+                }
                 bufsel ^= 1;
             }
         }
@@ -393,7 +425,8 @@ int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStrea
     if (a.G > 16) return fail(RA_ERR_UNSUPPORTED, "prefill: Hq / Hkv = %d exceeds 16", a.G);
     if (B > kMaxBatch) return fail(RA_ERR_UNSUPPORTED, "prefill: batch %d exceeds %d", B, kMaxBatch);
     const int n_rowblocks = (rows_total + kRowsPerItem - 1) / kRowsPerItem;
-    const size_t smem = align_up(SlotTable::bytes(a.view.R_max + 1), 16) + 2 * kTileBytes;
+    const size_t smem = align_up(SlotTable::bytes(a.view.R_max + 1), 16) + 2 * kTileBytes +
+                        (a.tile_lse ? (size_t)(a.view.R_max + 3) * sizeof(int) : 0);
     const long long max_tiles = (long long)B * (a.max_tokens / kTileP + a.view.R_max + 1 + a.cur_cap / kTileP + 1);
     long long max_pieces = (long long)B + max_tiles / a.min_units;
     if (max_pieces > (long long)B * a.S) max_pieces = (long long)B * a.S;

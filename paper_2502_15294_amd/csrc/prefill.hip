@@ -39,8 +39,13 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
     const AttnWorkspace w = attn_workspace(rows, S, D, B, layer->R_max);
     const bool with_scores = scores != nullptr;
     RA_REQUIRE(!with_scores || layer->R_max > 0, RA_ERR_INVALID_ARG, "watershed prefill: R_max is 0, there is nothing to score");
-    // one entry per 32-token tile of a sequence's table: history rounds (each rounded up), then the current round
-    const int64_t n_tiles64 = layer->max_tokens / 32 + layer->R_max + cur_len / 32 + 1;
+    // Few query rows per KV head: the decode kernel's token split keeps all four waves busy; otherwise
+    // the kernel whose waves own different rows and share each key tile through LDS.
+    const bool few_rows = q_len * G <= 32;
+    // score output: one entry per 32-token tile (decode kernel) or per 256-token chunk (many-row kernel) of a
+    // sequence's table: history rounds (each rounded up), then the current round
+    const int score_unit = few_rows ? 32 : 256;
+    const int64_t n_tiles64 = layer->max_tokens / score_unit + layer->R_max + cur_len / score_unit + 1;
     RA_REQUIRE(!with_scores || n_tiles64 <= (int64_t)1 << 24, RA_ERR_UNSUPPORTED, "watershed prefill: max_tokens too large");
     const int n_tiles_max = (int)n_tiles64;
     const size_t tile_bytes = with_scores ? align_up(rows * n_tiles_max * sizeof(float), 256) : 0;
@@ -76,9 +81,6 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
     a.tile_lse = with_scores ? reinterpret_cast<float*>(ctx->ws.base + w.total) : nullptr;
     a.n_tiles_max = with_scores ? n_tiles_max : 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    // Few query rows per KV head: the decode kernel's token split keeps all four waves busy; otherwise
-    // the kernel whose waves own different rows and share each key tile through LDS.
-    const bool few_rows = q_len * G <= 32;
     if (!(few_rows && attn_mfma_plans_inline(B, layer->R_max))) launch_plan(a, 32, st);
     {
         KernelTimer timer(ctx, st);
@@ -100,7 +102,7 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
         f.has_cur = cur_len > 0 && q_len > 1;
         f.cur_len = f.has_cur ? cur_len : 0;
         f.n_chunks_max = n_tiles_max;
-        f.chunk_tokens = 32;
+        f.chunk_tokens = score_unit;
         f.p_out = scores_head;
         f.s_out = scores;
         launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + w.total + tile_bytes), st);

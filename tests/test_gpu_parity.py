@@ -634,7 +634,13 @@ def test_watershed_prefill_attention_and_scores_match_oracle(name):
     out2, lse2 = ra.ra_round_sparse_attn_prefill(eng.ctx, q, view, None, None, ck, cv, scale=w.scale)
     P2, S2 = ra.ra_round_scores(eng.ctx, q, view, ck, scale=w.scale)
     torch.cuda.synchronize()
-    assert torch.equal(out, out2) and torch.equal(lse, lse2)
+    if w.q_len * w.G <= 32:
+        assert torch.equal(out, out2) and torch.equal(lse, lse2)          # same kernel, same pieces
+    else:
+        # the pieces of the fused pass end on 256-token chunk boundaries: other pieces, other softmax references,
+        # so the two results differ by the arithmetic's own error (both are held to the oracle below)
+        assert ora.row_error(out.cpu().numpy(), out2.cpu().numpy()) < STREAM_TOL
+        assert (lse - lse2).abs().max().item() < 2e-5
     out, P, S, P2, S2 = out.cpu().numpy(), P.cpu().numpy(), S.cpu().numpy(), P2.cpu().numpy(), S2.cpu().numpy()
     assert np.abs(P - P2).max() < SCORE_TOL and np.abs(S - S2).max() < SCORE_TOL
     for b in range(w.B):
