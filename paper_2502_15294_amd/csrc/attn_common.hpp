@@ -29,9 +29,9 @@ struct AttnArgs {
     char* plan;       // [B][plan_stride(R_max + 1)] per-sequence segment tables (see stream_kv.hpp)
     float* out;       // [rows][D]
     float* lse;       // [rows] or null
-    // decode at the watershed layer only: natural-log sum-exp of the scaled logits of every 32-token key tile,
-    // [rows][n_tiles_max], tile index = position in the sequence's table (history rounds in order, then the
-    // current round); null otherwise
+    // at the watershed layer only: natural-log sum-exp of the scaled logits of every score unit of a sequence's
+    // table (history rounds in order, then the current round), [rows][n_tiles_max]; the unit is a 32-token key
+    // tile in the 16-row kernel and a 256-token chunk of a round in the many-row kernel; null otherwise
     float* tile_lse;
     int n_tiles_max;
 };

@@ -7,8 +7,9 @@
 using namespace ra;
 
 // Shared by the two prefill entry points.  With `scores` given (watershed layer) the attention runs over every
-// history round and the kernel also leaves one log-sum-exp per (query row, 32-token key tile), which the
-// finishing kernels of the score pass turn into Eq. 1.
+// history round and the kernel also leaves one log-sum-exp per (query row, score unit: a 32-token key tile in the
+// 16-row kernel, a 256-token chunk of a round in the many-row kernel), which the finishing kernels of the score
+// pass turn into Eq. 1.
 static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq, const ra_kv_view* layer,
                         const int32_t* sel_idx, const int32_t* n_sel, const void* cur_k, const void* cur_v, int cur_len,
                         float scale, float* out, float* lse, float* scores_head, float* scores) {
