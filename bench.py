@@ -44,6 +44,8 @@ MEASURED_TRAFFIC = {
     ("cfg2", "ra_round_sparse_attn_decode"): 50_413_773,
     ("cfg5", "ra_round_scores"): 4_297_836_237,
     ("cfg5", "ra_round_sparse_attn_decode"): 5_122_599_322,
+    ("cfg3", "ra_round_scores"): 319_942_144,
+    ("cfg3", "ra_round_sparse_attn_prefill"): 263_445_811,
 }
 
 
