@@ -44,6 +44,8 @@ MEASURED_TRAFFIC = {
     ("cfg2", "ra_round_sparse_attn_decode"): 50_413_773,
     ("cfg5", "ra_round_scores"): 4_297_836_237,
     ("cfg5", "ra_round_sparse_attn_decode"): 5_122_599_322,
+    ("cfg4", "ra_round_sparse_attn_decode"): 2_775_888_691,
+    ("cfg4", "ra_round_scores"): 4_307_422_924,
     ("cfg3", "ra_round_scores"): 319_942_144,
     ("cfg3", "ra_round_sparse_attn_prefill"): 263_445_811,
 }
@@ -517,7 +519,8 @@ def bench_long_context(steps, warmup, lam, order_name):
                    "lambda": lam, "alpha": w.alpha,
                    "step": f"ra_round_scores -> ra_select_rounds -> {L_all} x ra_round_sparse_attn_decode on staged views"},
         "roofline": {"bound": "hbm", "kernel": groups[dom]["kernel"], "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": ach / HBM_PEAK_GBS, "traffic": None, "whole_call_achieved": groups[dom]["GB/s"]},
+                     "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(("cfg4", dom)),
+                     "whole_call_achieved": groups[dom]["GB/s"]},
         "kernel_groups": groups,
         "staging": {"order": order_name, "bytes": staged, "copies": n_copies, "registered_bytes_logical": registered,
                     "alone": stage_only, "overlapped_with_decode": overlapped,
