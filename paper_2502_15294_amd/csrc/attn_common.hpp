@@ -53,7 +53,7 @@ inline AttnWorkspace attn_workspace(size_t rows, int S, int D, int B, int R_max)
 
 // Builds the per-sequence segment tables for work units of `unit_tokens` tokens (grid B).
 void launch_plan(const AttnArgs& a, int unit_tokens, hipStream_t st);
-int attn_min_units();  // tuning knob (environment RA_ATTN_MIN_UNITS), default 8
+int attn_min_units();  // smallest piece of a sequence's key set, in 32-token tiles
 
 // bf16, d = 128, Hq/Hkv <= 16: matrix-core streaming kernel, the waves of a workgroup split the key tiles
 // of 16 query rows (decode, short questions).

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             vd[128] = sh.v2;
             vd[192] = sh.v3;
         };
-        auto consume = [&](const char* buf, int tok0, int len, bool is_cur, int u_seq) {
+        auto consume = [&](const char* buf, int tok0, int len, bool is_cur) {
             const bool full = !is_cur && (len - tok0 >= kTileP);
             const uint4* kb = reinterpret_cast<const uint4*>(buf);
             const uint2* vb = reinterpret_cast<const uint2*>(buf + 8192);
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                     sh = load_share();
                 }
                 RA_LAP(1);
-                consume(buf, tok0, len, is_cur, u);
+                consume(buf, tok0, len, is_cur);
                 RA_LAP(5);
                 if constexpr (TILE_LSE) {
                     const int uin = u - t_first;
