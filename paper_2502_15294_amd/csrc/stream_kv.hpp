@@ -31,7 +31,6 @@ __device__ __forceinline__ float row16_sum(float v) {
     v += dpp_mov<0x140>(v);  // row_mirror
     return v;
 }
-__device__ __forceinline__ float xrow_get(float v, int xor_mask) { return __shfl_xor(v, xor_mask, 64); }
 // Maxima without the NaN-quieting copies the compiler puts in front of fmaxf (three instructions per call).
 __device__ __forceinline__ float vmax(float a, float b) {
     float d;
