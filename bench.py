@@ -676,6 +676,14 @@ def main():
                                     "roofline": big["roofline"],
                                     "decode_frac_of_hbm_peak": big["kernel_groups"]["ra_round_sparse_attn_decode"]["GB/s"] / HBM_PEAK_GBS,
                                     "scores_frac_of_hbm_peak": big["kernel_groups"]["ra_round_scores"]["GB/s"] / HBM_PEAK_GBS}
+    # the practical ceiling beside the published peak: what a plain read kernel reaches on this GPU right now
+    ctx = ra.ra_create(0)
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    ra.ra_set_workspace(ctx, ws)
+    probe = torch.empty(1 << 30, dtype=torch.float32, device="cuda")  # 4 GiB, never initialised: only read
+    result["roofline"]["stream_read_GB/s"] = ra.ra_measure_read_bandwidth(ctx, probe, iters=5)
+    del probe
+    ra.ra_destroy(ctx)
     if not args.no_cpu_baseline:
         n = args.cpu_baseline_seqs or (w.B if args.workload in ("cfg1", "cfg2") else 2)
         result["cpu_baseline"] = cpu_baseline(w, args.lam, n)

@@ -33,7 +33,7 @@ EXPORTS = [
     "ra_kv_store_stage", "ra_kv_store_wait_layer", "ra_kv_store_layer_view", "ra_kv_store_stats",
     "ra_kv_store_release", "ra_kv_store_save_round", "ra_kv_store_save_wait", "ra_kv_store_round_activity",
     "ra_kv_store_drop_round", "ra_kv_store_drop_inactive",
-    "ra_round_scores_accumulate", "ra_layer_divergence", "ra_selection_coverage",
+    "ra_round_scores_accumulate", "ra_layer_divergence", "ra_selection_coverage", "ra_measure_read_bandwidth",
 ]
 
 
@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
         L.ra_profile_last_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.ra_round_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(ra_kv_view),
                                       C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p]
+        L.ra_measure_read_bandwidth.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int,
+                                                C.POINTER(C.c_float)]
         L.ra_round_scores_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                                  C.POINTER(ra_kv_view), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                                  C.c_void_p, C.c_void_p]
@@ -475,3 +477,11 @@ def ra_kv_store_drop_inactive(store, min_turns: int, B: int, R_max: int) -> Tupl
     n = torch.empty((B,), dtype=torch.int32)
     _check(lib().ra_kv_store_drop_inactive(store, min_turns, _ptr(idx), _ptr(n)))
     return idx, n
+
+
+def ra_measure_read_bandwidth(ctx, buf: torch.Tensor, iters: int = 5, stream=None) -> float:
+    """GB/s of a plain read kernel over `buf` (waits for the GPU)."""
+    out = C.c_float()
+    _check(lib().ra_measure_read_bandwidth(ctx, _stream(stream), _ptr(buf), buf.numel() * buf.element_size(), iters,
+                                           C.byref(out)))
+    return out.value

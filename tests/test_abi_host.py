@@ -62,6 +62,7 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert L.ra_set_workspace(None, None, 0) == ra.RA_ERR_INVALID_ARG
     assert L.ra_profile_kernels(None, 1) == ra.RA_ERR_INVALID_ARG
     assert L.ra_profile_last_ms(None, None) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_measure_read_bandwidth(None, None, None, 0, 1, None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_kv_store_create(None, None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_kv_store_register_round(None, 0, 0, None, 0) == ra.RA_ERR_INVALID_ARG
     assert L.ra_kv_store_stage(None, None, None, 0, None) == ra.RA_ERR_INVALID_ARG

@@ -698,3 +698,15 @@ def test_calls_on_a_side_stream_are_ordered_on_that_stream():
         assert sel_idx[b, :n_sel[b]].tolist() == r.sel
         assert ora.row_error(out[b].cpu().numpy()[None], r.out[1]) < STREAM_TOL
     eng.close()
+
+
+def test_read_bandwidth_probe_returns_a_plausible_figure():
+    eng = Engine(make_workload("cfg1"))
+    buf = torch.zeros(1 << 27, dtype=torch.float32, device="cuda")       # 512 MiB
+    gbs = ra.ra_measure_read_bandwidth(eng.ctx, buf, iters=3)
+    _say(f"plain read kernel: {gbs:.0f} GB/s")
+    assert 500.0 < gbs < 8000.0                                          # below the published peak, above PCIe-class rates
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_measure_read_bandwidth(eng.ctx, buf[1:5], iters=1)         # not 16-byte aligned
+    assert e.value.code == ra.RA_ERR_INVALID_ARG
+    eng.close()
