@@ -257,3 +257,96 @@ def test_save_round_error_paths():
     assert ra.ra_kv_store_stats(store)[1] == 0
     ra.ra_kv_store_destroy(small)
     ra.ra_kv_store_destroy(store)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_turns_against_the_ledger_and_the_oracle(seed):
+    """Six turns of a random dialogue: each turn stages a random selection (in either copy order), decodes one
+    layer from the staged view, saves a new round of random length, and now and then drops the rounds that were
+    never selected.  Counters follow the oracle's ledger, bytes follow the selection, attention follows the oracle."""
+    rng = np.random.default_rng(500 + seed)
+    B, R0, turns = 2, 4, 6
+    cur_cap = 40
+    w = make_workload("cfg4", B=B, R=R0, n_post_layers=2, cur_len=cur_cap, length=("uniform", 1, 120))
+    layers = [1, 2]
+    R_max = R0 + turns
+    store = _store(w, R_max, 64 << 20)
+    eng = Engine(w, extra_tokens=turns * cur_cap + 64)
+    side = torch.cuda.Stream()
+    ledgers = [sl.ActivityLedger() for _ in range(B)]
+    # per sequence: round index -> (length, keys per layer, values per layer) as float arrays; host tensors kept alive
+    content = [dict() for _ in range(B)]
+    keep = {}
+    for b in range(B):
+        for r in range(R0):
+            keep[b, r] = _pinned(pack_round_host(w, b, r, layers))
+            ra.ra_kv_store_register_round(store, b, r, keep[b, r], int(w.lens[b][r]))
+            content[b][r] = (int(w.lens[b][r]), [w.k_round(b, l, r) for l in layers], [w.v_round(b, l, r) for l in layers])
+            ledgers[b].add_round(r)
+    dropped = [set() for _ in range(B)]
+    for turn in range(turns):
+        n_now = R0 + turn
+        # ---- a random selection among the rounds that exist (dropped ones may be named: they are empty) ----------
+        sels = [sorted(rng.choice(n_now, size=int(rng.integers(1, n_now + 1)), replace=False).tolist()) for _ in range(B)]
+        sel_t = torch.full((B, R_max), -1, dtype=torch.int32)
+        for b, s in enumerate(sels):
+            sel_t[b, :len(s)] = torch.tensor(s, dtype=torch.int32)
+            ledgers[b].record_selection([r for r in s if r not in dropped[b]])
+        n_t = torch.tensor([len(s) for s in sels], dtype=torch.int32)
+        order = ra.RA_STAGE_ROUND_MAJOR if rng.random() < 0.5 else ra.RA_STAGE_LAYER_MAJOR
+        ra.ra_kv_store_stage(store, sel_t, n_t, order, side)
+        li = int(rng.integers(0, 2))
+        ra.ra_kv_store_wait_layer(store, li)
+        q_np = rng.standard_normal((B, 1, w.Hq, w.d)).astype(np.float32)
+        q = to_device(q_np[:, 0], w.dtype)
+        q_np = q.float().cpu().numpy()[:, None]                     # the values the GPU really sees
+        out, _ = ra.ra_round_sparse_attn_decode(eng.ctx, q, ra.ra_kv_store_layer_view(store, li), scale=w.scale)
+        torch.cuda.synchronize()
+        staged, registered, _ = ra.ra_kv_store_stats(store)
+        want_bytes = 0
+        for b in range(B):
+            live = [r for r in sels[b] if r not in dropped[b]]
+            want_bytes += sum(ra.ra_kv_store_round_bytes(store, content[b][r][0]) for r in live)
+            n_keys = sum(content[b][r][0] for r in live)
+            if n_keys == 0:
+                assert np.all(out[b].cpu().numpy() == 0)
+                continue
+            kr = {r: content[b][r][1][li] for r in live}
+            vr = {r: content[b][r][2][li] for r in live}
+            n_all = max(live) + 1
+            ro, _ = ora.sparse_attention(q_np[b], [kr.get(r) for r in range(n_all)], [vr.get(r) for r in range(n_all)], live,
+                                         w.scale, None, None)
+            assert ora.row_error(out[b].cpu().numpy()[None], ro) < STREAM_TOL, (turn, b)
+        assert staged == want_bytes
+        # ---- the turn ends: a new round of random length goes to host memory ---------------------------------
+        new_lens = [int(rng.integers(0, cur_cap + 1)) for _ in range(B)]
+        k_np = [rng.standard_normal((B, cur_cap, w.Hkv, w.d)).astype(np.float32) for _ in layers]
+        v_np = [rng.standard_normal((B, cur_cap, w.Hkv, w.d)).astype(np.float32) for _ in layers]
+        ks, vs = [to_device(x, w.dtype) for x in k_np], [to_device(x, w.dtype) for x in v_np]
+        hosts = [torch.empty(max(ra.ra_kv_store_round_bytes(store, n) // 2, 1), dtype=torch.int16).pin_memory()
+                 for n in new_lens]
+        ra.ra_kv_store_save_round(store, torch.full((B,), n_now, dtype=torch.int32),
+                                  torch.tensor(new_lens, dtype=torch.int32), ks, vs, hosts, None, side)
+        for b in range(B):
+            keep[b, n_now] = hosts[b]
+            n = new_lens[b]
+            content[b][n_now] = (n, [k.float().cpu().numpy()[b, :n] for k in ks], [v.float().cpu().numpy()[b, :n] for v in vs])
+            ledgers[b].add_round(n_now)
+        ra.ra_kv_store_release(store)
+        for b in range(B):
+            for r in ledgers[b].turns:
+                assert ra.ra_kv_store_round_activity(store, b, r) == (ledgers[b].turns[r], ledgers[b].hits[r]), (turn, b, r)
+        # ---- every other turn: drop what was never selected in at least two turns -------------------------------
+        if turn % 2 == 1:
+            idx, n = ra.ra_kv_store_drop_inactive(store, 2, B, R_max)
+            for b in range(B):
+                expect = ledgers[b].inactive(2)
+                assert idx[b, :n[b]].tolist() == expect, (turn, b)
+                ledgers[b].drop(expect)
+                dropped[b] |= set(expect)
+                for r in expect:
+                    content[b][r] = (0, content[b][r][1], content[b][r][2])
+                    keep.pop((b, r), None)
+    ra.ra_kv_store_save_wait(store)
+    ra.ra_kv_store_destroy(store)
+    eng.close()
