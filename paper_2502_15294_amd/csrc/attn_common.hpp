@@ -63,8 +63,13 @@ int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStrea
 // Small batches: the 16-row matrix-core kernel resolves the selection itself (every workgroup reads the whole
 // batch's segment lists in one memory round trip and builds its sequences' tables in LDS), so that no planning
 // kernel runs before it.
-inline bool attn_mfma_plans_inline(int B, int R_max) { return B <= 64 && (long long)B * R_max <= 1024; }
 inline size_t attn_mfma_inline_bytes(int B, int R_max) { return (size_t)B * R_max * 24 + (size_t)B * 12 + 16; }
+inline bool attn_mfma_plans_inline(int B, int R_max) {
+    // ... as long as the lists, the workgroup's own table (24 bytes per segment) and the 33 KB merge buffer stay
+    // within 64 KB of LDS, so that two workgroups still fit a compute unit
+    return B <= 64 && (long long)B * R_max <= 1024 &&
+           attn_mfma_inline_bytes(B, R_max) + (size_t)(R_max + 1) * 24 + 64 + 33280 <= 64 * 1024;
+}
 // Most pieces one sequence can be cut into by the matrix-core kernel (row length of the piece buffers).
 inline int mfma_max_pieces(int64_t max_tokens, int min_units, int cap) {
     int64_t s = max_tokens / (32 * (int64_t)min_units);

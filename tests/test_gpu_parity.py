@@ -507,9 +507,11 @@ def test_kernel_timing_hooks():
     eng.close()
 
 
-def test_largest_round_count_decode_and_prefill():
-    """R_max = 1024 rounds (the largest the entry points accept): the segment tables are at their biggest."""
-    w = make_workload("cfg2", B=2, R=1024, length=("uniform", 1, 6))
+@pytest.mark.parametrize("B", [2, 1])
+def test_largest_round_count_decode_and_prefill(B):
+    """R_max = 1024 rounds (the largest the entry points accept): the segment tables are at their biggest.  (With one
+    sequence the batch is small enough for the decode kernel to plan it by itself, were it not for the table sizes.)"""
+    w = make_workload("cfg2", B=B, R=1024, length=("uniform", 1, 6))
     eng = Engine(w)
     v0, v1 = device_view(w, 0, with_v=False), device_view(w, 1)
     P, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, scale=w.scale)
@@ -709,4 +711,16 @@ def test_read_bandwidth_probe_returns_a_plausible_figure():
     with pytest.raises(ra.RaError) as e:
         ra.ra_measure_read_bandwidth(eng.ctx, buf[1:5], iters=1)         # not 16-byte aligned
     assert e.value.code == ra.RA_ERR_INVALID_ARG
+    eng.close()
+
+
+def test_one_sequence_with_600_rounds_is_planned_inside_the_decode_kernel():
+    """The largest single-sequence batch whose segment lists the decode kernel still keeps in LDS by itself."""
+    w = make_workload("cfg2", B=1, R=600, cur_len=9, length=("uniform", 1, 40))
+    eng = Engine(w)
+    sels = [sorted(np.random.default_rng(1).choice(600, size=211, replace=False).tolist())]
+    out, lse = _gpu_decode(eng, w, 1, sels)
+    ref_o, ref_l = _oracle_attention(w, 1, sels)
+    assert ora.row_error(out, ref_o[:, 0]) < STREAM_TOL
+    assert np.allclose(lse, ref_l[:, 0], rtol=0, atol=2e-5 * np.abs(ref_l).max())
     eng.close()
