@@ -542,6 +542,13 @@ def test_largest_round_count_decode_and_prefill(B):
     sel = sel_idx[0, :n_sel[0]].tolist()
     ref_o, _ = pipeline.attention_for_sequence(w, 0, 1, sel)
     assert ora.row_error(out[0], ref_o) < STREAM_TOL
+    # the same question at the watershed layer, scores from the attention pass (chunk prefix table at its biggest)
+    o2, _, _, S2 = ra.ra_watershed_attn_prefill(eng.ctx, to_device(w.q(0), w.dtype), device_view(w, 0),
+                                                to_device(w.cur_k(0), w.dtype), to_device(w.cur_v(0), w.dtype), scale=w.scale)
+    torch.cuda.synchronize()
+    assert np.abs(S2[0].cpu().numpy() - rS).max() < SCORE_TOL
+    ref_o, _ = pipeline.attention_for_sequence(w, 0, 0, list(range(1024)))
+    assert ora.row_error(o2[0].cpu().numpy(), ref_o) < STREAM_TOL
     eng.close()
 
 
