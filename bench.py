@@ -678,7 +678,7 @@ def main():
                                     "scores_frac_of_hbm_peak": big["kernel_groups"]["ra_round_scores"]["GB/s"] / HBM_PEAK_GBS}
     # the practical ceiling beside the published peak: what a plain read kernel reaches on this GPU right now
     ctx = ra.ra_create(0)
-    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(1 << 18, dtype=torch.uint8, device="cuda")
     ra.ra_set_workspace(ctx, ws)
     probe = torch.empty(1 << 30, dtype=torch.float32, device="cuda")  # 4 GiB, never initialised: only read
     result["roofline"]["stream_read_GB/s"] = ra.ra_measure_read_bandwidth(ctx, probe, iters=5)

@@ -125,7 +125,7 @@ int ra_destroy(ra_ctx* ctx);
 
 /* Upper bound of the scratch bytes any compute call needs for problems inside `p`. */
 int ra_workspace_bytes(const ra_problem* p, size_t* bytes_out);
-/* Hand the context a device buffer (256-byte aligned) to use as scratch.  The caller keeps
+/* Hand the context a device buffer (256-byte aligned, at least 32 KB) to use as scratch.  The caller keeps
  * ownership and must keep it alive, and must not run two calls that use it concurrently. */
 int ra_set_workspace(ra_ctx* ctx, void* device_ptr, size_t bytes);
 

@@ -34,6 +34,12 @@ struct AttnArgs {
     // tile in the 16-row kernel and a 256-token chunk of a round in the many-row kernel; null otherwise
     float* tile_lse;
     int n_tiles_max;
+    // matrix-core kernel for up to 32 query rows per KV head (range schedule, see range_schedule.hpp): partial
+    // results of the sequences that lie in several ranges
+    float* rec_acc;   // [records][inner][16][D]   inner = Hkv * row blocks
+    float* rec_ml;    // [records][inner][16][2]   running max of the raw logits, sum of 2^((logit - max) * c)
+    int* seq_rec;     // [B][2] first record and number of records of every sequence (written by the kernel)
+    int max_ranges;   // most ranges the batch's key tiles are cut into
 };
 
 // Workspace layout of one attention call; returns the bytes needed past the reserved head.
@@ -55,22 +61,61 @@ inline AttnWorkspace attn_workspace(size_t rows, int S, int D, int B, int R_max)
 void launch_plan(const AttnArgs& a, int unit_tokens, hipStream_t st);
 int attn_min_units();  // smallest piece of a sequence's key set, in 32-token tiles
 
-// bf16, d = 128, Hq/Hkv <= 16: matrix-core streaming kernel, the waves of a workgroup split the key tiles
-// of 16 query rows (decode, short questions).
+// bf16, d = 128, Hq/Hkv <= 16, up to 32 query rows per KV head (decode, short questions): matrix-core streaming
+// kernel, one wavefront per (range of the batch's key tiles, KV head, block of 16 query rows).
 int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st);
+void launch_merge_records(const AttnArgs& a, int num_cu, hipStream_t st);  // ... and its second step
 // Same operands, many query rows per KV head: the waves own different rows and share key tiles through LDS.
 int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st);
-// Small batches: the 16-row matrix-core kernel resolves the selection itself (every workgroup reads the whole
-// batch's segment lists in one memory round trip and builds its sequences' tables in LDS), so that no planning
-// kernel runs before it.
-inline size_t attn_mfma_inline_bytes(int B, int R_max) { return (size_t)B * R_max * 24 + (size_t)B * 12 + 16; }
-inline bool attn_mfma_plans_inline(int B, int R_max) {
-    // ... as long as the lists, the workgroup's own table (24 bytes per segment) and the 33 KB merge buffer stay
-    // within 64 KB of LDS, so that two workgroups still fit a compute unit
-    return B <= 64 && (long long)B * R_max <= 1024 &&
-           attn_mfma_inline_bytes(B, R_max) + (size_t)(R_max + 1) * 24 + 64 + 33280 <= 64 * 1024;
+// Small batches: the first kernel resolves the selection itself (every workgroup reads the whole batch's segment
+// lists in one memory round trip and keeps them in LDS), so that no planning kernel runs before it.
+inline size_t attn_mfma_inline_bytes(int B, int R_max) {
+    return (size_t)B * R_max * 24 + (size_t)B * (R_max + 2) * 4 + (size_t)B * 16 + 16;
 }
-// Most pieces one sequence can be cut into by the matrix-core kernel (row length of the piece buffers).
+inline bool attn_mfma_plans_inline(int B, int R_max) {
+    return B <= 64 && (long long)B * R_max <= 1024;  // at most 29 KB of LDS beside the 17 KB of score staging
+}
+// Launch shape and scratch of that kernel.  `max_tiles` bounds the 32-token key tiles of the whole batch.
+constexpr int kMfmaMinUnits = 4;  // shortest range in key tiles (two tiles are in flight per wave; ranges of 2 and of 8 measured no better)
+struct MfmaDecodeShape {
+    int n_rowblocks, inner, grid, max_ranges, records;
+    size_t rec_bytes, ml_bytes;
+};
+inline MfmaDecodeShape mfma_decode_shape(int num_cu, int B, int R_max, int Hkv, int rows_total, long long max_tiles) {
+    MfmaDecodeShape s;
+    s.n_rowblocks = (rows_total + 15) / 16;
+    s.inner = Hkv * s.n_rowblocks;
+    long long want = max_tiles / kMfmaMinUnits;  // ranges the batch can have at most
+    if (want < 1) want = 1;
+    long long grid = (want * s.inner + 3) / 4;   // four waves per workgroup, at least one work item per wave
+    const long long full = 2ll * (num_cu > 512 ? 512 : num_cu);
+    if (grid > full) grid = full;
+    if (grid < 1) grid = 1;
+    s.grid = (int)grid;
+    long long ranges = grid * 4 / s.inner;  // one range per wave
+    if (ranges > want) ranges = want;
+    s.max_ranges = (int)(ranges < 1 ? 1 : ranges);
+    s.records = s.max_ranges + B;
+    s.rec_bytes = align_up((size_t)s.records * s.inner * 16 * 128 * sizeof(float), 256);
+    s.ml_bytes = align_up((size_t)s.records * s.inner * 16 * 2 * sizeof(float), 256);
+    return s;
+}
+// Bound of the 32-token tiles of a batch: every round and the current round may end with a partial tile.
+inline long long mfma_max_tiles(int B, long long max_tokens, int R_max, int cur_cap) {
+    return (long long)B * (max_tokens / 32 + R_max + cur_cap / 32 + 1);
+}
+struct MfmaDecodeWorkspace {
+    size_t plan_off, rec_off, ml_off, total;
+};
+inline MfmaDecodeWorkspace mfma_decode_workspace(const MfmaDecodeShape& s, int B, int R_max) {
+    MfmaDecodeWorkspace w;
+    w.plan_off = kWsReserved;
+    w.rec_off = w.plan_off + align_up(attn_plan_bytes(B, R_max), 256);
+    w.ml_off = w.rec_off + s.rec_bytes;
+    w.total = w.ml_off + s.ml_bytes;
+    return w;
+}
+// Most pieces one sequence can be cut into by the many-row kernel (row length of its piece buffers).
 inline int mfma_max_pieces(int64_t max_tokens, int min_units, int cap) {
     int64_t s = max_tokens / (32 * (int64_t)min_units);
     return (int)(s < 1 ? 1 : (s > cap ? cap : s));

@@ -3,7 +3,7 @@
 //
 // This kernel serves decode and short questions; long questions use the kernel that shares key tiles
 // through LDS.  The "query rows" of a KV head g are the pairs (query token i, head h of the group),
-// row = i * G + h: G rows for decode, q_len * G in general; they are handled in tiles of 16 rows.
+// row = i * G + h: G rows for decode, q_len * G in general; they are handled in blocks of 16 rows.
 // Keys/values are streamed in tiles of 32 tokens that never cross a round:
 //
 //   S^T tile  [16 tokens x 16 rows]  = K[16 x 128] . Q^T[128 x 16]        4 x mfma 16x16x32 per 16 tokens
@@ -19,63 +19,166 @@
 //
 // P is rounded to bf16 twice (P = hi + lo, both bf16) so that the product carries ~16 bits of P.
 //
-// Launch: persistent workgroups, about two per compute unit.  Every workgroup derives the same
-// balanced schedule of the batch (see build_schedule) and walks the work items
-// (piece of a sequence, KV head, row block) with stride gridDim.x.
-// The four waves of a workgroup take different key tiles of the same 16 rows and are merged through LDS.
+// Work decomposition (range_schedule.hpp): the key tiles of the whole batch are cut into equal ranges, and ONE
+// WAVEFRONT streams one range for one (KV head, block of 16 query rows), two tiles in flight, everything it
+// needs in its own registers.  After the prologue, in which a workgroup derives the batch's tile prefix (and,
+// for small batches, resolves the selections itself), the waves never meet again: there is no barrier and no
+// shared buffer in the streaming loop, and no wave ever waits for another.  A sequence that lies in one range is
+// written out directly; otherwise each of its segments leaves a partial result ("record") and a second, small
+// kernel merges the records of every sequence that was cut.
 #include "attn_common.hpp"
 #include "mfma_util.hpp"
-#include "debug_ts.hpp"
+#include "range_schedule.hpp"
 
 namespace ra {
 
 constexpr int kTile = 32;  // tokens per key tile (two 16-token halves)
 constexpr int D128 = 128;
-constexpr int kPiecesPerWorkgroup = 4;  // pieces a persistent workgroup aims to get when work is plentiful
+constexpr int kLsePitch = 65;  // floats per row of a wave's strip of staged tile log-sum-exps
 
 struct KVTile {
     uint4 k[2][4];  // [half][kk]: 8 channels kk*32 + 8*(lane/16) .. of token half*16 + lane%16
     uint2 v[8][2];  // [dt][half]: tokens 4*(lane/16) .. +3 of that half, channel dt*16 + lane%16
 };
 
-// TILE_LSE: 0 = attention only; 1 = also one log-sum-exp per (query row, key tile), stored as it is produced;
-// 2 = the same, staged in LDS and written out in blocks of 64 tiles (pays when a piece has many tiles).
+// Where a key tile lies; every field is the same in all lanes of the wave.
+struct TileRef {
+    int len;           // tokens of the segment (round) the tile belongs to
+    int uin;           // index of the tile inside its segment
+    int u_seq;         // index of the tile inside the sequence's table
+    bool is_cur;       // the segment is the current round (token-major keys and values)
+    long long ok, ov;  // start of the segment's keys / values (tokens, or block-table slots when paged)
+};
+
+__device__ __forceinline__ int lane_get(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+__device__ __forceinline__ long long lane_get64(long long v, int l) {
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(unsigned long long)v, l);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)((unsigned long long)v >> 32), l);
+    return (long long)(((unsigned long long)hi << 32) | lo);
+}
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Exclusive prefix sum over the 64 lanes of a wave; `total` receives the sum of all lanes.
+__device__ __forceinline__ int wave_exclusive_scan(int v, int lane, int& total) {
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += t;
+    }
+    total = __builtin_amdgcn_readlane(incl, 63);
+    return incl - v;
+}
+
+// A record: the accumulators of the 16 rows of a block, row-major [16][128], and (max, sum) per row.
+constexpr int kRecFloats = 16 * D128;
+
+// Merge of the records of every (sequence, KV head, row block) that was cut; grid (B * inner), block 256.
+// Thread = (group, row, four channels): the rows of the block (at most eight per pass) times 32 channel quads fill
+// 32 .. 256 threads, and when they fill fewer the remaining threads form further groups that take every NG-th
+// record; the groups are then merged through LDS.  Four records per thread are in flight at a time.
+__global__ __launch_bounds__(256) void merge_records_kernel(AttnArgs a, int n_rowblocks) {
+    __shared__ float sh_num[8][8][D128];  // [group][row][channel]
+    __shared__ float sh_ml[8][8][2];
+    const int Hkv = a.view.Hkv, inner = Hkv * n_rowblocks;
+    const int b = blockIdx.x / inner, gi = blockIdx.x - b * inner;
+    const int g = gi % Hkv, rowblock = gi / Hkv;
+    const int rec0 = a.seq_rec[2 * b], n_parts = a.seq_rec[2 * b + 1];
+    if (n_parts <= 1) return;  // written directly by the streaming kernel (or no key at all)
+    const int rows_here = min(16, a.q_len * a.G - rowblock * 16);
+    const int t = threadIdx.x;
+    for (int row0 = 0; row0 < rows_here; row0 += 8) {
+        const int R = min(8, rows_here - row0);
+        const int rp_log2 = R <= 1 ? 0 : (R <= 2 ? 1 : (R <= 4 ? 2 : 3));
+        const int group_threads = 32 << rp_log2, NG = 256 >> (5 + rp_log2);
+        const int grp = t >> (5 + rp_log2), tt = t & (group_threads - 1);
+        const int r = tt >> 5, c4 = tt & 31;
+        const bool active = r < R;
+        const int row = row0 + (active ? r : 0);
+        float M = kNegBig, den = 0.f;
+        floatx4_t num = floatx4_t{0.f, 0.f, 0.f, 0.f};
+        for (int p0 = grp; p0 < n_parts; p0 += 4 * NG) {
+            floatx4_t v[4];
+            float2 ml[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int p = p0 + j * NG;
+                v[j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+                ml[j] = make_float2(kNegBig, 0.f);
+                if (p < n_parts && active) {
+                    const size_t rrow = ((size_t)(rec0 + p) * inner + gi) * 16 + row;
+                    v[j] = *reinterpret_cast<const floatx4_t*>(a.rec_acc + rrow * D128 + c4 * 4);
+                    ml[j] = *reinterpret_cast<const float2*>(a.rec_ml + rrow * 2);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float m_new = fmaxf(M, ml[j].x);
+                const float f_old = fast_exp2((M - m_new) * a.c), f_new = fast_exp2((ml[j].x - m_new) * a.c);
+                den = __builtin_fmaf(ml[j].y, f_new, den * f_old);
+                num = v[j] * f_new + num * f_old;
+                M = m_new;
+            }
+        }
+        if (active) {
+            *reinterpret_cast<floatx4_t*>(&sh_num[grp][r][c4 * 4]) = num;
+            if (c4 == 0) {
+                sh_ml[grp][r][0] = M;
+                sh_ml[grp][r][1] = den;
+            }
+        }
+        __syncthreads();
+        if (grp == 0 && active) {
+            float Mx = kNegBig;
+            for (int k = 0; k < NG; ++k) Mx = fmaxf(Mx, sh_ml[k][r][0]);
+            float d = 0.f;
+            floatx4_t o = floatx4_t{0.f, 0.f, 0.f, 0.f};
+            for (int k = 0; k < NG; ++k) {
+                const float f = fast_exp2((sh_ml[k][r][0] - Mx) * a.c);
+                d = __builtin_fmaf(sh_ml[k][r][1], f, d);
+                o += *reinterpret_cast<const floatx4_t*>(&sh_num[k][r][c4 * 4]) * f;
+            }
+            const int rw = rowblock * 16 + row, qi = rw / a.G;
+            const size_t rid = ((size_t)b * a.q_len + qi) * a.Hq + (size_t)g * a.G + (rw - qi * a.G);
+            const float inv = d > 0.f ? 1.f / d : 0.f;
+            *reinterpret_cast<floatx4_t*>(a.out + rid * D128 + c4 * 4) = o * inv;
+            if (a.lse && c4 == 0) a.lse[rid] = d > 0.f ? __builtin_fmaf(Mx, a.scale, __builtin_logf(d)) : -__builtin_inff();
+        }
+        __syncthreads();  // the next pass reuses the buffers
+    }
+}
+
+// TILE_LSE: also one log-sum-exp per (query row, key tile), the raw material of the round scores at the watershed
+// layer; staged per wave in LDS and written out in runs of up to 64 tiles per row.
 // INLINE_PLAN: the workgroup resolves the batch's selections itself instead of reading the planning kernel's tables.
-template <bool PAGED, int TILE_LSE, bool INLINE_PLAN>
+template <bool PAGED, bool TILE_LSE, bool INLINE_PLAN>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
-    RA_TS(0);
     const DevView& vw = a.view;
-    const int Hkv = vw.Hkv;
+    const int Hkv = vw.Hkv, B = vw.B;
     const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = uni(tid >> 6);
     const int lane = tid & 63, n = lane & 15, q4 = lane >> 4;
     const int G = a.G, q_len = a.q_len;
     const int rows_total = q_len * G;
-    constexpr int NT = 1, RB = 16;  // one tile of 16 rows per work item
-
     const int cap = vw.R_max + 1;
-    SlotTable tab;
-    tab.carve(smem, cap);
-    float* red = reinterpret_cast<float*>(smem + ((SlotTable::bytes(cap) + 15) & ~(size_t)15));
-    constexpr int kLsePitch = 65, kLseBlock = 16 * kLsePitch;
-    float* lse_buf = red + 128;  // [2][16][65] tile log-sum-exps on their way out; reused by the merge afterwards
+    const int inner = Hkv * n_rowblocks;
 
-    // ---- the batch's schedule, identical in every workgroup --------------------------------------------
-    const int inner = Hkv * n_rowblocks;  // work items per piece
-    const long long slots = ((long long)gridDim.x * kPiecesPerWorkgroup + inner - 1) / inner;
-    // Without a planning kernel: the raw segment lists of the whole batch, by round index, in LDS.
-    const int BR = vw.B * vw.R_max;
-    long long* raw_ok = reinterpret_cast<long long*>(red + 128 + 4 * 16 * 128);  // [B][R_max]
+    // ---- LDS: this wave's strip of staged tile log-sum-exps; the batch's raw segment lists ---------------------
+    float* lse_buf = reinterpret_cast<float*>(smem) + (TILE_LSE ? wave * 16 * kLsePitch : 0);  // [16][kLsePitch]
+    char* lists = smem + (TILE_LSE ? 4 * 16 * kLsePitch * sizeof(float) : 0);
+    const int BR = B * vw.R_max;
+    long long* raw_ok = reinterpret_cast<long long*>(lists);  // [B][R_max], by round index
     long long* raw_ov = raw_ok + BR;
     int* raw_len = reinterpret_cast<int*>(raw_ov + BR);
     int* raw_sel = raw_len + BR;
-    int* meta = raw_sel + BR;  // [B][3]: rounds of the sequence, listed rounds, length of the current round
+    int* meta = raw_sel + BR;   // [B][4]: rounds of the sequence, listed rounds, length of the current round, segments
+    int* cum_l = meta + 4 * B;  // [B][cap + 1] tile prefix of every sequence's table
     // Segment i of sequence b's table, as the planning kernel defines it: the i-th listed round (entries that are
     // not rounds of the sequence count as empty), then the current round.
     auto plan_entry = [&](int b, int i, int& len, long long& ok, long long& ov) {
-        const int n_rounds = meta[3 * b], n_hist = meta[3 * b + 1], cur_len = meta[3 * b + 2];
+        const int n_rounds = meta[4 * b], n_hist = meta[4 * b + 1], cur_len = meta[4 * b + 2];
         len = 0;
         ok = ov = 0;
         if (i < n_hist) {
@@ -89,7 +192,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             len = cur_len;
         }
     };
-    int P;
+    const size_t pstride = plan_stride(cap);
+
+    // ---- prologue (the only part with barriers): tiles of every sequence, their prefix over the batch ----------
     if constexpr (INLINE_PLAN) {
         for (int idx = tid; idx < BR; idx += 256) {
             raw_len[idx] = vw.seg_len[idx];
@@ -97,167 +202,260 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             raw_ov[idx] = vw.seg_off_v[idx];
             raw_sel[idx] = a.sel_idx ? a.sel_idx[idx] : idx % vw.R_max;
         }
-        for (int b = tid; b < vw.B; b += 256) {
+        for (int b = tid; b < B; b += 256) {
             const int n_rounds = min(max(vw.n_rounds[b], 0), vw.R_max);
-            meta[3 * b] = n_rounds;
-            meta[3 * b + 1] = a.sel_idx ? min(max(a.n_sel[b], 0), vw.R_max) : n_rounds;
-            meta[3 * b + 2] = a.cur_k ? min(max(a.cur_len_dev ? a.cur_len_dev[b] : a.cur_len_host, 0), a.cur_cap) : 0;
-            sU[b] = 0;
+            const int n_hist = a.sel_idx ? min(max(a.n_sel[b], 0), vw.R_max) : n_rounds;
+            const int cur_len = a.cur_k ? min(max(a.cur_len_dev ? a.cur_len_dev[b] : a.cur_len_host, 0), a.cur_cap) : 0;
+            meta[4 * b] = n_rounds;
+            meta[4 * b + 1] = n_hist;
+            meta[4 * b + 2] = cur_len;
+            meta[4 * b + 3] = n_hist + (cur_len > 0 ? 1 : 0);
         }
         __syncthreads();
-        // work units of every sequence: one table entry per thread, integer adds in LDS (order does not matter)
-        for (int idx = tid; idx < vw.B * cap; idx += 256) {
-            const int b = idx / cap, i = idx - b * cap;
-            int len;
-            long long ok, ov;
-            plan_entry(b, i, len, ok, ov);
-            if (len > 0) atomicAdd(&sU[b], (len + kTile - 1) / kTile);
+        for (int b = wave; b < B; b += 4) {  // one wave per sequence: prefix of its segments' tile counts
+            int carry = 0;
+            for (int i0 = 0; i0 < cap; i0 += 64) {
+                const int i = i0 + lane;
+                int units = 0;
+                if (i < cap) {
+                    int len;
+                    long long ok, ov;
+                    plan_entry(b, i, len, ok, ov);
+                    units = (len + kTile - 1) / kTile;
+                }
+                int total;
+                const int excl = wave_exclusive_scan(units, lane, total);
+                if (i < cap) cum_l[b * (cap + 1) + i] = carry + excl;
+                carry += total;
+            }
+            if (lane == 0) {
+                cum_l[b * (cap + 1) + cap] = carry;
+                sU[b] = carry;
+            }
         }
-        P = schedule_from_counts(vw.B, a.S, a.min_units, slots, sU, sps);
     } else {
-        P = build_schedule(a.plan, cap, vw.B, a.S, a.min_units, slots, sU, sps);
+        for (int b = tid; b < B; b += 256) sU[b] = reinterpret_cast<const PlanHeader*>(a.plan + (size_t)b * pstride)->U;
     }
-    if (blockIdx.x == 0)
-        for (int b = tid; b < vw.B; b += 256) a.n_parts[b] = sps[b + 1] - sps[b];
+    __syncthreads();
+    for (int b = tid; b < B; b += 256) sps[b] = sU[b];
+    exclusive_scan_units(sps, B);  // sps[b] = first tile of sequence b in the batch's list, sps[B] = all tiles
+    const int total = sps[B];
 
+    // A sequence with an empty key set has no tile and therefore no wave: its rows are written here.
+    if (blockIdx.x == 0) {
+        const int rows_seq = q_len * a.Hq;
+        for (int b = wave; b < B; b += 4) {
+            if (sU[b] != 0) continue;
+            for (int i = lane; i < rows_seq * D128; i += 64) a.out[(size_t)b * rows_seq * D128 + i] = 0.f;
+            if (a.lse)
+                for (int i = lane; i < rows_seq; i += 64) a.lse[(size_t)b * rows_seq + i] = -__builtin_inff();
+        }
+    }
+    if (total == 0) {
+        if (blockIdx.x == 0)
+            for (int b = tid; b < B; b += 256) a.seq_rec[2 * b] = a.seq_rec[2 * b + 1] = 0;
+        return;
+    }
+
+    const RangeCut cut = range_cut((unsigned)total, a.min_units, a.max_ranges);
+    const int n_items = (int)cut.n_ranges * inner;
+    if (blockIdx.x == 0)  // for the merge kernel: first record and number of records of every sequence
+        for (int b = tid; b < B; b += 256) {
+            SeqParts sp = {0, 0};
+            if (sU[b] > 0) sp = seq_parts(cut, sps[b], sps[b + 1]);
+            a.seq_rec[2 * b] = record_index(sp.first_range, b);
+            a.seq_rec[2 * b + 1] = sp.n_parts;
+        }
+    const int n_waves = gridDim.x * 4;
     const char* kbase = reinterpret_cast<const char*>(vw.k);
     const char* vbase = reinterpret_cast<const char*>(vw.v);
     const char* ck = reinterpret_cast<const char*>(a.cur_k);
     const char* cv = reinterpret_cast<const char*>(a.cur_v);
-    const long long n_items = (long long)P * inner;
-    RA_TS(1);
 
-    for (long long item = blockIdx.x; item < n_items; item += gridDim.x) {
-        const int piece = (int)(item / inner);
-        const int rest = (int)(item - (long long)piece * inner);
-        const int g = rest % Hkv, rowblock = rest / Hkv;
-        const int b = find_slot(sps, vw.B, piece);  // sps[b] <= piece < sps[b + 1]
-        const int s = piece - sps[b];
-        const int S_eff = sps[b + 1] - sps[b];
-        const int U = sU[b];
-        const int u_lo = (int)(((long long)U * s) / S_eff);
-        const int u_hi = (int)(((long long)U * (s + 1)) / S_eff);
+    // One work item per wave (a second one only when there are more items than waves).  Handing the items out
+    // dynamically in smaller ranges was measured and lost: under load every dependent memory round trip at the
+    // start of an item waits for the compute unit's whole queue of tile loads, 5 to 10 microseconds.
+    for (int item = blockIdx.x * 4 + wave; item < n_items; item += n_waves) {
+        const int range = item / inner, gi = item - range * inner;  // the (KV head, row block) items of a range are neighbours
+        const int g = gi % Hkv, rowblock = gi / Hkv;
+        int t_lo = (int)range_begin(cut, range);
+        const int t_hi = (int)range_begin(cut, range + 1);
+        int b;  // the sequence that holds tile t_lo: the last one with sps[b] <= t_lo
+        if (B <= 64) b = __popcll(__ballot(lane < B && sps[lane < B ? lane : 0] <= t_lo)) - 1;
+        else b = upper_slot(sps, B, t_lo);
 
-        __syncthreads();  // the previous item's readers of tab / red are done
-        int n_slots, n_hist;
-        if constexpr (INLINE_PLAN) {
-            n_hist = meta[3 * b + 1];
-            n_slots = n_hist + (meta[3 * b + 2] > 0 ? 1 : 0);
-            for (int i = tid; i < cap; i += 256) {
-                int len;
-                long long ok, ov;
-                plan_entry(b, i, len, ok, ov);
-                tab.len[i] = len;
-                tab.off_k[i] = ok;
-                tab.off_v[i] = ov;
-                tab.cum[i] = (len + kTile - 1) / kTile;
+        // ---- the segments of this range: one per sequence it touches --------------------------------------
+        for (; t_lo < t_hi; ++b) {
+            const int seq_lo = sps[b], seq_hi = sps[b + 1];
+            const int seg_hi = min(t_hi, seq_hi);
+            if (seg_hi <= t_lo) continue;  // a sequence without tiles
+            const int u_lo = t_lo - seq_lo, u_hi = seg_hi - seq_lo;  // tiles of the sequence's own table
+            t_lo = seg_hi;
+            const SeqParts parts = seq_parts(cut, seq_lo, seq_hi);
+            const int rec = record_index(range, b);
+
+            // ---- this wave's query rows ---------------------------------------------------------------
+            const int row = rowblock * 16 + n;
+            const bool row_ok = row < rows_total;
+            const int rr = row_ok ? row : 0;
+            const int qtok = rr / G;
+            const size_t rowid = ((size_t)b * q_len + qtok) * a.Hq + (size_t)g * G + (rr - qtok * G);
+            uint4 qf[4];
+            {
+                const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.q) + rowid * D128 * 2);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) qf[kk] = row_ok ? qp[kk * 4 + q4] : make_uint4(0, 0, 0, 0);
             }
-            exclusive_scan_units(tab.cum, cap);
-        } else {
-            const PlanHeader hdr = load_plan(a.plan + (size_t)b * plan_stride(cap), cap, tab);
-            n_slots = hdr.n_slots;
-            n_hist = hdr.n_hist;
-            __syncthreads();
-        }
 
-        RA_TS(2);
-        // ---- this wave's query rows -------------------------------------------------------------------
-        int qtok[NT];
-        bool row_ok[NT];
-        size_t rowid[NT];
-        uint4 qf[NT][4];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int row = rowblock * RB + nt * 16 + n;
-            row_ok[nt] = row < rows_total;
-            const int rr = row_ok[nt] ? row : 0;
-            qtok[nt] = rr / G;
-            rowid[nt] = ((size_t)b * q_len + qtok[nt]) * a.Hq + (size_t)g * G + (rr - qtok[nt] * G);
-            const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.q) + rowid[nt] * D128 * 2);
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) qf[nt][kk] = row_ok[nt] ? qp[kk * 4 + q4] : make_uint4(0, 0, 0, 0);
-        }
-
-        floatx4_t acc[NT][8];
-        float m[NT], l[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            m[nt] = kNegBig;
-            l[nt] = 0.f;
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) acc[nt][dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-        }
-
-        // Loads of tile `uin` of segment `slot`.  Halves that lie past the segment's end re-read its
-        // last 16-token block (their scores are masked), so every address stays inside the segment.
-        auto issue = [&](int uin, int slot, KVTile& t, int& len_out, bool& is_cur_out) {
-            const int len = tab.len[slot];
-            const bool is_cur = slot >= n_hist;
-            len_out = len;
-            is_cur_out = is_cur;
-            const int nblk = (len + 15) >> 4;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int blk = min(uin * 2 + h, nblk - 1);  // uniform
-                const int rin = min(n, len - 1 - blk * 16);  // row inside the block, clamped
-                if (is_cur) {
-                    const size_t e0 = (((size_t)b * a.cur_cap + blk * 16 + rin) * Hkv + g) * D128;
-                    const uint4* kp = reinterpret_cast<const uint4*>(ck + e0 * 2);
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) t.k[h][kk] = kp[kk * 4 + q4];
-                    // token-major values: gather 4 tokens of one channel with 2-byte loads
-                    const unsigned short* vp = reinterpret_cast<const unsigned short*>(cv);
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt) {
-                        uint32_t e[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int tok = min(blk * 16 + q4 * 4 + j, len - 1);
-                            e[j] = vp[(((size_t)b * a.cur_cap + tok) * Hkv + g) * D128 + dt * 16 + n];
-                        }
-                        t.v[dt][h] = make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
-                    }
-                } else {
-                    const char *kp, *vp;
-                    if (PAGED) {
-                        long long si = tab.off_k[slot] + blk;
-                        si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
-                        int pb = vw.block_table[(size_t)b * vw.max_blocks + si];
-                        pb = pb < 0 ? 0 : pb;
-                        kp = kbase + ((((size_t)pb * Hkv + g) * 16 + rin) * D128) * 2;
-                        vp = vbase + (((size_t)pb * Hkv + g) * D128 * 16) * 2;
+            // ---- the sequence's segment table: a window of 64 entries in this wave's registers -------------
+            int n_hist;  // segments before the current round's
+            const char* plan_b = a.plan + (size_t)b * pstride;
+            if constexpr (INLINE_PLAN) n_hist = meta[4 * b + 1];
+            else n_hist = uni(reinterpret_cast<const PlanHeader*>(plan_b)->n_hist);
+            const long long* g_ok = reinterpret_cast<const long long*>(plan_b + sizeof(PlanHeader));
+            const long long* g_ov = g_ok + cap;
+            const int* g_len = reinterpret_cast<const int*>(g_ov + cap);
+            const int* g_cum = g_len + cap;
+            auto cum_at = [&](int i) { return INLINE_PLAN ? cum_l[b * (cap + 1) + i] : g_cum[i]; };  // i <= cap
+            int win_lo = 0, w_len = 0, w_cum = 0;
+            long long w_ok = 0, w_ov = 0;
+            auto fill_window = [&](int lo) {  // entries lo .. lo + 63 (those past the table read as empty)
+                win_lo = lo;
+                const int i = lo + lane;
+                w_len = 0;
+                w_ok = w_ov = 0;
+                w_cum = cum_at(min(i, cap));
+                if (i < cap) {
+                    if constexpr (INLINE_PLAN) {
+                        plan_entry(b, i, w_len, w_ok, w_ov);
                     } else {
-                        const size_t L16 = (size_t)nblk * 16;
-                        kp = kbase + ((((size_t)tab.off_k[slot] * Hkv + (size_t)g * len + blk * 16 + rin) * D128)) * 2;
-                        vp = vbase + ((((size_t)tab.off_v[slot] * Hkv + (size_t)g * L16 + (size_t)blk * 16) * D128)) * 2;
+                        w_len = g_len[i];
+                        w_ok = g_ok[i];
+                        w_ov = g_ov[i];
                     }
-                    const uint4* kq = reinterpret_cast<const uint4*>(kp);
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) t.k[h][kk] = kq[kk * 4 + q4];
-                    const uint2* vq = reinterpret_cast<const uint2*>(vp);
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt) t.v[dt][h] = vq[(dt * 16 + n) * 4 + q4];  // 4 x 8 bytes per channel
                 }
+            };
+            // The first 64 entries are fetched together with the table's header and the queries (one memory round
+            // trip for a sequence of up to 63 segments).  Slot of tile u_lo: the last entry with cum[i] <= u_lo;
+            // entries past the sequence's segments hold the total, which is larger.
+            fill_window(0);
+            int slot = __popcll(__ballot(lane < cap && w_cum <= u_lo)) - 1;
+            for (int i0 = 64; i0 < cap; i0 += 64) {
+                const int i = i0 + lane;
+                slot += __popcll(__ballot(i < cap && cum_at(min(i, cap)) <= u_lo));
             }
-        };
+            int s_len, s_first, s_end;  // the slot the walk stands in: tokens, first tile, tile after the last
+            long long s_ok, s_ov;
+            auto open_slot = [&]() {
+                if (slot - win_lo >= 63) fill_window(slot);  // entry slot + 1 must be in the window too
+                const int j = slot - win_lo;
+                s_len = lane_get(w_len, j);
+                s_first = lane_get(w_cum, j);
+                s_end = lane_get(w_cum, j + 1);
+                s_ok = lane_get64(w_ok, j);
+                s_ov = lane_get64(w_ov, j);
+            };
+            open_slot();
+            auto tile_at = [&](int u) {  // u >= the tile of the last call
+                while (u >= s_end) {
+                    ++slot;
+                    open_slot();
+                }
+                TileRef t;
+                t.len = s_len;
+                t.uin = u - s_first;
+                t.u_seq = u;
+                t.is_cur = slot >= n_hist;
+                t.ok = s_ok;
+                t.ov = s_ov;
+                return t;
+            };
 
-        auto consume = [&](const KVTile& t, int uin, int len, bool is_cur, int u_seq) {
-            const int tok0 = uin * kTile;
-            const bool full = !is_cur && (len - tok0 >= kTile);
+            floatx4_t acc[8];
+            float m = kNegBig, l = 0.f;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
+            for (int dt = 0; dt < 8; ++dt) acc[dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+            // Loads of a tile.  Halves that lie past the segment's end re-read its last 16-token block (their
+            // scores are masked), so every address stays inside the segment.
+            auto issue = [&](const TileRef& r, KVTile& t) {
+                const int len = r.len;
+                const int nblk = (len + 15) >> 4;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int blk = min(r.uin * 2 + h, nblk - 1);  // uniform
+                    const int rin = min(n, len - 1 - blk * 16);    // row inside the block, clamped
+                    if (r.is_cur) {
+                        const size_t e0 = (((size_t)b * a.cur_cap + blk * 16 + rin) * Hkv + g) * D128;
+                        const uint4* kp = reinterpret_cast<const uint4*>(ck + e0 * 2);
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) t.k[h][kk] = kp[kk * 4 + q4];
+                        // token-major values: gather 4 tokens of one channel with 2-byte loads
+                        const unsigned short* vp = reinterpret_cast<const unsigned short*>(cv);
+#pragma unroll
+                        for (int dt = 0; dt < 8; ++dt) {
+                            uint32_t e[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int tok = min(blk * 16 + q4 * 4 + j, len - 1);
+                                e[j] = vp[(((size_t)b * a.cur_cap + tok) * Hkv + g) * D128 + dt * 16 + n];
+                            }
+                            t.v[dt][h] = make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
+                        }
+                    } else {
+                        const char *kp, *vp;
+                        if (PAGED) {
+                            long long si = r.ok + blk;
+                            si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
+                            int pb = vw.block_table[(size_t)b * vw.max_blocks + si];
+                            pb = pb < 0 ? 0 : pb;
+                            kp = kbase + ((((size_t)pb * Hkv + g) * 16 + rin) * D128) * 2;
+                            vp = vbase + (((size_t)pb * Hkv + g) * D128 * 16) * 2;
+                        } else {
+                            const size_t L16 = (size_t)nblk * 16;
+                            kp = kbase + ((((size_t)r.ok * Hkv + (size_t)g * len + blk * 16 + rin) * D128)) * 2;
+                            vp = vbase + ((((size_t)r.ov * Hkv + (size_t)g * L16 + (size_t)blk * 16) * D128)) * 2;
+                        }
+                        const uint4* kq = reinterpret_cast<const uint4*>(kp);
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) t.k[h][kk] = kq[kk * 4 + q4];
+                        const uint2* vq = reinterpret_cast<const uint2*>(vp);
+#pragma unroll
+                        for (int dt = 0; dt < 8; ++dt) t.v[dt][h] = vq[(dt * 16 + n) * 4 + q4];  // 4 x 8 bytes per channel
+                    }
+                }
+            };
+
+            // Row r of the strip, tiles of this segment from index `first` on, to tile_lse in the score pass's
+            // row order [B][Hq][q_len]: 64 consecutive lanes write 64 consecutive tiles of one row.
+            auto flush_tile_lse = [&](int first, int count) {
+                __builtin_amdgcn_wave_barrier();  // same wave: LDS operations complete in program order
+                const int rows_here = min(16, rows_total - rowblock * 16);
+                for (int r = 0; r < rows_here; ++r) {
+                    const int rw = rowblock * 16 + r, qt = rw / G;
+                    const size_t head = (size_t)g * G + (rw - qt * G);
+                    float* dst = a.tile_lse + (((size_t)b * a.Hq + head) * q_len + qt) * a.n_tiles_max;
+                    const int ut = u_lo + first + lane;
+                    if (lane < count && ut < a.n_tiles_max) dst[ut] = lse_buf[r * kLsePitch + lane];
+                }
+                __builtin_amdgcn_wave_barrier();
+            };
+
+            auto consume = [&](const KVTile& t, const TileRef& r) {
+                const int tok0 = r.uin * kTile, len = r.len;
+                const bool full = !r.is_cur && (len - tok0 >= kTile);
                 floatx4_t sc[2];
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     sc[h] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) sc[h] = mfma16(t.k[h][kk], qf[nt][kk], sc[h]);
+                    for (int kk = 0; kk < 4; ++kk) sc[h] = mfma16(t.k[h][kk], qf[kk], sc[h]);
                 }
                 if (!full) {
                     // tokens this row may see: the segment's length, or inside the current round the causal limit
                     int lim = len;
-                    if (is_cur) lim = min(len, max(len - q_len + qtok[nt] + 1, 0));
-                    if (!row_ok[nt]) lim = 0;
+                    if (r.is_cur) lim = min(len, max(len - q_len + qtok + 1, 0));
+                    if (!row_ok) lim = 0;
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -267,39 +465,29 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                 float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                                  fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
                 mx = xrow_max4(mx);
-                const float m_new = fmaxf(m[nt], mx);
-                if (__any(m_new > m[nt])) {
-                    const float alpha = fast_exp2((m[nt] - m_new) * a.c);
-                    l[nt] *= alpha;
+                const float m_new = fmaxf(m, mx);
+                if (__any(m_new > m)) {
+                    const float alpha = fast_exp2((m - m_new) * a.c);
+                    l *= alpha;
 #pragma unroll
-                    for (int dt = 0; dt < 8; ++dt) acc[nt][dt] *= alpha;
-                    m[nt] = m_new;
+                    for (int dt = 0; dt < 8; ++dt) acc[dt] *= alpha;
+                    m = m_new;
                 }
-                const float mc = m[nt] * a.c;
+                const float mc = m * a.c;
                 float p[8];
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) p[h * 4 + i] = fast_exp2(__builtin_fmaf(sc[h][i], a.c, -mc));
                 const float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-                l[nt] += ps;
-                if constexpr (TILE_LSE == 1) {  // the tile's share of the softmax normaliser: the round scores' raw material
+                l += ps;
+                if constexpr (TILE_LSE) {  // the tile's share of the softmax normaliser: the round scores' raw material
                     const float pt = xrow_sum4(ps);
-                    if (q4 == 0 && row_ok[nt] && u_seq < a.n_tiles_max) {
-                        // row order of the score pass: [B][Hq][q_len]
-                        const size_t head = rowid[nt] - ((size_t)b * q_len + qtok[nt]) * a.Hq;
-                        const size_t srow = ((size_t)b * a.Hq + head) * q_len + qtok[nt];
-                        a.tile_lse[srow * a.n_tiles_max + u_seq] =
-                            pt > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(pt)) : -__builtin_inff();
-                    }
-                } else if constexpr (TILE_LSE == 2) {
-                    // Staged in LDS, [2 blocks of 64 tiles][16 rows][64 + 1]; flush_tile_lse writes a block out in
-                    // whole runs per row (one scattered 4-byte store per row and tile costs 14 % of a long pass).
-                    const float pt = xrow_sum4(ps);
-                    const int ut = u_seq - u_lo;
+                    const int ut = r.u_seq - u_lo;
                     if (q4 == 0)
-                        lse_buf[((ut >> 6) & 1) * kLseBlock + n * kLsePitch + (ut & 63)] =
-                            pt > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(pt)) : -__builtin_inff();
+                        lse_buf[n * kLsePitch + (ut & 63)] =
+                            pt > 0.f ? kLn2 * __builtin_fmaf(m, a.c, fast_log2(pt)) : -__builtin_inff();
+                    if ((ut & 63) == 63) flush_tile_lse(ut - 63, 64);
                 }
                 uint4 phi, plo;
                 phi.x = pack_trunc(p[0], p[1]);
@@ -313,195 +501,101 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt) {
                     const uint4 vf = make_uint4(t.v[dt][0].x, t.v[dt][0].y, t.v[dt][1].x, t.v[dt][1].y);
-                    acc[nt][dt] = mfma16(vf, phi, acc[nt][dt]);
-                    acc[nt][dt] = mfma16(vf, plo, acc[nt][dt]);
+                    acc[dt] = mfma16(vf, phi, acc[dt]);
+                    acc[dt] = mfma16(vf, plo, acc[dt]);
+                }
+            };
+
+            // ---- stream the tiles u_lo .. u_hi - 1 --------------------------------------------------------
+            // Two tile buffers used alternately: the loads of one tile are in flight while the other is consumed,
+            // and no register that is still being loaded is ever copied.
+            {
+                KVTile ta, tb;
+                TileRef ref_a, ref_b;
+                int u = u_lo;
+                ref_a = tile_at(u);
+                issue(ref_a, ta);
+                while (true) {
+                    ++u;
+                    const bool have_b = u < u_hi;
+                    if (have_b) {
+                        ref_b = tile_at(u);
+                        issue(ref_b, tb);
+                    }
+                    consume(ta, ref_a);
+                    if (!have_b) break;
+                    ++u;
+                    const bool have_a = u < u_hi;
+                    if (have_a) {
+                        ref_a = tile_at(u);
+                        issue(ref_a, ta);
+                    }
+                    consume(tb, ref_b);
+                    if (!have_a) break;
+                }
+                if constexpr (TILE_LSE) {
+                    const int done = u_hi - u_lo;
+                    if (done & 63) flush_tile_lse(done & ~63, done & 63);
                 }
             }
-        };
 
-        // Block k of the staged tile log-sum-exps (tiles u_lo + 64 k ...) to tile_lse, rows in the score pass's
-        // order [B][Hq][q_len]: 16 consecutive lanes write 16 consecutive tiles of one row.
-        auto flush_tile_lse = [&](int k) {
-            const int r = tid >> 4, rr = rowblock * RB + r;
-            if (rr >= rows_total) return;
-            const int qt = rr / G;
-            const size_t head = (size_t)g * G + (rr - qt * G);
-            float* dst = a.tile_lse + (((size_t)b * a.Hq + head) * q_len + qt) * a.n_tiles_max;
-            const float* src = lse_buf + (k & 1) * kLseBlock + r * kLsePitch;
+            // ---- the four lane groups hold partial sums of the same rows -------------------------------------
+            l = xrow_sum4(l);
+            if (parts.n_parts == 1) {
+                if (row_ok) {
+                    const float inv = l > 0.f ? 1.f / l : 0.f;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int col = (tid & 15) + 16 * i;
-                const int ut = u_lo + 64 * k + col;
-                if (ut < u_hi && ut < a.n_tiles_max) dst[ut] = src[col];
+                    for (int dt = 0; dt < 8; ++dt)
+                        *reinterpret_cast<floatx4_t*>(a.out + rowid * D128 + dt * 16 + q4 * 4) = acc[dt] * inv;
+                    if (a.lse && q4 == 0)
+                        a.lse[rowid] = l > 0.f ? __builtin_fmaf(m, a.scale, __builtin_logf(l)) : -__builtin_inff();
+                }
+                continue;
             }
-        };
 
-        // ---- stream the key tiles --------------------------------------------------------------------
-        {
-            const int step = 4;
-            int u = u_lo + wave;
-            bool have = u < u_hi;
-            int slot = 0;
-            // Two tile buffers used alternately: the loads of one tile are in flight while the other
-            // is consumed, and no register that is still being loaded is ever copied.
-            KVTile ta, tb;
-            int len_a = 0, uin_a = 0, len_b = 0, uin_b = 0, us_a = 0, us_b = 0;
-            bool cur_a = false, cur_b = false;
-            if (have) {
-                slot = find_slot(tab.cum, n_slots, u);
-                uin_a = u - tab.cum[slot];
-                us_a = u;
-                issue(uin_a, slot, ta, len_a, cur_a);
-            }
-            if constexpr (TILE_LSE == 2) {
-                // Same walk, but with a trip count every wave shares (a pair of tiles per wave and trip, eight
-                // tiles per workgroup), so that the workgroup can meet at a barrier after each block of 64 tiles
-                // and write that block out while the next one is computed into the other half of the buffer.
-                const int n_trips = (u_hi - u_lo + 7) >> 3;
-                for (int trip = 0; trip < n_trips; ++trip) {
-                    if (have) {
-                        u += step;
-                        const bool have_b = u < u_hi;
-                        if (have_b) {
-                            while (u >= tab.cum[slot + 1]) ++slot;
-                            uin_b = u - tab.cum[slot];
-                            us_b = u;
-                            issue(uin_b, slot, tb, len_b, cur_b);
-                        }
-                        consume(ta, uin_a, len_a, cur_a, us_a);
-                        have = false;
-                        if (have_b) {
-                            u += step;
-                            have = u < u_hi;
-                            if (have) {
-                                while (u >= tab.cum[slot + 1]) ++slot;
-                                uin_a = u - tab.cum[slot];
-                                us_a = u;
-                                issue(uin_a, slot, ta, len_a, cur_a);
-                            }
-                            consume(tb, uin_b, len_b, cur_b, us_b);
-                        }
-                    }
-                    if ((trip & 7) == 7 || trip == n_trips - 1) {
-                        __syncthreads();  // every wave's values of this block are in LDS
-                        flush_tile_lse(trip >> 3);
-                    }
-                }
-                __syncthreads();  // the staging buffer shares its memory with the merge below
-            } else
-            while (have) {
-                u += step;
-                const bool have_b = u < u_hi;
-                if (have_b) {
-                    while (u >= tab.cum[slot + 1]) ++slot;
-                    uin_b = u - tab.cum[slot];
-                    us_b = u;
-                    issue(uin_b, slot, tb, len_b, cur_b);
-                }
-                consume(ta, uin_a, len_a, cur_a, us_a);
-                if (!have_b) break;
-                u += step;
-                have = u < u_hi;
-                if (have) {
-                    while (u >= tab.cum[slot + 1]) ++slot;
-                    uin_a = u - tab.cum[slot];
-                    us_a = u;
-                    issue(uin_a, slot, ta, len_a, cur_a);
-                }
-                consume(tb, uin_b, len_b, cur_b, us_b);
+            // ---- the sequence lies in several ranges: leave this segment's partial result ---------------------
+            if (row_ok) {
+                const size_t rrow = ((size_t)rec * inner + gi) * 16 + n;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt)
+                    *reinterpret_cast<floatx4_t*>(a.rec_acc + rrow * D128 + dt * 16 + q4 * 4) = acc[dt];
+                if (q4 == 0) *reinterpret_cast<float2*>(a.rec_ml + rrow * 2) = make_float2(m, l);
             }
         }
-
-        RA_TS(3);
-        // ---- the four lane groups hold partial sums of the same rows ---------------------------------------
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            l[nt] = xrow_sum4(l[nt]);
-        }
-
-        {
-            // ---- merge the four waves (different tokens, same rows) through LDS ----------------------------
-            float* sm = red;          // [4][16]
-            float* sl = red + 64;     // [4][16]
-            float* sacc = red + 128;  // [4][16][128]
-            if (q4 == 0) {
-                sm[wave * 16 + n] = m[0];
-                sl[wave * 16 + n] = l[0];
-            }
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-                *reinterpret_cast<floatx4_t*>(sacc + ((wave * 16 + n) * D128) + dt * 16 + q4 * 4) = acc[0][dt];
-            __syncthreads();
-            const int rows_here = min(16, rows_total - rowblock * RB);
-            for (int idx = tid; idx < rows_here * D128; idx += 256) {
-                const int r = idx >> 7, dim = idx & 127;
-                const float M = fmaxf(fmaxf(sm[r], sm[16 + r]), fmaxf(sm[32 + r], sm[48 + r]));
-                float num = 0.f, den = 0.f;
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const float f = fast_exp2((sm[w * 16 + r] - M) * a.c);
-                    num = __builtin_fmaf(sacc[(w * 16 + r) * D128 + dim], f, num);
-                    den = __builtin_fmaf(sl[w * 16 + r], f, den);
-                }
-                const int rr = rowblock * RB + r;
-                const int qi = rr / G;
-                const size_t rid = ((size_t)b * q_len + qi) * a.Hq + (size_t)g * G + (rr - qi * G);
-                if (S_eff > 1) {
-                    const size_t pr = rid * a.S + s;
-                    a.part_acc[pr * D128 + dim] = num;
-                    if (dim == 0) {
-                        a.part_m[pr] = M;
-                        a.part_l[pr] = den;
-                    }
-                } else {
-                    a.out[rid * D128 + dim] = den > 0.f ? num / den : 0.f;
-                    if (a.lse && dim == 0)
-                        a.lse[rid] = den > 0.f ? __builtin_fmaf(M, a.scale, __builtin_logf(den)) : -__builtin_inff();
-                }
-            }
-        }
-        RA_TS(4);
     }
-    RA_TS(5);
 }
-
-RA_TS_DEFINE_READER(ra_debug_read_ts_attn)
 
 int launch_attn_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) {
     const int rows_total = a.q_len * a.G;
     const int B = a.view.B, Hkv = a.view.Hkv;
     if (a.G > 16) return fail(RA_ERR_UNSUPPORTED, "attention: Hq / Hkv = %d exceeds 16", a.G);
     if (B > kMaxBatch) return fail(RA_ERR_UNSUPPORTED, "attention: batch %d exceeds %d", B, kMaxBatch);
-    const size_t tab_bytes = align_up(SlotTable::bytes(a.view.R_max + 1), 16);
-    const int n_rowblocks = (rows_total + 15) / 16;
-    // Persistent launch: two workgroups per compute unit, but never more than the work items the batch
-    // can have at most (every sequence has at least one piece and at most S).
-    const long long max_tiles = (long long)B * (a.max_tokens / kTile + a.view.R_max + 1 + a.cur_cap / kTile + 1);
-    long long max_pieces = (long long)B + max_tiles / a.min_units;
-    if (max_pieces > (long long)B * a.S) max_pieces = (long long)B * a.S;
-    long long grid = (long long)2 * num_cu;
-    if (grid > max_pieces * Hkv * n_rowblocks) grid = max_pieces * Hkv * n_rowblocks;
-    if (grid < 1) grid = 1;
+    const MfmaDecodeShape s =
+        mfma_decode_shape(num_cu, B, a.view.R_max, Hkv, rows_total, mfma_max_tiles(B, a.max_tokens, a.view.R_max, a.cur_cap));
+    if (a.max_ranges != s.max_ranges) return fail(RA_ERR_INVALID_ARG, "attention: launch shape mismatch");
     const bool inline_plan = attn_mfma_plans_inline(B, a.view.R_max);
-    // tiles a piece is expected to hold: a sequence's tiles over the pieces it gets when the work is spread
-    // over the grid (at most S)
-    const long long tiles_seq = a.max_tokens / kTile + 1;
-    long long pieces_seq = grid * kPiecesPerWorkgroup / ((long long)B * Hkv * n_rowblocks);
-    pieces_seq = pieces_seq < 1 ? 1 : (pieces_seq > a.S ? a.S : pieces_seq);
-    const int lse_mode = !a.tile_lse ? 0 : (tiles_seq / pieces_seq >= 128 ? 2 : 1);
-    const size_t smem = tab_bytes + (128 + 4 * 16 * 128) * sizeof(float) +
+    const bool tile_lse = a.tile_lse != nullptr;
+    const size_t smem = (tile_lse ? (size_t)4 * 16 * kLsePitch * sizeof(float) : 0) +
                         (inline_plan ? attn_mfma_inline_bytes(B, a.view.R_max) : 0);
-    const dim3 g((unsigned)grid), blk(256);
+    const dim3 g((unsigned)s.grid), blk(256);
 #define RA_ATTN_CASE(P_, L_, I_)                                                                          \
-    if (paged == P_ && lse_mode == L_ && inline_plan == I_) {                                             \
-        RA_LAUNCH_TIMED((attn_mfma_kernel<P_, L_, I_>), g, blk, smem, st, a, n_rowblocks);                \
+    if (paged == P_ && tile_lse == L_ && inline_plan == I_) {                                             \
+        RA_LAUNCH_TIMED((attn_mfma_kernel<P_, L_, I_>), g, blk, smem, st, a, s.n_rowblocks);              \
         return RA_OK;                                                                                     \
     }
-    RA_ATTN_CASE(false, 0, false) RA_ATTN_CASE(false, 0, true) RA_ATTN_CASE(true, 0, false) RA_ATTN_CASE(true, 0, true)
-    RA_ATTN_CASE(false, 1, false) RA_ATTN_CASE(false, 1, true) RA_ATTN_CASE(true, 1, false) RA_ATTN_CASE(true, 1, true)
-    RA_ATTN_CASE(false, 2, false) RA_ATTN_CASE(false, 2, true) RA_ATTN_CASE(true, 2, false) RA_ATTN_CASE(true, 2, true)
+    RA_ATTN_CASE(false, false, false) RA_ATTN_CASE(false, false, true) RA_ATTN_CASE(true, false, false)
+    RA_ATTN_CASE(true, false, true) RA_ATTN_CASE(false, true, false) RA_ATTN_CASE(false, true, true)
+    RA_ATTN_CASE(true, true, false) RA_ATTN_CASE(true, true, true)
 #undef RA_ATTN_CASE
     return RA_OK;
+}
+
+// Second step of the matrix-core kernel above: merges the records of the sequences that were cut.
+void launch_merge_records(const AttnArgs& a, int num_cu, hipStream_t st) {
+    const MfmaDecodeShape s = mfma_decode_shape(num_cu, a.view.B, a.view.R_max, a.view.Hkv, a.q_len * a.G,
+                                                mfma_max_tiles(a.view.B, a.max_tokens, a.view.R_max, a.cur_cap));
+    if (s.max_ranges <= 1) return;  // a single range never cuts a sequence
+    hipLaunchKernelGGL(merge_records_kernel, dim3((unsigned)(a.view.B * s.inner)), dim3(256), 0, st, a, s.n_rowblocks);
 }
 
 }  // namespace ra

@@ -22,7 +22,6 @@
 #include "attn_common.hpp"
 #include "mfma_util.hpp"
 #include "stream_kv.hpp"
-#include "debug_ts.hpp"
 
 namespace ra {
 
@@ -42,7 +41,6 @@ template <bool PAGED, bool TILE_LSE>
 __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
-    RA_TS(0);
     const DevView& vw = a.view;
     const int Hkv = vw.Hkv;
     const int tid = threadIdx.x;
@@ -68,8 +66,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
     const char* ck = reinterpret_cast<const char*>(a.cur_k);
     const char* cv = reinterpret_cast<const char*>(a.cur_v);
     const long long n_items = (long long)P * inner;
-    RA_TS(1);
-    RA_LAP_DECL;
 
     for (long long item = blockIdx.x; item < n_items; item += gridDim.x) {
         const int piece = (int)(item / inner);
@@ -281,7 +277,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                 mx[nt] = max8(sc[nt][0], sc[nt][1]);
                 raise |= mx[nt] > m[nt] + slack;
             }
-            RA_LAP(2);
             if (__any(raise)) {
 #pragma unroll
                 for (int nt = 0; nt < kNTP; ++nt) {
@@ -333,11 +328,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             accumulate(0, phi0, plo0);
             probabilities(1, phi1, plo1);
             accumulate(1, phi1, plo1);
-            RA_LAP(3);
         };
 
         // ---- walk the key tiles: the whole workgroup in lockstep -----------------------------------------
-        RA_TS(2);
         if (u_lo < u_hi) {
             int slot = find_slot(tab.cum, n_slots, u_lo);
             open_seg(slot, u_lo);
@@ -346,13 +339,11 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             int bufsel = 0;
             for (int u = u_lo; u < u_hi; ++u) {
                 char* buf = tiles + bufsel * kTileBytes;
-                RA_LAP_START;
                 store_share(buf, sh);
                 const int len = seg_len, tok0 = c_tok0;  // of the tile just stored
                 const bool is_cur = seg_cur;
                 const int t_slot = slot, t_first = seg_first, t_end = seg_end;
                 __syncthreads();
-                RA_LAP(0);
                 if (u + 1 < u_hi) {
                     if (u + 1 >= seg_end) {
                         do ++slot; while (u + 1 >= uni(tab.cum[slot + 1]));
@@ -361,9 +352,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                     c_tok0 = seg_len - rows_left;
                     sh = load_share();
                 }
-                RA_LAP(1);
                 consume(buf, tok0, len, is_cur);
-                RA_LAP(5);
                 if constexpr (TILE_LSE) {
                     const int uin = u - t_first;
                     if ((uin & 7) == 7 || u + 1 == t_end || u + 1 == u_hi) {  // the chunk ends with this tile
@@ -386,7 +375,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             }
         }
 
-        RA_TS(3);
         // ---- the four lane groups hold partial sums of the same rows; each wave owns its rows ------------------
 #pragma unroll
         for (int nt = 0; nt < kNTP; ++nt) {
@@ -411,13 +399,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                         l[nt] > 0.f ? __builtin_fmaf(m[nt], a.scale, __builtin_logf(l[nt])) : -__builtin_inff();
             }
         }
-        RA_TS(4);
     }
-    RA_TS(5);
-    RA_LAP_FLUSH(8);
 }
 
-RA_TS_DEFINE_READER(ra_debug_read_ts_prefill)
 
 int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStream_t st) {
     const int rows_total = a.q_len * a.G;

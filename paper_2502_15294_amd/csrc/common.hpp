@@ -86,9 +86,14 @@ int decode_splits(int num_cu, int B, int Hkv, int64_t max_tokens);
 
 constexpr int kUnitTokens = 16;   // tokens per work unit of the streaming kernels (= one paged block)
 constexpr int kMaxRounds = 1024;  // largest R_max any entry point accepts
-// Head of the workspace kept for small integer state (arrival counters) that must read zero at the
-// start of every launch: ra_set_workspace clears it once and the kernels restore it.
-constexpr size_t kWsReserved = 16384;
+constexpr int kMaxBatch = 1024;   // largest batch of the matrix-core attention kernels (their schedule lives in LDS)
+// Head of the workspace kept for small integer state (ra_set_workspace clears it once; nothing relies on that):
+//   [0, 16384)       pieces every sequence was cut into by the last generic / many-row attention call
+//   [16384, 24576)   first record and number of records of every sequence, matrix-core decode kernel
+//   last 64 bytes    a spare word for the bandwidth probe
+constexpr size_t kWsSmallState = 16384;
+constexpr size_t kWsSeqRecOff = 16384;
+constexpr size_t kWsReserved = 32768;
 
 // ---- device helpers --------------------------------------------------------------------------
 constexpr float kLog2e = 1.4426950408889634f;

@@ -190,7 +190,15 @@ int ra_workspace_bytes(const ra_problem* p, size_t* bytes_out) {
     RA_REQUIRE(p->Hq % p->Hkv == 0, RA_ERR_INVALID_ARG, "ra_workspace_bytes: Hq %% Hkv != 0");
     const size_t rows = (size_t)p->B * p->q_len_max * p->Hq;
     // attention partials: up to 64 splits of (d accumulators + running max + running sum) per output row
-    const size_t attn = rows * 64 * ((size_t)p->d + 2) * sizeof(float);
+    size_t attn = rows * 64 * ((size_t)p->d + 2) * sizeof(float);
+    // ... or, in the matrix-core kernel for few query rows, one partial result of 16 rows per (range, KV head, row
+    // block) and per (sequence, KV head, row block): at most 4096 wavefronts with a range each, and never more
+    // ranges than half the batch's 32-token key tiles
+    const size_t inner2 = (size_t)p->Hkv * 2;
+    size_t slots = ((size_t)p->B * ((size_t)(p->max_tokens / 32) + p->R_max + 2) / 2 + 1) * inner2;
+    if (slots > 4096) slots = 4096;
+    const size_t few = (slots + (size_t)p->B * inner2) * 16 * ((size_t)p->d + 2) * sizeof(float) + 512;
+    if (few > attn) attn = few;
     // score intermediates: one log-sum-exp per (row, 256-token chunk), plus up to eight partial per-head score rows
     const size_t chunks = (size_t)(p->max_tokens / 256) + p->R_max + 2;
     const size_t sc = rows * chunks * sizeof(float) + (size_t)8 * p->B * p->Hq * p->R_max * sizeof(float) + 256;
@@ -211,7 +219,7 @@ int ra_set_workspace(ra_ctx* ctx, void* device_ptr, size_t bytes) {
     RA_REQUIRE(((uintptr_t)device_ptr & 255u) == 0, RA_ERR_INVALID_ARG, "ra_set_workspace: pointer not 256-byte aligned");
     RA_REQUIRE(bytes == 0 || bytes >= kWsReserved, RA_ERR_WORKSPACE,
                "ra_set_workspace: a workspace must have at least %zu bytes", kWsReserved);
-    if (bytes) RA_HIP_CHECK(hipMemset(device_ptr, 0, kWsReserved));  // arrival counters start at zero
+    if (bytes) RA_HIP_CHECK(hipMemset(device_ptr, 0, kWsReserved));
     ctx->ws.base = (char*)device_ptr;
     ctx->ws.bytes = bytes;
     return RA_OK;

@@ -385,8 +385,8 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
     else
         RA_REQUIRE(G == 1 || G == 2 || G == 4 || G == 8, RA_ERR_UNSUPPORTED,
                    "decode: Hq / Hkv = %d not in {1, 2, 4, 8} for this dtype / head_dim", G);
-    RA_REQUIRE((size_t)B * sizeof(int) <= kWsReserved, RA_ERR_UNSUPPORTED, "decode: B = %d exceeds %zu", B,
-               kWsReserved / sizeof(int));
+    RA_REQUIRE((size_t)B * sizeof(int) <= kWsSmallState, RA_ERR_UNSUPPORTED, "decode: B = %d exceeds %zu", B,
+               kWsSmallState / sizeof(int));
 
     const bool with_scores = scores != nullptr;
     if (with_scores) {
@@ -395,19 +395,38 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
     }
 
     const int64_t max_tok = layer->max_tokens + (has_cur ? cur_cap : 0);
-    const int S = mfma ? mfma_max_pieces(max_tok, attn_min_units(), 64) : decode_splits(ctx->num_cu, B, layer->Hkv, max_tok);
     const size_t rows = (size_t)B * Hq;
-    const AttnWorkspace w = attn_workspace(rows, S, D, B, layer->R_max);
+    // scratch: the matrix-core kernel keeps one partial result per (range, sequence) it cuts; the generic kernel
+    // one per (sequence, split)
+    MfmaDecodeShape shape = {};
+    size_t plan_off, scratch_total;
+    int S = 1;
+    AttnWorkspace w = {};
+    MfmaDecodeWorkspace mw = {};
+    if (mfma) {
+        RA_REQUIRE(B <= kMaxBatch, RA_ERR_UNSUPPORTED, "decode: batch %d exceeds %d", B, kMaxBatch);
+        const long long max_tiles = mfma_max_tiles(B, layer->max_tokens, layer->R_max, has_cur ? cur_cap : 0);
+        RA_REQUIRE(max_tiles < ((long long)1 << 30), RA_ERR_UNSUPPORTED, "decode: max_tokens too large for this batch");
+        shape = mfma_decode_shape(ctx->num_cu, B, layer->R_max, layer->Hkv, G, max_tiles);
+        mw = mfma_decode_workspace(shape, B, layer->R_max);
+        plan_off = mw.plan_off;
+        scratch_total = mw.total;
+    } else {
+        S = decode_splits(ctx->num_cu, B, layer->Hkv, max_tok);
+        w = attn_workspace(rows, S, D, B, layer->R_max);
+        plan_off = w.plan_off;
+        scratch_total = w.total;
+    }
     // one entry per 32-token tile of a sequence's table: history rounds (each rounded up), then the current round
     const int64_t n_tiles64 = layer->max_tokens / 32 + layer->R_max + (has_cur ? cur_cap / 32 + 1 : 0);
     RA_REQUIRE(!with_scores || n_tiles64 <= (int64_t)1 << 24, RA_ERR_UNSUPPORTED, "watershed decode: max_tokens too large");
     const int n_tiles_max = (int)n_tiles64;
     const size_t tile_bytes = with_scores ? align_up(rows * n_tiles_max * sizeof(float), 256) : 0;
     const size_t p_bytes = with_scores ? scores_finish_part_bytes(1, B, Hq, layer->R_max, n_tiles_max) : 0;
-    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total + tile_bytes + p_bytes, RA_ERR_WORKSPACE,
-               "decode: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total + tile_bytes + p_bytes);
+    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= scratch_total + tile_bytes + p_bytes, RA_ERR_WORKSPACE,
+               "decode: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, scratch_total + tile_bytes + p_bytes);
 
-    AttnArgs a;
+    AttnArgs a = {};
     a.view = to_dev(layer);
     a.q = q;
     a.sel_idx = sel_idx;
@@ -422,18 +441,22 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
     a.Hq = Hq;
     a.G = G;
     a.S = S;
-    a.min_units = attn_min_units();
+    a.min_units = mfma ? kMfmaMinUnits : attn_min_units();
     a.c = scale * kLog2e;
     a.scale = scale;
-    a.part_acc = reinterpret_cast<float*>(ctx->ws.base + w.acc_off);
-    a.part_m = reinterpret_cast<float*>(ctx->ws.base + w.m_off);
-    a.part_l = reinterpret_cast<float*>(ctx->ws.base + w.l_off);
+    a.part_acc = mfma ? nullptr : reinterpret_cast<float*>(ctx->ws.base + w.acc_off);
+    a.part_m = mfma ? nullptr : reinterpret_cast<float*>(ctx->ws.base + w.m_off);
+    a.part_l = mfma ? nullptr : reinterpret_cast<float*>(ctx->ws.base + w.l_off);
     a.n_parts = reinterpret_cast<int*>(ctx->ws.base);
-    a.plan = ctx->ws.base + w.plan_off;
+    a.plan = ctx->ws.base + plan_off;
     a.out = out;
     a.lse = lse;
-    a.tile_lse = with_scores ? reinterpret_cast<float*>(ctx->ws.base + w.total) : nullptr;
+    a.tile_lse = with_scores ? reinterpret_cast<float*>(ctx->ws.base + scratch_total) : nullptr;
     a.n_tiles_max = with_scores ? n_tiles_max : 0;
+    a.rec_acc = mfma ? reinterpret_cast<float*>(ctx->ws.base + mw.rec_off) : nullptr;
+    a.rec_ml = mfma ? reinterpret_cast<float*>(ctx->ws.base + mw.ml_off) : nullptr;
+    a.seq_rec = reinterpret_cast<int*>(ctx->ws.base + kWsSeqRecOff);
+    a.max_ranges = shape.max_ranges;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool paged = layer->block_size != 0;
@@ -454,7 +477,8 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
         }
     }
     if (rc) return rc;
-    if (S > 1) launch_combine(a, D, rows, st);
+    if (mfma) launch_merge_records(a, ctx->num_cu, st);
+    else if (S > 1) launch_combine(a, D, rows, st);
     if (with_scores) {
         // With a single query token the current round cancels in the normalisation over history rounds: the
         // finishing kernel reads the history tiles only.
@@ -471,7 +495,7 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
         f.has_cur = false;
         f.p_out = scores_head;
         f.s_out = scores;
-        launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + w.total + tile_bytes), st);
+        launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + scratch_total + tile_bytes), st);
     }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;

@@ -32,17 +32,32 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
                "prefill: only bf16 with head_dim 128 is implemented");
     const int G = Hq / layer->Hkv, B = layer->B, D = 128;
     RA_REQUIRE(G <= 16, RA_ERR_UNSUPPORTED, "prefill: Hq / Hkv = %d exceeds 16", G);
-    RA_REQUIRE((size_t)B * sizeof(int) <= kWsReserved, RA_ERR_UNSUPPORTED, "prefill: B = %d exceeds %zu", B,
-               kWsReserved / sizeof(int));
+    RA_REQUIRE(B <= kMaxBatch, RA_ERR_UNSUPPORTED, "prefill: batch %d exceeds %d", B, kMaxBatch);
 
-    const int S = mfma_max_pieces(layer->max_tokens + cur_len, attn_min_units(), q_len * G <= 32 ? 64 : 8);
+    // Few query rows per KV head: the decode kernel (one wave per range of key tiles and block of 16 rows);
+    // otherwise the kernel whose waves own different rows and share each key tile through LDS.
+    const bool few_rows = q_len * G <= 32;
     const size_t rows = (size_t)B * q_len * Hq;
-    const AttnWorkspace w = attn_workspace(rows, S, D, B, layer->R_max);
+    MfmaDecodeShape shape = {};
+    MfmaDecodeWorkspace mw = {};
+    AttnWorkspace w = {};
+    int S = 1;
+    size_t plan_off, scratch_total;
+    if (few_rows) {
+        const long long max_tiles = mfma_max_tiles(B, layer->max_tokens, layer->R_max, cur_len);
+        RA_REQUIRE(max_tiles < ((long long)1 << 30), RA_ERR_UNSUPPORTED, "prefill: max_tokens too large for this batch");
+        shape = mfma_decode_shape(ctx->num_cu, B, layer->R_max, layer->Hkv, q_len * G, max_tiles);
+        mw = mfma_decode_workspace(shape, B, layer->R_max);
+        plan_off = mw.plan_off;
+        scratch_total = mw.total;
+    } else {
+        S = mfma_max_pieces(layer->max_tokens + cur_len, attn_min_units(), 8);
+        w = attn_workspace(rows, S, D, B, layer->R_max);
+        plan_off = w.plan_off;
+        scratch_total = w.total;
+    }
     const bool with_scores = scores != nullptr;
     RA_REQUIRE(!with_scores || layer->R_max > 0, RA_ERR_INVALID_ARG, "watershed prefill: R_max is 0, there is nothing to score");
-    // Few query rows per KV head: the decode kernel's token split keeps all four waves busy; otherwise
-    // the kernel whose waves own different rows and share each key tile through LDS.
-    const bool few_rows = q_len * G <= 32;
     // score output: one entry per 32-token tile (decode kernel) or per 256-token chunk (many-row kernel) of a
     // sequence's table: history rounds (each rounded up), then the current round
     const int score_unit = few_rows ? 32 : 256;
@@ -51,10 +66,10 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
     const int n_tiles_max = (int)n_tiles64;
     const size_t tile_bytes = with_scores ? align_up(rows * n_tiles_max * sizeof(float), 256) : 0;
     const size_t p_bytes = with_scores ? scores_finish_part_bytes(q_len, B, Hq, layer->R_max, n_tiles_max) : 0;
-    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= w.total + tile_bytes + p_bytes, RA_ERR_WORKSPACE,
-               "prefill: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, w.total + tile_bytes + p_bytes);
+    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= scratch_total + tile_bytes + p_bytes, RA_ERR_WORKSPACE,
+               "prefill: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, scratch_total + tile_bytes + p_bytes);
 
-    AttnArgs a;
+    AttnArgs a = {};
     a.view = to_dev(layer);
     a.q = q;
     a.sel_idx = sel_idx;
@@ -69,18 +84,22 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
     a.Hq = Hq;
     a.G = G;
     a.S = S;
-    a.min_units = attn_min_units();
+    a.min_units = few_rows ? kMfmaMinUnits : attn_min_units();
     a.c = scale * kLog2e;
     a.scale = scale;
-    a.part_acc = reinterpret_cast<float*>(ctx->ws.base + w.acc_off);
-    a.part_m = reinterpret_cast<float*>(ctx->ws.base + w.m_off);
-    a.part_l = reinterpret_cast<float*>(ctx->ws.base + w.l_off);
+    a.part_acc = few_rows ? nullptr : reinterpret_cast<float*>(ctx->ws.base + w.acc_off);
+    a.part_m = few_rows ? nullptr : reinterpret_cast<float*>(ctx->ws.base + w.m_off);
+    a.part_l = few_rows ? nullptr : reinterpret_cast<float*>(ctx->ws.base + w.l_off);
     a.n_parts = reinterpret_cast<int*>(ctx->ws.base);
-    a.plan = ctx->ws.base + w.plan_off;
+    a.plan = ctx->ws.base + plan_off;
     a.out = out;
     a.lse = lse;
-    a.tile_lse = with_scores ? reinterpret_cast<float*>(ctx->ws.base + w.total) : nullptr;
+    a.tile_lse = with_scores ? reinterpret_cast<float*>(ctx->ws.base + scratch_total) : nullptr;
     a.n_tiles_max = with_scores ? n_tiles_max : 0;
+    a.rec_acc = few_rows ? reinterpret_cast<float*>(ctx->ws.base + mw.rec_off) : nullptr;
+    a.rec_ml = few_rows ? reinterpret_cast<float*>(ctx->ws.base + mw.ml_off) : nullptr;
+    a.seq_rec = reinterpret_cast<int*>(ctx->ws.base + kWsSeqRecOff);
+    a.max_ranges = shape.max_ranges;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (!(few_rows && attn_mfma_plans_inline(B, layer->R_max))) launch_plan(a, 32, st);
     {
@@ -89,7 +108,8 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
                               : launch_attn_prefill_mfma(a, layer->block_size != 0, ctx->num_cu, st))
             return rc;
     }
-    if (S > 1) launch_combine(a, D, rows, st);
+    if (few_rows) launch_merge_records(a, ctx->num_cu, st);
+    else if (S > 1) launch_combine(a, D, rows, st);
     if (with_scores) {
         // Eq. 1 over history rounds and, for several query tokens, the visible part of the question itself
         // (with one query token the current round cancels in the normalisation over history rounds).
@@ -106,7 +126,7 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
         f.chunk_tokens = score_unit;
         f.p_out = scores_head;
         f.s_out = scores;
-        launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + w.total + tile_bytes), st);
+        launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + scratch_total + tile_bytes), st);
     }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;

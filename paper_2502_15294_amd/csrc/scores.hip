@@ -543,12 +543,12 @@ static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int 
     const size_t p_bytes = scores_finish_part_bytes(q_len, B, Hq, R_max, n_chunks_max);
     // more than 16 query rows per KV head on the matrix cores: persistent kernel driven by segment tables
     const bool many_rows = mfma && q_len * G > 16;
+    if (mfma) RA_REQUIRE(G <= 16, RA_ERR_UNSUPPORTED, "round_scores: Hq / Hkv = %d exceeds 16", G);
+    if (many_rows) RA_REQUIRE(B <= kMaxBatch, RA_ERR_UNSUPPORTED, "round_scores: batch %d exceeds %d", B, kMaxBatch);
     const size_t plan_bytes = many_rows ? align_up((size_t)B * plan_stride(R_max + 1), 256) : 0;
     RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= kWsReserved + part_bytes + p_bytes + plan_bytes,
                RA_ERR_WORKSPACE, "round_scores: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes,
                kWsReserved + part_bytes + p_bytes + plan_bytes);
-    RA_REQUIRE(!many_rows || (size_t)B * sizeof(int) <= kWsReserved, RA_ERR_UNSUPPORTED, "round_scores: B = %d exceeds %zu",
-               B, kWsReserved / sizeof(int));
 
     ScoreArgs a;
     a.view = to_dev(watershed);

@@ -10,7 +10,6 @@
 // take two key tiles each, all loads issued up front, and are merged through LDS.
 #include "scores_common.hpp"
 #include "mfma_util.hpp"
-#include "debug_ts.hpp"
 
 namespace ra {
 
@@ -24,7 +23,6 @@ template <bool PAGED>
 __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     extern __shared__ __align__(16) char smem[];
     __shared__ float sm[4][16], sl[4][16];
-    RA_TS(0);
     const DevView& vw = a.view;
     const int Hkv = vw.Hkv;
     const int c = blockIdx.x, b = blockIdx.z;
@@ -64,7 +62,6 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     }
     exclusive_scan_units(t_cum, n_slots);
     const int total = n_slots > 0 ? t_cum[n_slots] : 0;
-    RA_TS(1);
     if (c >= total) return;
     const int slot = find_slot(t_cum, n_slots, c);
     const int len = t_len[slot];
@@ -170,7 +167,6 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
             if (tok0[j] < len) consume(t[j], tok0[j]);
     }
 
-    RA_TS(3);
     // ---- merge the four lane groups of every row
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -197,10 +193,8 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
                 den > 0.f ? kLn2 * __builtin_fmaf(M, a.c, fast_log2(den)) : -__builtin_inff();
         }
     }
-    RA_TS(4);
 }
 
-RA_TS_DEFINE_READER(ra_debug_read_ts_scores)
 
 int launch_scores_mfma(const ScoreArgs& a, bool paged, int /*num_cu*/, hipStream_t st) {
     const int G = a.Hq / a.view.Hkv;

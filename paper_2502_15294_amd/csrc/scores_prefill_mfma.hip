@@ -19,7 +19,6 @@
 #include "scores_common.hpp"
 #include "mfma_util.hpp"
 #include "stream_kv.hpp"
-#include "debug_ts.hpp"
 
 namespace ra {
 
@@ -80,8 +79,6 @@ template <bool PAGED>
 __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_kernel(ScoreArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
-    RA_TS(0);
-    RA_LAP_DECL;
     const DevView& vw = a.view;
     const int Hkv = vw.Hkv;
     const int tid = threadIdx.x;
@@ -238,7 +235,6 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
                             if (tok0 + h * 16 + q4 * 4 + i >= lim) sc[nt][h][i] = -__builtin_inff();
                 }
             }
-            RA_LAP(2);
             float mx[kNTS];
             bool raise = false;
 #pragma unroll
@@ -294,13 +290,11 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
         int bufsel = 0;
         while (true) {
             char* buf = tiles + bufsel * kKTileBytes;
-            RA_LAP_START;
             store_share(buf, k0, k1);
             // the tile just stored, as the consumer needs it; it ends its chunk if the chunk or the segment ends
             const int c_len = seg_len, c_u = lu, c_t = c_tok0;
             const bool c_cur = seg_cur, c_last = lj + 1 == kTilesPerChunk || rows_left <= 0;
             __syncthreads();
-            RA_LAP(0);
             bool more = true;
             if (!c_last) {
                 ++lj;
@@ -318,22 +312,14 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
                 c_tok0 = seg_len - rows_left;
                 load_share(k0, k1);
             }
-            RA_LAP(1);
             consume(buf, c_t, c_len, c_cur);
-            RA_LAP(4);
             if (c_last) finish_chunk(c_u);
-            RA_LAP(5);
-            RA_LAP_COUNT(6, 1);
-            RA_LAP_COUNT(7, c_last ? 1 : 0);
             if (!more) break;
             bufsel ^= 1;
         }
     }
-    RA_TS(5);
-    RA_LAP_FLUSH(8);
 }
 
-RA_TS_DEFINE_READER(ra_debug_read_ts_scores_prefill)
 
 void launch_scores_plan(const ScoreArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(scores_plan_kernel, dim3(a.view.B), dim3(256), (size_t)(a.view.R_max + 2) * 2 * sizeof(int), st, a,

@@ -204,7 +204,6 @@ __device__ inline void exclusive_scan_units(int* cum, int n) {
 // so that pieces have about equal size whatever the selection sizes are, and the batch has about
 // `slots` pieces in total.  sU[b] = U_b, sps = exclusive prefix of n_b (sps[B] = number of pieces).
 // Must be called by all threads of the workgroup.
-constexpr int kMaxBatch = 1024;
 // Same, from unit counts already in sU[0..B) (written by all threads before the call, no barrier needed).
 __device__ inline int schedule_from_counts(int B, int S, int min_units, long long slots, int* sU, int* sps);
 

@@ -272,7 +272,7 @@ def test_workspace_and_argument_errors():
     eng = Engine(w)
     view = device_view(w, 1)
     q = to_device(w.q(1)[:, 0], w.dtype)
-    ra.ra_set_workspace(eng.ctx, eng.workspace[:16384])
+    ra.ra_set_workspace(eng.ctx, eng.workspace[:32768])
     with pytest.raises(ra.RaError) as e:
         ra.ra_round_sparse_attn_decode(eng.ctx, q, view, scale=w.scale)
     assert e.value.code == ra.RA_ERR_WORKSPACE
@@ -289,6 +289,48 @@ def test_workspace_and_argument_errors():
         ra.ra_round_sparse_attn_decode(eng.ctx, q, view, sel_idx, None, scale=w.scale)
     assert e.value.code == ra.RA_ERR_INVALID_ARG
     eng.close()
+
+
+def test_shapes_beyond_the_limits_are_rejected_before_anything_is_launched():
+    """A batch above 1024 and more than 16 query heads per KV head are refused by the matrix-core paths with
+    RA_ERR_UNSUPPORTED, by the argument checks (the outputs, filled with a marker, stay untouched)."""
+    ctx = ra.ra_create(0)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    ra.ra_set_workspace(ctx, ws)
+
+    def tiny_view(B, Hkv):
+        k = torch.zeros((B * 16 * Hkv * 128,), dtype=torch.bfloat16, device="cuda")
+        seg_off = torch.arange(B, dtype=torch.int64, device="cuda").reshape(B, 1) * 16
+        seg_len = torch.full((B, 1), 16, dtype=torch.int32, device="cuda")
+        n_rounds = torch.ones((B,), dtype=torch.int32, device="cuda")
+        return ra.KVView(k, k.clone(), seg_off, seg_len, n_rounds, Hkv, 128, 16)
+
+    marker = 12345.0
+    # batch of 1025
+    v = tiny_view(1025, 1)
+    q = torch.zeros((1025, 1, 128), dtype=torch.bfloat16, device="cuda")
+    out = torch.full((1025, 1, 128), marker, dtype=torch.float32, device="cuda")
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_round_sparse_attn_decode(ctx, q, v, scale=0.1, out=out)
+    assert e.value.code == ra.RA_ERR_UNSUPPORTED
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_round_sparse_attn_prefill(ctx, q.reshape(1025, 1, 1, 128), v, scale=0.1, out=out.reshape(1025, 1, 1, 128))
+    assert e.value.code == ra.RA_ERR_UNSUPPORTED
+    # 32 query heads on one KV head
+    v = tiny_view(2, 1)
+    q = torch.zeros((2, 32, 128), dtype=torch.bfloat16, device="cuda")
+    out2 = torch.full((2, 32, 128), marker, dtype=torch.float32, device="cuda")
+    S = torch.full((2, 1), marker, dtype=torch.float32, device="cuda")
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_round_sparse_attn_decode(ctx, q, v, scale=0.1, out=out2)
+    assert e.value.code == ra.RA_ERR_UNSUPPORTED
+    for q_len in (1, 4):                                   # both score kernels
+        with pytest.raises(ra.RaError) as e:
+            ra.ra_round_scores(ctx, torch.zeros((2, q_len, 32, 128), dtype=torch.bfloat16, device="cuda"), v, scale=0.1, scores=S)
+        assert e.value.code == ra.RA_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert (out == marker).all() and (out2 == marker).all() and (S == marker).all()
+    ra.ra_destroy(ctx)
 
 
 # --------------------------------------------------------------------------- question prefill (matrix cores)
