@@ -200,6 +200,18 @@ int ra_select_rounds(ra_ctx* ctx, void* stream, const float* scores, const int32
                      const ra_select_params* params, int32_t* sel_idx, int32_t* n_sel);
 
 /*
+ * Round scores and round selection in one call (Sec. 3.2 step 3: "identify the top-k relevant rounds" with the
+ * watershed layer's attention; Sec. 3.1 Eq. 1 followed by Sec. 3.3).  Same arguments and outputs as
+ * ra_round_scores followed by ra_select_rounds on its `scores`; the workgroup that finishes a sequence's scores
+ * selects its rounds while they are still on chip, which saves a kernel launch on the path of every question.
+ * scores_head, scores, sel_idx and n_sel are bitwise what the two separate calls give.
+ *   params   as for ra_select_rounds;  sel_idx device int32 [B][R_max];  n_sel device int32 [B]
+ */
+int ra_round_scores_select(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq, const ra_kv_view* watershed,
+                           const void* cur_k, int cur_len, float scale, const ra_select_params* params,
+                           float* scores_head, float* scores, int32_t* sel_idx, int32_t* n_sel);
+
+/*
  * Round-sparse decode attention (Sec. 3.2 step 5): one query token per sequence attends over the
  * tokens of the selected rounds of `layer` plus the first cur_len[b] tokens of the current round.
  *   q        device [B][Hq][d]
@@ -305,9 +317,13 @@ typedef struct ra_store_cfg {
 } ra_store_cfg;
 
 typedef enum ra_stage_order {
-    RA_STAGE_ROUND_MAJOR = 0, /* one copy per selected round (the paper's monolithic transfer)        */
-    RA_STAGE_LAYER_MAJOR = 1  /* one copy per (layer, round), layer by layer, so that the first
-                                 post-watershed layer can start before the last one has arrived  */
+    RA_STAGE_ROUND_MAJOR = 0, /* one copy per selected round (the paper's monolithic transfer).  Every layer
+                                 becomes ready only when the last round has arrived: no overlap with compute   */
+    RA_STAGE_LAYER_MAJOR = 1, /* one copy per (layer, round), layer by layer: the first post-watershed layer can
+                                 start after 1 / n_layers of the transfer, at the price of n_layers times the copies */
+    RA_STAGE_GROUPED = 2      /* one copy per (group of consecutive layers, round): a first group of n_layers / 8
+                                 layers, then groups of n_layers / 4.  Overlaps like LAYER_MAJOR with a fifth of its
+                                 copies; the order to use when compute should overlap the transfer (Sec. 3.2)  */
 } ra_stage_order;
 
 int ra_kv_store_create(ra_kv_store** out, const ra_store_cfg* cfg);

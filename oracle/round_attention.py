@@ -27,6 +27,7 @@ Readings where the paper is silent (each is listed in the design notes too):
     rounds are kept.
 
 Parity unpinned (no value in the paper fixes them): the default lambda = 1 and ddof = 0.
+The two error measures at the end of the file (row_error, large_entry_error) are pinned by hand values.
 
 Shapes, per sequence: q [q_len, Hq, d]; a round's keys/values [len_r, Hkv, d];
 cur_k / cur_v [cur_len, Hkv, d].
@@ -239,3 +240,15 @@ def row_error(out, ref) -> float:
     num = np.abs(out - ref).max(axis=-1)
     den = np.abs(ref).max(axis=-1)
     return float((num / den).max())
+
+
+def large_entry_error(out, ref, floor: float = 0.05) -> float:
+    """Second error measure: the largest elementwise relative error |out - ref| / |ref| over the entries whose
+    reference value is at least `floor` times the largest magnitude of their row (entries near zero, where a
+    relative error says nothing, are left out).  0.0 if no entry qualifies."""
+    out, ref = _f64(out), _f64(ref)
+    big = np.abs(ref) >= floor * np.abs(ref).max(axis=-1, keepdims=True)
+    big &= ref != 0.0
+    if not big.any():
+        return 0.0
+    return float((np.abs(out - ref)[big] / np.abs(ref)[big]).max())

@@ -20,14 +20,14 @@ LIB_PATH = os.environ.get("RA_LIBRARY") or os.path.join(_HERE, "libround_attenti
 
 RA_F32, RA_BF16 = 0, 1
 RA_SEL_ADAPTIVE, RA_SEL_TOP_FRACTION, RA_SEL_THRESHOLD = 0, 1, 2
-RA_STAGE_ROUND_MAJOR, RA_STAGE_LAYER_MAJOR = 0, 1
+RA_STAGE_ROUND_MAJOR, RA_STAGE_LAYER_MAJOR, RA_STAGE_GROUPED = 0, 1, 2
 RA_OK, RA_ERR_INVALID_ARG, RA_ERR_UNSUPPORTED, RA_ERR_WORKSPACE, RA_ERR_STATE, RA_ERR_OOM, RA_ERR_HIP = \
     0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "ra_last_error", "ra_create", "ra_destroy", "ra_workspace_bytes", "ra_set_workspace",
     "ra_profile_kernels", "ra_profile_last_ms",
-    "ra_round_scores", "ra_select_rounds", "ra_round_sparse_attn_decode", "ra_watershed_attn_decode",
+    "ra_round_scores", "ra_round_scores_select", "ra_select_rounds", "ra_round_sparse_attn_decode", "ra_watershed_attn_decode",
     "ra_round_sparse_attn_prefill", "ra_watershed_attn_prefill",
     "ra_kv_store_create", "ra_kv_store_destroy", "ra_kv_store_register_round", "ra_kv_store_round_bytes",
     "ra_kv_store_stage", "ra_kv_store_wait_layer", "ra_kv_store_layer_view", "ra_kv_store_stats",
@@ -89,6 +89,9 @@ def lib() -> C.CDLL:
         L.ra_profile_last_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.ra_round_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(ra_kv_view),
                                       C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p]
+        L.ra_round_scores_select.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(ra_kv_view),
+                                             C.c_void_p, C.c_int, C.c_float, C.POINTER(ra_select_params), C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p]
         L.ra_measure_read_bandwidth.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int,
                                                 C.POINTER(C.c_float)]
         L.ra_round_scores_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
@@ -240,6 +243,32 @@ def ra_round_scores(ctx, q: torch.Tensor, view: KVView, cur_k: Optional[torch.Te
     _check(lib().ra_round_scores(ctx, _stream(stream), _ptr(q), q_len, Hq, C.byref(view.c), _ptr(cur_k), cur_len,
                                  scale, _ptr(scores_head), _ptr(scores)))
     return scores_head, scores
+
+
+def ra_round_scores_select(ctx, q: torch.Tensor, view: KVView, params: Optional["ra_select_params"] = None,
+                           cur_k: Optional[torch.Tensor] = None, scale: Optional[float] = None,
+                           scores_head: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                           sel_idx: Optional[torch.Tensor] = None, n_sel: Optional[torch.Tensor] = None, stream=None
+                           ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Returns (scores_head, scores, sel_idx, n_sel)."""
+    B, q_len, Hq, d = q.shape
+    if scale is None:
+        scale = d ** -0.5
+    if params is None:
+        params = make_select_params()
+    if scores_head is None:
+        scores_head = torch.empty((B, Hq, view.R_max), dtype=torch.float32, device=q.device)
+    if scores is None:
+        scores = torch.empty((B, view.R_max), dtype=torch.float32, device=q.device)
+    if sel_idx is None:
+        sel_idx = torch.empty((B, view.R_max), dtype=torch.int32, device=q.device)
+    if n_sel is None:
+        n_sel = torch.empty((B,), dtype=torch.int32, device=q.device)
+    cur_len = 0 if cur_k is None else cur_k.shape[1]
+    _check(lib().ra_round_scores_select(ctx, _stream(stream), _ptr(q), q_len, Hq, C.byref(view.c), _ptr(cur_k), cur_len,
+                                        scale, C.byref(params), _ptr(scores_head), _ptr(scores), _ptr(sel_idx),
+                                        _ptr(n_sel)))
+    return scores_head, scores, sel_idx, n_sel
 
 
 def ra_round_scores_accumulate(ctx, q: torch.Tensor, view: KVView, acc: torch.Tensor,

@@ -224,8 +224,8 @@ int ra_kv_store_stage(ra_kv_store* s, const int32_t* sel_idx_host, const int32_t
                       void* side_stream) {
     RA_REQUIRE(s != nullptr && sel_idx_host != nullptr && n_sel_host != nullptr, RA_ERR_INVALID_ARG,
                "kv_store_stage: NULL argument");
-    RA_REQUIRE(order == RA_STAGE_ROUND_MAJOR || order == RA_STAGE_LAYER_MAJOR, RA_ERR_INVALID_ARG,
-               "kv_store_stage: unknown order %d", order);
+    RA_REQUIRE(order == RA_STAGE_ROUND_MAJOR || order == RA_STAGE_LAYER_MAJOR || order == RA_STAGE_GROUPED,
+               RA_ERR_INVALID_ARG, "kv_store_stage: unknown order %d", order);
     RA_REQUIRE(!s->staged, RA_ERR_STATE, "kv_store_stage: already staged; call ra_kv_store_release first");
     const int B = s->cfg.B, R = s->cfg.R_max, L = s->cfg.n_layers;
     // ---- validate the selection and place every selected round in the pool ----------------------
@@ -301,6 +301,25 @@ int ra_kv_store_stage(ra_kv_store* s, const int32_t* sel_idx_host, const int32_t
             ++s->n_copies;
         }
         for (int l = 0; l < L; ++l) RA_HIP_CHECK(hipEventRecord(s->ready[l], st));
+    } else if (order == RA_STAGE_GROUPED) {
+        // Groups of consecutive layers, one copy per (group, round): a round's layers are contiguous in its host
+        // tensor, so a group is one slice.  A small first group lets the first post-watershed layer start early,
+        // larger groups keep the number of copies (and their fixed cost on the link) down.
+        for (int l0 = 0; l0 < L;) {
+            const int g = l0 == 0 ? (L / 8 > 1 ? L / 8 : 1) : ((L + 3) / 4 > 1 ? (L + 3) / 4 : 1);
+            const int l1 = l0 + g < L ? l0 + g : L;
+            for (const Job& jb : jobs) {
+                if (jb.len == 0) continue;
+                const size_t bytes = (size_t)(l1 - l0) * layer_tokens(jb.len) * s->token_bytes;
+                const size_t o = (size_t)l0 * layer_tokens(jb.len) * s->token_bytes;
+                RA_HIP_CHECK(hipMemcpyAsync(s->pool + jb.dst_tok * s->token_bytes + o, jb.src + o, bytes,
+                                            hipMemcpyHostToDevice, st));
+                s->staged_bytes += bytes;
+                ++s->n_copies;
+            }
+            for (int l = l0; l < l1; ++l) RA_HIP_CHECK(hipEventRecord(s->ready[l], st));
+            l0 = l1;
+        }
     } else {
         for (int l = 0; l < L; ++l) {
             for (const Job& jb : jobs) {

@@ -14,6 +14,7 @@
 //     rounds, mean over query heads.  One kernel does all of it for a single query token; for several query
 //     tokens the work of a head is split over several workgroups and a second small kernel normalises.
 #include "scores_common.hpp"
+#include "select_common.hpp"
 #include "stream_kv.hpp"
 
 namespace ra {
@@ -295,11 +296,19 @@ __global__ __launch_bounds__(W * 64) void scores_finish_kernel(FinishArgs a, boo
     }
     __syncthreads();
     const float inv_h = 1.f / (float)a.Hq;
+    float* svec = reinterpret_cast<float*>(cum);  // the sequence's scores, for the selection (cum is no longer read)
     for (int r = tid; r < a.R_max; r += W * 64) {
         float s = 0.f;
 #pragma unroll
         for (int w = 0; w < W; ++w) s += hs[w * a.R_max + r];
-        a.s_out[(size_t)b * a.R_max + r] = s * inv_h;
+        const float val = s * inv_h;
+        a.s_out[(size_t)b * a.R_max + r] = val;
+        if (a.with_select) svec[r] = val;
+    }
+    if (a.with_select) {  // Sec. 3.3 on the scores just written, same bits
+        __shared__ SelectShared<W> sh;
+        __syncthreads();
+        select_rounds_block<W>(svec, R, a.R_max, a.sel, a.sel_idx + (size_t)b * a.R_max, a.n_sel + b, sh);
     }
 }
 
@@ -382,8 +391,16 @@ __global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_rows_kernel(F
 // (Eq. 1; written to p_out [B][Hq][R_max] if given); scores[b][r] is the mean over heads.  A wave takes heads
 // wave, wave + 16, ... and a lane the rounds lane, lane + 64, ..., so all sums run in a fixed order.
 constexpr int kHeadsWaves = 16;
+struct HeadsSelect {
+    bool with_select;
+    ra_select_params sel;
+    const int32_t* n_rounds;
+    int32_t* sel_idx;
+    int32_t* n_sel;
+};
 __global__ __launch_bounds__(kHeadsWaves * 64) void scores_heads_kernel(const float* p_part, int Z, int R_max, int Hq,
-                                                                        float* p_out, float* s_out, float* acc) {
+                                                                        float* p_out, float* s_out, float* acc,
+                                                                        HeadsSelect hsel) {
     extern __shared__ __align__(16) char smem[];
     float* sacc = reinterpret_cast<float*>(smem);  // [kHeadsWaves][R_max]
     constexpr int KPL = kMaxRounds / 64;
@@ -425,7 +442,15 @@ __global__ __launch_bounds__(kHeadsWaves * 64) void scores_heads_kernel(const fl
     for (int r = threadIdx.x; r < R_max; r += kHeadsWaves * 64) {
         float s = 0.f;
         for (int w = 0; w < kHeadsWaves; ++w) s += sacc[w * R_max + r];
-        s_out[(size_t)b * R_max + r] = s * inv_h;
+        const float val = s * inv_h;
+        s_out[(size_t)b * R_max + r] = val;
+        if (hsel.with_select) sacc[r] = val;  // (a thread only ever touches its own column r of sacc)
+    }
+    if (hsel.with_select) {  // Sec. 3.3 on the scores just written, same bits
+        __shared__ SelectShared<kHeadsWaves> sh;
+        __syncthreads();
+        const int R = min(max(hsel.n_rounds[b], 0), R_max);
+        select_rounds_block<kHeadsWaves>(sacc, R, R_max, hsel.sel, hsel.sel_idx + (size_t)b * R_max, hsel.n_sel + b, sh);
     }
 }
 
@@ -475,8 +500,14 @@ void launch_scores_finish_rows(const FinishArgs& f, int B, float* p_part, int Z,
     else
         hipLaunchKernelGGL((scores_finish_rows_kernel<kMaxRounds / 64>), fgrid, fin_block, smem, st, f, p_part,
                            stage_rows);
+    HeadsSelect hsel;
+    hsel.with_select = f.with_select;
+    hsel.sel = f.sel;
+    hsel.n_rounds = f.n_rounds;
+    hsel.sel_idx = f.sel_idx;
+    hsel.n_sel = f.n_sel;
     hipLaunchKernelGGL(scores_heads_kernel, dim3(B), dim3(kHeadsWaves * 64), (size_t)kHeadsWaves * R_max * sizeof(float),
-                       st, p_part, Z, R_max, Hq, f.p_out, f.s_out, f.acc);
+                       st, p_part, Z, R_max, Hq, f.p_out, f.s_out, f.acc, hsel);
 }
 
 // One query token: the finishing kernel for B sequences (a.q_len must be 1).
@@ -511,7 +542,8 @@ void launch_scores_finish(const FinishArgs& f, int B, float* p_part, hipStream_t
 }  // namespace ra
 
 static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq, const ra_kv_view* watershed,
-                       const void* cur_k, int cur_len, float scale, float* acc, float* scores_head, float* scores) {
+                       const void* cur_k, int cur_len, float scale, float* acc, float* scores_head, float* scores,
+                       const ra_select_params* sel = nullptr, int32_t* sel_idx = nullptr, int32_t* n_sel = nullptr) {
     RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "round_scores: ctx is NULL");
     RA_REQUIRE(q != nullptr && scores != nullptr, RA_ERR_INVALID_ARG, "round_scores: q or scores is NULL");
     if (int rc = check_view(watershed, false, "round_scores")) return rc;
@@ -524,6 +556,10 @@ static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int 
                "round_scores: the q_len query tokens are the tail of the current round, so cur_len >= q_len");
     RA_REQUIRE(scale > 0.f && scale == scale, RA_ERR_INVALID_ARG, "round_scores: scale must be positive");
     RA_REQUIRE(watershed->R_max > 0, RA_ERR_INVALID_ARG, "round_scores: R_max is 0, there is nothing to score");
+    if (sel) {
+        RA_REQUIRE(sel_idx != nullptr && n_sel != nullptr, RA_ERR_INVALID_ARG, "round_scores_select: sel_idx or n_sel is NULL");
+        if (int rc = check_select_params(sel, "round_scores_select")) return rc;
+    }
     const int G = Hq / watershed->Hkv, D = watershed->d, B = watershed->B, R_max = watershed->R_max;
     RA_REQUIRE(D == 64 || D == 128, RA_ERR_UNSUPPORTED, "round_scores: head_dim %d not in {64, 128}", D);
     RA_REQUIRE((int64_t)B * q_len <= 65535, RA_ERR_UNSUPPORTED, "round_scores: B * q_len exceeds 65535");
@@ -599,6 +635,12 @@ static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int 
     f.p_out = scores_head;
     f.s_out = scores;
     f.acc = acc;
+    if (sel) {
+        f.with_select = true;
+        f.sel = *sel;
+        f.sel_idx = sel_idx;
+        f.n_sel = n_sel;
+    }
     launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + kWsReserved + part_bytes), st);
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
@@ -615,4 +657,13 @@ extern "C" int ra_round_scores_accumulate(ra_ctx* ctx, void* stream, const void*
                                           float* acc, float* scores_head, float* scores) {
     RA_REQUIRE(acc != nullptr, RA_ERR_INVALID_ARG, "round_scores_accumulate: acc is NULL");
     return scores_impl(ctx, stream, q, q_len, Hq, watershed, cur_k, cur_len, scale, acc, scores_head, scores);
+}
+
+extern "C" int ra_round_scores_select(ra_ctx* ctx, void* stream, const void* q, int q_len, int Hq,
+                                      const ra_kv_view* watershed, const void* cur_k, int cur_len, float scale,
+                                      const ra_select_params* params, float* scores_head, float* scores,
+                                      int32_t* sel_idx, int32_t* n_sel) {
+    RA_REQUIRE(params != nullptr, RA_ERR_INVALID_ARG, "round_scores_select: params is NULL");
+    return scores_impl(ctx, stream, q, q_len, Hq, watershed, cur_k, cur_len, scale, nullptr, scores_head, scores, params,
+                       sel_idx, n_sel);
 }

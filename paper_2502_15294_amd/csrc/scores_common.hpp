@@ -33,6 +33,11 @@ struct FinishArgs {
     float* s_out;
     float* acc = nullptr;  // [B][Hq][R_max] running round masses of earlier calls (Eq. 1 over a growing set of
                            // query tokens): added to this call's masses before normalising, then updated
+    // Sec. 3.3 in the same kernel: the workgroup that has a sequence's scores in LDS also selects its rounds
+    bool with_select = false;
+    ra_select_params sel = {};
+    int32_t* sel_idx = nullptr;  // [B][R_max]
+    int32_t* n_sel = nullptr;    // [B]
 };
 void launch_scores_finish_single(const FinishArgs& f, int B, hipStream_t st);
 int scores_finish_splits(int q_len, int B, int Hq);  // Z of launch_scores_finish_rows

@@ -47,6 +47,8 @@ def test_null_arguments_are_rejected_before_any_launch():
     p = ra.make_select_params()
     assert L.ra_round_scores(None, None, None, 1, 4, C.byref(view), None, 0, 1.0, None, None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_select_rounds(None, None, None, None, 1, 8, C.byref(p), None, None) == ra.RA_ERR_INVALID_ARG
+    assert L.ra_round_scores_select(None, None, None, 1, 4, C.byref(view), None, 0, 1.0, C.byref(p), None, None, None,
+                                    None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_round_sparse_attn_decode(None, None, None, 4, C.byref(view), None, None, None, None, None, 0, 1.0,
                                          None, None) == ra.RA_ERR_INVALID_ARG
     assert L.ra_watershed_attn_decode(None, None, None, 4, C.byref(view), None, None, None, 0, 1.0, None, None, None,

@@ -1,7 +1,12 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration
-`bench.py` times.  The GPU runs the whole batch; the fp64 oracle computes a sample of the sequences one by
-one (scores, selection, attention) and those rows are compared to the same bars as everywhere else:
-indices bit-exact, attention within 2e-3 (and within the arithmetic bound 5e-5), scores within 1e-5."""
+`bench.py` times.  The GPU runs the whole batch; the fp64 oracle then computes EVERY sequence of the batch, one by
+one (scores, selection, attention), and all of them are held to the same bars as everywhere else: indices
+bit-exact with the selection margin asserted, attention within 2e-3 (and within the arithmetic bound 5e-5) by the
+row measure and within 2e-3 elementwise on the entries of at least 5 % of their row's largest magnitude, scores
+within 1e-5.  (The one exception is stated where it is made: the second staged layer of the long-context
+configuration is compared on a sample of the sequences.)"""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -20,18 +25,31 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _check_sequence(w, b, S, sel_idx, n_sel, out, lam=1.0, layer=1):
-    r = pipeline.run_sequence(w, b, select_params=dict(lam=lam), layers=[layer])
+def _check_sequence(w, b, S, sel_idx, n_sel, out, lam=1.0, layer=1, attention=True):
+    r = pipeline.run_sequence(w, b, select_params=dict(lam=lam), layers=[layer] if attention else [])
     R = w.n_rounds(b)
     assert np.abs(S[b, :R] - r.S).max() < SCORE_TOL
     assert r.info["margin"] > 1e-4, "ill-conditioned seed: a score sits on the cut"
     assert sel_idx[b, :n_sel[b]].tolist() == r.sel
-    err = ora.row_error(out[b], r.out[layer] if out[b].ndim == 3 else r.out[layer][0])
-    _say(f"  seq {b}: {len(r.sel)} of {R} rounds kept, margin {r.info['margin']:.3f}, row error {err:.2e}")
-    assert err < OUT_TOL and err < STREAM_TOL
+    if not attention:
+        _say(f"  seq {b}: {len(r.sel)} of {R} rounds kept, margin {r.info['margin']:.3f}")
+        return r.info["margin"], 0.0
+    ref = r.out[layer] if out[b].ndim == 3 else r.out[layer][0]
+    err, big = ora.row_error(out[b], ref), ora.large_entry_error(out[b], ref)
+    _say(f"  seq {b}: {len(r.sel)} of {R} rounds kept, margin {r.info['margin']:.3f}, row error {err:.2e}, "
+         f"large-entry error {big:.2e}")
+    assert err < OUT_TOL and err < STREAM_TOL and big < OUT_TOL
+    return r.info["margin"], err
 
 
-def test_config5_full_size_paged_decode_sampled_sequences():
+def _check_all(w, seqs, *args, workers=4, **kw):
+    """The oracle on several sequences at a time (numpy releases the interpreter lock inside its BLAS calls)."""
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        res = list(ex.map(lambda b: _check_sequence(w, b, *args, **kw), seqs))
+    _say(f"  {len(res)} sequences: smallest margin {min(m for m, _ in res):.4f}, largest row error {max(e for _, e in res):.2e}")
+
+
+def test_config5_full_size_paged_decode_every_sequence():
     w = make_workload("cfg5")
     _say(f"cfg5 full: B={w.B} Hq={w.Hq} tokens/seq~{w.total_tokens(0)} paged")
     eng = Engine(w)
@@ -41,8 +59,7 @@ def test_config5_full_size_paged_decode_sampled_sequences():
     out, _ = ra.ra_round_sparse_attn_decode(eng.ctx, to_device(w.q(1)[:, 0], w.dtype), v1, sel_idx, n_sel, scale=w.scale)
     torch.cuda.synchronize()
     S, sel_idx, n_sel, out = S.cpu().numpy(), sel_idx.cpu().numpy(), n_sel.cpu().numpy(), out.cpu().numpy()
-    for b in (0, 17, 40, 63):
-        _check_sequence(w, b, S, sel_idx, n_sel, out)
+    _check_all(w, range(w.B), S, sel_idx, n_sel, out)
     assert np.isfinite(out).all() and (n_sel >= 1).all()
     eng.close()
 
@@ -102,12 +119,11 @@ def test_config3_full_size_prefill():
                                              scale=w.scale)
     torch.cuda.synchronize()
     S, sel_idx, n_sel, out = S.cpu().numpy(), sel_idx.cpu().numpy(), n_sel.cpu().numpy(), out.cpu().numpy()
-    for b in (0, 3):
-        _check_sequence(w, b, S, sel_idx, n_sel, out)
+    _check_all(w, range(w.B), S, sel_idx, n_sel, out, workers=2)
     eng.close()
 
 
-def test_config4_full_size_staged_decode_sampled():
+def test_config4_full_size_staged_decode_every_sequence():
     """128K-token contexts, 200 rounds, batch 16: scores and selection on the full batch, the selected rounds of
     the first and the last post-watershed layer staged from pinned host memory, decode on the staged views."""
     w = make_workload("cfg4")
@@ -130,7 +146,7 @@ def test_config4_full_size_staged_decode_sampled():
         for r in range(w.n_rounds(b)):
             ra.ra_kv_store_register_round(store, b, r, host.get((b, r), dummy), int(w.lens[b][r]))
     side = torch.cuda.Stream()
-    ra.ra_kv_store_stage(store, sel_h, n_h, ra.RA_STAGE_LAYER_MAJOR, side)
+    ra.ra_kv_store_stage(store, sel_h, n_h, ra.RA_STAGE_GROUPED, side)
     outs = []
     for li, layer in enumerate(layers):
         ra.ra_kv_store_wait_layer(store, li)
@@ -139,9 +155,11 @@ def test_config4_full_size_staged_decode_sampled():
         outs.append(o)
     torch.cuda.synchronize()
     S, sel_np, n_np = S.cpu().numpy(), sel_h.numpy(), n_h.numpy()
-    for li, layer in enumerate(layers):
-        for b in ((0, 11) if li == 0 else (5,)):
-            _check_sequence(w, b, S, sel_np, n_np, outs[li].cpu().numpy(), layer=layer)
+    # every sequence: scores, selection and the first post-watershed layer's attention; the last layer's attention
+    # on a sample of four (its selection is the same one, only K, V and the queries differ)
+    _check_all(w, range(w.B), S, sel_np, n_np, outs[0].cpu().numpy(), layer=layers[0], workers=3)
+    for b in (1, 5, 10, 15):
+        _check_sequence(w, b, S, sel_np, n_np, outs[1].cpu().numpy(), layer=layers[1])
     ra.ra_kv_store_release(store)
     ra.ra_kv_store_destroy(store)
     eng.close()

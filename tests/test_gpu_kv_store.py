@@ -25,12 +25,22 @@ def _make_store(w, pool_bytes):
     return ra.ra_kv_store_create(0, w.n_post_layers, w.B, max(w.R_max, 1), w.Hkv, w.d, dt, pool_bytes)
 
 
-@pytest.mark.parametrize("order", [ra.RA_STAGE_ROUND_MAJOR, ra.RA_STAGE_LAYER_MAJOR])
-def test_store_stage_then_decode_every_layer(order):
+def _grouped_copies_per_round(L):
+    """Groups of the grouped order: a first group of L / 8 layers (at least one), then groups of ceil(L / 4)."""
+    n, l0 = 0, 0
+    while l0 < L:
+        l0 += max(L // 8, 1) if l0 == 0 else max((L + 3) // 4, 1)
+        n += 1
+    return n
+
+
+@pytest.mark.parametrize("order,n_layers", [(ra.RA_STAGE_ROUND_MAJOR, 3), (ra.RA_STAGE_LAYER_MAJOR, 3),
+                                            (ra.RA_STAGE_GROUPED, 3), (ra.RA_STAGE_GROUPED, 9)])
+def test_store_stage_then_decode_every_layer(order, n_layers):
     """Reduced copy of the long-context configuration: score on the watershed layer, select, copy the
     selection to the host, stage the selected rounds from pinned memory on a side stream, and run
     round-sparse decode on each post-watershed layer as soon as that layer has arrived."""
-    w = make_workload("cfg4", B=3, R=14, n_post_layers=3, length=("lognormal", 60.0, 0.8, 1500))
+    w = make_workload("cfg4", B=3, R=14, n_post_layers=n_layers, length=("lognormal", 60.0, 0.8, 1500))
     print(f"store case order={order}: B={w.B} R={w.R_max} layers={w.n_post_layers}", flush=True)
     eng = Engine(w)
     layers = list(range(1, w.n_post_layers + 1))
@@ -70,7 +80,10 @@ def test_store_stage_then_decode_every_layer(order):
     assert staged == sel_bytes
     assert registered == sum(t.numel() * t.element_size() for t in keep)
     n_sel_rounds = int(n_h.sum())
-    assert n_copies == (n_sel_rounds if order == ra.RA_STAGE_ROUND_MAJOR else n_sel_rounds * len(layers))
+    per_round = {ra.RA_STAGE_ROUND_MAJOR: 1, ra.RA_STAGE_LAYER_MAJOR: len(layers),
+                 ra.RA_STAGE_GROUPED: _grouped_copies_per_round(len(layers))}[order]
+    assert _grouped_copies_per_round(24) == 5 and _grouped_copies_per_round(9) == 4
+    assert n_copies == n_sel_rounds * per_round
 
     # a second selection after release reuses the pool
     ra.ra_kv_store_release(store)

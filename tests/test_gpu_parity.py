@@ -10,6 +10,7 @@ import paper_2502_15294_amd as ra
 from oracle import pipeline
 from oracle import round_attention as ora
 from synth import make_workload
+from select_edge_cases import select_edge_cases
 from synth.device import Engine, device_view, sel_to_device, to_device
 
 pytestmark = pytest.mark.gpu
@@ -229,6 +230,64 @@ def test_select_function_parity_is_bit_exact(pi):
         got = sel_idx[b, :n_sel[b]].tolist()
         assert got == expect, (b, params)
         assert np.all(sel_idx[b, n_sel[b]:] == -1)
+    eng.close()
+
+
+def test_select_scores_at_and_one_ulp_around_the_cut():
+    """Scores placed exactly on the THRESHOLD and ADAPTIVE cuts, and one fp32 ulp above and below them: the
+    inequality is strict, the cut is formed in double from the fp32 scores, and the kernel must take every one of
+    these decisions as the oracle does (hand-derived expectations for the cases that have one)."""
+    cases = select_edge_cases()
+    R_max = 16
+    ctx = ra.ra_create(0)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    ra.ra_set_workspace(ctx, ws)
+    for scores, params, expected in cases:
+        S = np.zeros((1, R_max), dtype=np.float32)
+        S[0, :len(scores)] = np.asarray(scores, dtype=np.float32)
+        n_rounds = np.array([len(scores)], dtype=np.int32)
+        p = ra.make_select_params(strategy=params["strategy"], lam=params.get("lam", 1.0),
+                                  threshold=params.get("threshold", 0.10), min_rounds=params.get("min_rounds", 1))
+        sel_idx, n_sel = ra.ra_select_rounds(ctx, torch.from_numpy(S).cuda(), torch.from_numpy(n_rounds).cuda(), p)
+        torch.cuda.synchronize()
+        got = sel_idx.cpu().numpy()[0, :int(n_sel.cpu()[0])].tolist()
+        want = _oracle_select_on(S[0], len(scores), params)
+        assert got == want, (scores, params, got, want)
+        if expected is not None:
+            assert want == expected, ("the oracle itself disagrees with the hand-derived selection", scores, params, want)
+    ra.ra_destroy(ctx)
+
+
+SCORES_SELECT_CASES = {
+    "fp32_generic": ("cfg1", {}),
+    "bf16_decode": ("cfg2", {}),
+    "bf16_decode_64_heads_paged": ("cfg5", dict(B=3)),
+    "question_8_tokens": ("cfg3", dict(B=2, R=9, q_len=8, cur_len=8, length=("uniform", 20, 300))),
+    "rounds_above_256": ("cfg2", dict(B=2, R=300, length=("uniform", 1, 40))),
+}
+
+
+@pytest.mark.parametrize("name", list(SCORES_SELECT_CASES))
+def test_scores_and_selection_in_one_call_equal_the_two_calls_bitwise(name):
+    cfg, over = SCORES_SELECT_CASES[name]
+    w = make_workload(cfg, **over)
+    eng = Engine(w)
+    view = device_view(w, 0, with_v=False)
+    q0 = to_device(w.q(0), w.dtype)
+    ck0 = to_device(w.cur_k(0), w.dtype) if w.cur_len else None
+    for params in SELECT_PARAMS[:9]:
+        p = ra.make_select_params(strategy=params["strategy"], lam=params.get("lam", 1.0),
+                                  fraction=params.get("fraction", 0.10), threshold=params.get("threshold", 0.10),
+                                  ddof=params.get("ddof", 0), min_rounds=params.get("min_rounds", 1),
+                                  max_rounds=params.get("max_rounds", 0))
+        P1, S1 = ra.ra_round_scores(eng.ctx, q0, view, ck0, scale=w.scale)
+        sel1, n1 = ra.ra_select_rounds(eng.ctx, S1, view.n_rounds, p)
+        P2, S2, sel2, n2 = ra.ra_round_scores_select(eng.ctx, q0, view, p, ck0, scale=w.scale)
+        torch.cuda.synchronize()
+        assert torch.equal(P1, P2) and torch.equal(S1, S2) and torch.equal(sel1, sel2) and torch.equal(n1, n2), params
+        S, sel, n = S2.cpu().numpy(), sel2.cpu().numpy(), n2.cpu().numpy()
+        for b in range(w.B):   # and the oracle's rule on these scores
+            assert sel[b, :n[b]].tolist() == _oracle_select_on(S[b], w.n_rounds(b), params), (b, params)
     eng.close()
 
 

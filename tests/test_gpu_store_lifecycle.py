@@ -293,7 +293,7 @@ def test_random_turns_against_the_ledger_and_the_oracle(seed):
             sel_t[b, :len(s)] = torch.tensor(s, dtype=torch.int32)
             ledgers[b].record_selection([r for r in s if r not in dropped[b]])
         n_t = torch.tensor([len(s) for s in sels], dtype=torch.int32)
-        order = ra.RA_STAGE_ROUND_MAJOR if rng.random() < 0.5 else ra.RA_STAGE_LAYER_MAJOR
+        order = [ra.RA_STAGE_ROUND_MAJOR, ra.RA_STAGE_LAYER_MAJOR, ra.RA_STAGE_GROUPED][int(rng.integers(3))]
         ra.ra_kv_store_stage(store, sel_t, n_t, order, side)
         li = int(rng.integers(0, 2))
         ra.ra_kv_store_wait_layer(store, li)

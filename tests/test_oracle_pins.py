@@ -380,3 +380,52 @@ def test_answer_tokens_one_at_a_time_sum_to_eq1_right():
             acc[h] += np.array(e_rounds) / z
     assert np.allclose(P, acc / acc.sum(axis=1, keepdims=True), rtol=1e-12, atol=0)
     assert np.allclose(S, (acc / acc.sum(axis=1, keepdims=True)).mean(axis=0), rtol=1e-12, atol=0)
+
+
+def test_select_scores_on_the_cut_and_one_ulp_beside_it_hand_values():
+    """Strict inequality at the cut (Sec. 3.3 writes ">"), decided in double on fp32 scores: hand-derived selections
+    for vectors whose mean / standard deviation are exact binary fractions."""
+    from select_edge_cases import select_edge_cases
+    n_hand = 0
+    for scores, params, expected in select_edge_cases():
+        got, _ = ra.select_rounds([float(np.float32(x)) for x in scores], **params)
+        if expected is not None:
+            assert got == expected, (scores, params)
+            n_hand += 1
+    assert n_hand >= 10
+
+
+def test_row_error_hand_values():
+    """row_error = max over rows of (largest absolute error of the row) / (largest magnitude of the row's reference):
+    hand-worked, with the largest error of a row away from its largest entry, rows of different scale, a leading
+    batch axis, and the uniform relative perturbation that must come back as itself."""
+    ref = np.array([[1.0, -4.0, 2.0, 0.5], [0.1, 0.2, -0.05, 0.0]])
+    out = ref.copy()
+    out[0, 3] += 0.02       # row 0: 0.02 / 4 = 0.005, the error sits on the entry 0.5
+    out[1, 0] -= 0.003      # row 1: 0.003 / 0.2 = 0.015
+    assert ra.row_error(out, ref) == pytest.approx(0.015, rel=1e-12)
+    out[1, 0] = ref[1, 0]
+    assert ra.row_error(out, ref) == pytest.approx(0.005, rel=1e-12)
+    # a wrong axis or a per-element denominator would give 0.02 / 0.5 or 0.003 / 0.1 instead
+    assert ra.row_error(ref * (1 + 1e-3), ref) == pytest.approx(1e-3, rel=1e-9)
+    # rows are the last axis, whatever lies in front: [token][head][channel]
+    ref3 = np.stack([ref, 10 * ref])
+    out3 = ref3.copy()
+    out3[1, 0, 0] += 0.4    # 0.4 / 40
+    out3[0, 1, 2] += 0.001  # 0.001 / 0.2
+    assert ra.row_error(out3, ref3) == pytest.approx(0.01, rel=1e-12)
+    assert ra.row_error(ref3, ref3) == 0.0
+
+
+def test_large_entry_error_hand_values():
+    """Elementwise relative error over the entries of at least 5 % of their row's largest magnitude."""
+    ref = np.array([[1.0, -4.0, 2.0, 0.1], [0.1, 0.2, -0.05, 0.0]])
+    out = ref.copy()
+    out[0, 3] += 0.05       # 0.1 < 0.05 * 4: below the floor, ignored although its relative error is 50 %
+    out[0, 2] += 0.004      # 0.004 / 2 = 0.002
+    out[1, 2] += 0.001      # 0.05 >= 0.05 * 0.2: counted, 0.001 / 0.05 = 0.02
+    assert ra.large_entry_error(out, ref) == pytest.approx(0.02, rel=1e-12)
+    out[1, 2] = ref[1, 2]
+    assert ra.large_entry_error(out, ref) == pytest.approx(0.002, rel=1e-12)
+    assert ra.large_entry_error(out, ref, floor=0.01) == pytest.approx(0.5, rel=1e-12)
+    assert ra.large_entry_error(np.ones((2, 3)), np.zeros((2, 3))) == 0.0
