@@ -228,6 +228,22 @@ int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq
                                 float* lse);
 
 /*
+ * ra_round_sparse_attn_decode for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, bitwise the same
+ * results; the scratch is a 32 MiB array inside the library's device code (every GPU the library runs on holds it
+ * until the process ends), whose address ra_create looks up once per device.  The context's workspace is neither
+ * needed nor touched.  The call allocates nothing, synchronises nothing and records no memset.
+ * RA_ERR_WORKSPACE if the call would need more than 32 MiB of scratch (about 4000 partial results: every
+ * benchmark configuration of this repository fits); RA_ERR_UNSUPPORTED etc. as for the other call.
+ * All calls on one GPU share the array: two calls that overlap in time (different streams, different contexts)
+ * race; consecutive calls on one stream do not.  Nothing in the array has to be cleared between calls.
+ */
+int ra_round_sparse_attn_decode_noalloc(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* layer,
+                                        const int32_t* sel_idx, const int32_t* n_sel, const void* cur_k,
+                                        const void* cur_v, const int32_t* cur_len, int cur_cap, float scale,
+                                        float* out, float* lse);
+
+/*
  * Decode at the watershed layer itself (Sec. 3.2 steps 2-3: the round scores are taken with the watershed
  * layer's own attention, qAtt^{L_w}; Eq. 1 in its one-query-token form): dense attention of one query token per
  * sequence over every history round of `watershed` (which must carry values) plus the current round, and, from

@@ -27,7 +27,8 @@ RA_OK, RA_ERR_INVALID_ARG, RA_ERR_UNSUPPORTED, RA_ERR_WORKSPACE, RA_ERR_STATE, R
 EXPORTS = [
     "ra_last_error", "ra_create", "ra_destroy", "ra_workspace_bytes", "ra_set_workspace",
     "ra_profile_kernels", "ra_profile_last_ms",
-    "ra_round_scores", "ra_round_scores_select", "ra_select_rounds", "ra_round_sparse_attn_decode", "ra_watershed_attn_decode",
+    "ra_round_scores", "ra_round_scores_select", "ra_select_rounds", "ra_round_sparse_attn_decode", "ra_round_sparse_attn_decode_noalloc",
+    "ra_watershed_attn_decode",
     "ra_round_sparse_attn_prefill", "ra_watershed_attn_prefill",
     "ra_kv_store_create", "ra_kv_store_destroy", "ra_kv_store_register_round", "ra_kv_store_round_bytes",
     "ra_kv_store_stage", "ra_kv_store_wait_layer", "ra_kv_store_layer_view", "ra_kv_store_stats",
@@ -106,6 +107,7 @@ def lib() -> C.CDLL:
         L.ra_round_sparse_attn_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(ra_kv_view),
                                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                                   C.c_float, C.c_void_p, C.c_void_p]
+        L.ra_round_sparse_attn_decode_noalloc.argtypes = L.ra_round_sparse_attn_decode.argtypes
         L.ra_watershed_attn_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(ra_kv_view),
                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                                C.c_void_p, C.c_void_p, C.c_void_p]
@@ -350,6 +352,21 @@ def ra_round_sparse_attn_decode(ctx, q: torch.Tensor, view: KVView, sel_idx: Opt
                                              _ptr(n_sel), _ptr(cur_k), _ptr(cur_v), _ptr(cur_len), cur_cap, scale,
                                              _ptr(out), _ptr(lse)))
     return out, lse
+
+
+def ra_round_sparse_attn_decode_noalloc(ctx, q: torch.Tensor, view: KVView, out: torch.Tensor, lse: Optional[torch.Tensor],
+                                        sel_idx: Optional[torch.Tensor] = None, n_sel: Optional[torch.Tensor] = None,
+                                        cur_k: Optional[torch.Tensor] = None, cur_v: Optional[torch.Tensor] = None,
+                                        cur_len: Optional[torch.Tensor] = None, scale: Optional[float] = None,
+                                        stream=None) -> None:
+    """The decode call on the library's built-in scratch: the caller passes every output, nothing is allocated."""
+    B, Hq, d = q.shape
+    if scale is None:
+        scale = d ** -0.5
+    cur_cap = 0 if cur_k is None else cur_k.shape[1]
+    _check(lib().ra_round_sparse_attn_decode_noalloc(ctx, _stream(stream), _ptr(q), Hq, C.byref(view.c), _ptr(sel_idx),
+                                                     _ptr(n_sel), _ptr(cur_k), _ptr(cur_v), _ptr(cur_len), cur_cap,
+                                                     scale, _ptr(out), _ptr(lse)))
 
 
 def ra_watershed_attn_decode(ctx, q: torch.Tensor, view: KVView, cur_k: Optional[torch.Tensor] = None,

@@ -77,6 +77,7 @@ struct DevView {
 };
 
 int check_view(const ra_kv_view* v, bool need_v, const char* who);
+int static_scratch_init(int device);  // decode.hip: device address of the built-in scratch of the no-allocation entry point
 DevView to_dev(const ra_kv_view* v);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

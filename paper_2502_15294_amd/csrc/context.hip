@@ -91,6 +91,7 @@ int ra_create(ra_ctx** out, int device) {
                n);
     hipDeviceProp_t prop;
     RA_HIP_CHECK(hipGetDeviceProperties(&prop, device));
+    if (int rc = static_scratch_init(device)) return rc;
     ra_ctx* c = new (std::nothrow) ra_ctx();
     RA_REQUIRE(c != nullptr, RA_ERR_OOM, "ra_create: out of host memory");
     c->device = device;

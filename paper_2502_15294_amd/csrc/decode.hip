@@ -359,10 +359,12 @@ using namespace ra;
 // Shared by the two decode entry points.  With `scores` given (watershed layer) the attention runs over every
 // history round and the kernel also leaves one log-sum-exp per 32-token key tile, which the finishing kernel of
 // the score pass turns into Eq. 1.
-static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* layer, const int32_t* sel_idx,
-                       const int32_t* n_sel, const void* cur_k, const void* cur_v, const int32_t* cur_len, int cur_cap,
-                       float scale, float* out, float* lse, float* scores_head, float* scores) {
+static int decode_impl(ra_ctx* ctx, const Workspace* scratch, void* stream, const void* q, int Hq, const ra_kv_view* layer,
+                       const int32_t* sel_idx, const int32_t* n_sel, const void* cur_k, const void* cur_v,
+                       const int32_t* cur_len, int cur_cap, float scale, float* out, float* lse, float* scores_head,
+                       float* scores) {
     RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "decode: ctx is NULL");
+    const Workspace ws = scratch ? *scratch : ctx->ws;  // the context's workspace, or the built-in scratch
     RA_REQUIRE(q != nullptr && out != nullptr, RA_ERR_INVALID_ARG, "decode: q or out is NULL");
     if (int rc = check_view(layer, true, "decode")) return rc;
     RA_REQUIRE(Hq > 0 && Hq % layer->Hkv == 0, RA_ERR_INVALID_ARG, "decode: Hq %d is not a multiple of Hkv %d", Hq,
@@ -423,8 +425,9 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
     const int n_tiles_max = (int)n_tiles64;
     const size_t tile_bytes = with_scores ? align_up(rows * n_tiles_max * sizeof(float), 256) : 0;
     const size_t p_bytes = with_scores ? scores_finish_part_bytes(1, B, Hq, layer->R_max, n_tiles_max) : 0;
-    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= scratch_total + tile_bytes + p_bytes, RA_ERR_WORKSPACE,
-               "decode: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes, scratch_total + tile_bytes + p_bytes);
+    RA_REQUIRE(ws.base != nullptr && ws.bytes >= scratch_total + tile_bytes + p_bytes, RA_ERR_WORKSPACE,
+               "decode: %s has %zu bytes, this call needs %zu", scratch ? "the built-in scratch" : "the workspace", ws.bytes,
+               scratch_total + tile_bytes + p_bytes);
 
     AttnArgs a = {};
     a.view = to_dev(layer);
@@ -444,18 +447,18 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
     a.min_units = mfma ? kMfmaMinUnits : attn_min_units();
     a.c = scale * kLog2e;
     a.scale = scale;
-    a.part_acc = mfma ? nullptr : reinterpret_cast<float*>(ctx->ws.base + w.acc_off);
-    a.part_m = mfma ? nullptr : reinterpret_cast<float*>(ctx->ws.base + w.m_off);
-    a.part_l = mfma ? nullptr : reinterpret_cast<float*>(ctx->ws.base + w.l_off);
-    a.n_parts = reinterpret_cast<int*>(ctx->ws.base);
-    a.plan = ctx->ws.base + plan_off;
+    a.part_acc = mfma ? nullptr : reinterpret_cast<float*>(ws.base + w.acc_off);
+    a.part_m = mfma ? nullptr : reinterpret_cast<float*>(ws.base + w.m_off);
+    a.part_l = mfma ? nullptr : reinterpret_cast<float*>(ws.base + w.l_off);
+    a.n_parts = reinterpret_cast<int*>(ws.base);
+    a.plan = ws.base + plan_off;
     a.out = out;
     a.lse = lse;
-    a.tile_lse = with_scores ? reinterpret_cast<float*>(ctx->ws.base + scratch_total) : nullptr;
+    a.tile_lse = with_scores ? reinterpret_cast<float*>(ws.base + scratch_total) : nullptr;
     a.n_tiles_max = with_scores ? n_tiles_max : 0;
-    a.rec_acc = mfma ? reinterpret_cast<float*>(ctx->ws.base + mw.rec_off) : nullptr;
-    a.rec_ml = mfma ? reinterpret_cast<float*>(ctx->ws.base + mw.ml_off) : nullptr;
-    a.seq_rec = reinterpret_cast<int*>(ctx->ws.base + kWsSeqRecOff);
+    a.rec_acc = mfma ? reinterpret_cast<float*>(ws.base + mw.rec_off) : nullptr;
+    a.rec_ml = mfma ? reinterpret_cast<float*>(ws.base + mw.ml_off) : nullptr;
+    a.seq_rec = reinterpret_cast<int*>(ws.base + kWsSeqRecOff);
     a.max_ranges = shape.max_ranges;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -495,7 +498,7 @@ static int decode_impl(ra_ctx* ctx, void* stream, const void* q, int Hq, const r
         f.has_cur = false;
         f.p_out = scores_head;
         f.s_out = scores;
-        launch_scores_finish(f, B, reinterpret_cast<float*>(ctx->ws.base + scratch_total + tile_bytes), st);
+        launch_scores_finish(f, B, reinterpret_cast<float*>(ws.base + scratch_total + tile_bytes), st);
     }
     RA_HIP_CHECK(hipGetLastError());
     return RA_OK;
@@ -505,14 +508,53 @@ extern "C" int ra_round_sparse_attn_decode(ra_ctx* ctx, void* stream, const void
                                            const int32_t* sel_idx, const int32_t* n_sel, const void* cur_k,
                                            const void* cur_v, const int32_t* cur_len, int cur_cap, float scale,
                                            float* out, float* lse) {
-    return decode_impl(ctx, stream, q, Hq, layer, sel_idx, n_sel, cur_k, cur_v, cur_len, cur_cap, scale, out, lse, nullptr,
-                       nullptr);
+    return decode_impl(ctx, nullptr, stream, q, Hq, layer, sel_idx, n_sel, cur_k, cur_v, cur_len, cur_cap, scale, out, lse,
+                       nullptr, nullptr);
+}
+
+// ---- the same call for callers that cannot allocate ------------------------------------------------------------
+// Scratch in a file-scope device array instead of a caller-provided workspace.  In host code the array's name only
+// stands for the symbol: its device address is asked for once per device (every GPU holds its own copy) and that
+// pointer is what kernels and entry points get.
+namespace ra {
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static char* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, null until asked for
+
+// Called by ra_create with the context's device: looks the address up the first time a device is seen.
+int static_scratch_init(int device) {
+    RA_REQUIRE(device >= 0 && device < kMaxDevices, RA_ERR_UNSUPPORTED, "device %d: at most %d devices", device, kMaxDevices);
+    if (g_scratch_ptr[device]) return RA_OK;
+    int prev = 0;
+    RA_HIP_CHECK(hipGetDevice(&prev));
+    RA_HIP_CHECK(hipSetDevice(device));
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    (void)hipSetDevice(prev);
+    if (e != hipSuccess || ptr == nullptr)
+        return fail(RA_ERR_HIP, "hipGetSymbolAddress(built-in scratch) on device %d: %s", device, hipGetErrorString(e));
+    g_scratch_ptr[device] = static_cast<char*>(ptr);
+    return RA_OK;
+}
+}  // namespace ra
+
+extern "C" int ra_round_sparse_attn_decode_noalloc(ra_ctx* ctx, void* stream, const void* q, int Hq,
+                                                   const ra_kv_view* layer, const int32_t* sel_idx, const int32_t* n_sel,
+                                                   const void* cur_k, const void* cur_v, const int32_t* cur_len,
+                                                   int cur_cap, float scale, float* out, float* lse) {
+    RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "decode: ctx is NULL");
+    RA_REQUIRE(ctx->device >= 0 && ctx->device < kMaxDevices && g_scratch_ptr[ctx->device] != nullptr, RA_ERR_STATE,
+               "decode: the built-in scratch of device %d was not set up by ra_create", ctx->device);
+    const Workspace builtin = {g_scratch_ptr[ctx->device], kStaticScratchBytes};
+    return decode_impl(ctx, &builtin, stream, q, Hq, layer, sel_idx, n_sel, cur_k, cur_v, cur_len, cur_cap, scale, out, lse,
+                       nullptr, nullptr);
 }
 
 extern "C" int ra_watershed_attn_decode(ra_ctx* ctx, void* stream, const void* q, int Hq, const ra_kv_view* watershed,
                                         const void* cur_k, const void* cur_v, const int32_t* cur_len, int cur_cap,
                                         float scale, float* out, float* lse, float* scores_head, float* scores) {
     RA_REQUIRE(scores != nullptr, RA_ERR_INVALID_ARG, "watershed decode: scores is NULL");
-    return decode_impl(ctx, stream, q, Hq, watershed, nullptr, nullptr, cur_k, cur_v, cur_len, cur_cap, scale, out, lse,
-                       scores_head, scores);
+    return decode_impl(ctx, nullptr, stream, q, Hq, watershed, nullptr, nullptr, cur_k, cur_v, cur_len, cur_cap, scale, out,
+                       lse, scores_head, scores);
 }
