@@ -338,8 +338,9 @@ typedef enum ra_stage_order {
     RA_STAGE_LAYER_MAJOR = 1, /* one copy per (layer, round), layer by layer: the first post-watershed layer can
                                  start after 1 / n_layers of the transfer, at the price of n_layers times the copies */
     RA_STAGE_GROUPED = 2      /* one copy per (group of consecutive layers, round): a first group of n_layers / 8
-                                 layers, then groups of n_layers / 4.  Overlaps like LAYER_MAJOR with a fifth of its
-                                 copies; the order to use when compute should overlap the transfer (Sec. 3.2)  */
+                                 layers, up to three larger groups, a last group of one layer.  Overlaps like
+                                 LAYER_MAJOR with a fifth of its copies (24 layers: groups of 3, 7, 7, 6, 1); the order
+                                 to use when compute should overlap the transfer (Sec. 3.2)                    */
 } ra_stage_order;
 
 int ra_kv_store_create(ra_kv_store** out, const ra_store_cfg* cfg);

@@ -212,33 +212,67 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             meta[4 * b + 3] = n_hist + (cur_len > 0 ? 1 : 0);
         }
         __syncthreads();
-        for (int b = wave; b < B; b += 4) {  // one wave per sequence: prefix of its segments' tile counts
-            int carry = 0;
-            for (int i0 = 0; i0 < cap; i0 += 64) {
-                const int i = i0 + lane;
-                int units = 0;
-                if (i < cap) {
-                    int len;
-                    long long ok, ov;
-                    plan_entry(b, i, len, ok, ov);
-                    units = (len + kTile - 1) / kTile;
-                }
-                int total;
-                const int excl = wave_exclusive_scan(units, lane, total);
-                if (i < cap) cum_l[b * (cap + 1) + i] = carry + excl;
-                carry += total;
+        if (cap <= 128) {
+            // short tables (the usual case): the tile count of every entry by its own thread, then one thread per
+            // sequence turns its row into the exclusive prefix with a few dozen LDS operations
+            for (int idx = tid; idx < B * cap; idx += 256) {
+                const int b = idx / cap, i = idx - b * cap;
+                int len;
+                long long ok, ov;
+                plan_entry(b, i, len, ok, ov);
+                cum_l[b * (cap + 1) + i] = (len + kTile - 1) / kTile;
             }
-            if (lane == 0) {
-                cum_l[b * (cap + 1) + cap] = carry;
-                sU[b] = carry;
+            __syncthreads();
+            for (int b = tid; b < B; b += 256) {
+                int run = 0;
+                for (int i = 0; i < cap; ++i) {
+                    const int u = cum_l[b * (cap + 1) + i];
+                    cum_l[b * (cap + 1) + i] = run;
+                    run += u;
+                }
+                cum_l[b * (cap + 1) + cap] = run;
+                sU[b] = run;
+            }
+        } else {
+            for (int b = wave; b < B; b += 4) {  // one wave per sequence: prefix of its segments' tile counts
+                int carry = 0;
+                for (int i0 = 0; i0 < cap; i0 += 64) {
+                    const int i = i0 + lane;
+                    int units = 0;
+                    if (i < cap) {
+                        int len;
+                        long long ok, ov;
+                        plan_entry(b, i, len, ok, ov);
+                        units = (len + kTile - 1) / kTile;
+                    }
+                    int total;
+                    const int excl = wave_exclusive_scan(units, lane, total);
+                    if (i < cap) cum_l[b * (cap + 1) + i] = carry + excl;
+                    carry += total;
+                }
+                if (lane == 0) {
+                    cum_l[b * (cap + 1) + cap] = carry;
+                    sU[b] = carry;
+                }
             }
         }
+        __syncthreads();
+        if (tid == 0) {  // at most 64 sequences here: their prefix by one thread
+            int run = 0;
+            for (int b = 0; b < B; ++b) {
+                sps[b] = run;
+                run += sU[b];
+            }
+            sps[B] = run;
+        }
+        __syncthreads();
     } else {
         for (int b = tid; b < B; b += 256) sU[b] = reinterpret_cast<const PlanHeader*>(a.plan + (size_t)b * pstride)->U;
+        __syncthreads();
+        for (int b = tid; b < B; b += 256) sps[b] = sU[b];
+        exclusive_scan_units(sps, B);
     }
-    __syncthreads();
-    for (int b = tid; b < B; b += 256) sps[b] = sU[b];
-    exclusive_scan_units(sps, B);  // sps[b] = first tile of sequence b in the batch's list, sps[B] = all tiles
+    // sps[b] = first tile of sequence b in the batch's list, sps[B] = all tiles
     const int total = sps[B];
 
     // A sequence with an empty key set has no tile and therefore no wave: its rows are written here.

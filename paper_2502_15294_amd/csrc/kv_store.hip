@@ -57,6 +57,17 @@ using namespace ra;
 // whole 16-token tiles.
 static inline size_t layer_tokens(int len) { return (size_t)len + (size_t)((len + 15) / 16) * 16; }
 
+// Layers in group gi of the grouped staging order for L layers: first max(1, L / 8); last 1; the layers in
+// between in three groups as equal as possible (fewer when there are fewer layers).
+static int grouped_stage_size(int L, int gi) {
+    const int first = L / 8 > 1 ? L / 8 : 1;
+    if (gi == 0) return first < L ? first : L;
+    const int middle = L - first - 1;                 // layers between the first group and the last layer
+    const int n_mid = middle < 3 ? (middle > 0 ? middle : 0) : 3;
+    if (gi <= n_mid) return middle / n_mid + (gi <= middle % n_mid ? 1 : 0);
+    return 1;
+}
+
 static bool is_pinned_host(const void* p) {
     hipPointerAttribute_t attr;
     hipError_t e = hipPointerGetAttributes(&attr, p);
@@ -303,11 +314,11 @@ int ra_kv_store_stage(ra_kv_store* s, const int32_t* sel_idx_host, const int32_t
         for (int l = 0; l < L; ++l) RA_HIP_CHECK(hipEventRecord(s->ready[l], st));
     } else if (order == RA_STAGE_GROUPED) {
         // Groups of consecutive layers, one copy per (group, round): a round's layers are contiguous in its host
-        // tensor, so a group is one slice.  A small first group lets the first post-watershed layer start early,
-        // larger groups keep the number of copies (and their fixed cost on the link) down.
-        for (int l0 = 0; l0 < L;) {
-            const int g = l0 == 0 ? (L / 8 > 1 ? L / 8 : 1) : ((L + 3) / 4 > 1 ? (L + 3) / 4 : 1);
-            const int l1 = l0 + g < L ? l0 + g : L;
+        // tensor, so a group is one slice.  A small first group lets the first post-watershed layer start early, a
+        // last group of one layer leaves a single layer's attention to run after the last byte has arrived, and
+        // up to three larger groups in between keep the number of copies (and their fixed cost on the link) down.
+        for (int l0 = 0, gi = 0; l0 < L; ++gi) {
+            const int l1 = l0 + grouped_stage_size(L, gi);
             for (const Job& jb : jobs) {
                 if (jb.len == 0) continue;
                 const size_t bytes = (size_t)(l1 - l0) * layer_tokens(jb.len) * s->token_bytes;

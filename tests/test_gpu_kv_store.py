@@ -25,13 +25,20 @@ def _make_store(w, pool_bytes):
     return ra.ra_kv_store_create(0, w.n_post_layers, w.B, max(w.R_max, 1), w.Hkv, w.d, dt, pool_bytes)
 
 
+def _grouped_sizes(L):
+    """Groups of the grouped order: first max(1, L // 8) layers, last one layer, the layers in between in up to
+    three groups as equal as possible."""
+    first = max(L // 8, 1)
+    if first >= L:
+        return [L]
+    middle = L - first - 1
+    n_mid = min(3, max(middle, 0))
+    mids = [middle // n_mid + (1 if i < middle % n_mid else 0) for i in range(n_mid)]
+    return [first] + mids + [1]
+
+
 def _grouped_copies_per_round(L):
-    """Groups of the grouped order: a first group of L / 8 layers (at least one), then groups of ceil(L / 4)."""
-    n, l0 = 0, 0
-    while l0 < L:
-        l0 += max(L // 8, 1) if l0 == 0 else max((L + 3) // 4, 1)
-        n += 1
-    return n
+    return len(_grouped_sizes(L))
 
 
 @pytest.mark.parametrize("order,n_layers", [(ra.RA_STAGE_ROUND_MAJOR, 3), (ra.RA_STAGE_LAYER_MAJOR, 3),
@@ -82,7 +89,8 @@ def test_store_stage_then_decode_every_layer(order, n_layers):
     n_sel_rounds = int(n_h.sum())
     per_round = {ra.RA_STAGE_ROUND_MAJOR: 1, ra.RA_STAGE_LAYER_MAJOR: len(layers),
                  ra.RA_STAGE_GROUPED: _grouped_copies_per_round(len(layers))}[order]
-    assert _grouped_copies_per_round(24) == 5 and _grouped_copies_per_round(9) == 4
+    assert _grouped_sizes(24) == [3, 7, 7, 6, 1] and _grouped_sizes(9) == [1, 3, 2, 2, 1] and _grouped_sizes(3) == [1, 1, 1]
+    assert _grouped_sizes(1) == [1] and _grouped_sizes(2) == [1, 1] and all(sum(_grouped_sizes(n)) == n for n in range(1, 70))
     assert n_copies == n_sel_rounds * per_round
 
     # a second selection after release reuses the pool
