@@ -63,6 +63,9 @@ def parse():
     ap.add_argument("--lam", type=float, default=1.0, help="multiplier of the adaptive selection rule")
     ap.add_argument("--alpha", type=float, default=None, help="override the key bias strength of the workload")
     ap.add_argument("--replicas", type=int, default=0, help="input replicas rotated through (0 = enough to defeat the Infinity Cache)")
+    ap.add_argument("--prefill-p", default="bf16x2", choices=["bf16x2", "f16"],
+                    help="how the many-row prefill kernel feeds P to the matrix cores (ra_set_prefill_precision); "
+                         "f16 is the named lower-precision mode and is reported as such in config")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the workload itself: no kept-fraction points, no cfg2 / cfg3 / cfg4 summaries")
@@ -141,7 +144,24 @@ def cpu_baseline(w, lam: float, seqs, gpu=None):
     return res, parity
 
 
-def bench_step(name, plan, alpha, replicas, dense=True, keep_outputs=False):
+def cpu_baseline_once(w, lam, b, gpu):
+    """One oracle pass over sequence b (untimed use): the parity figures of the GPU outputs `gpu`."""
+    from oracle import round_attention as ora
+    R = w.n_rounds(b)
+    ck0 = None if w.cur_len == 0 else w.cur_k(0)[b]
+    _, S = ora.round_scores(w.q(0)[b], [w.k_round(b, 0, r) for r in range(R)], w.scale, ck0)
+    sel, info = ora.select_rounds(S, lam=lam)
+    O, _ = ora.sparse_attention(w.q(1)[b], [w.k_round(b, 1, r) for r in range(R)], [w.v_round(b, 1, r) for r in range(R)],
+                                sel, w.scale, None if w.cur_len == 0 else w.cur_k(1)[b],
+                                None if w.cur_len == 0 else w.cur_v(1)[b])
+    S_g, sel_g, n_g, out_g = gpu
+    ref = O if out_g[b].ndim == 3 else O[0]
+    return O, {"selection_bit_exact": sel_g[b, :n_g[b]].tolist() == sel, "margin": info["margin"],
+               "max_score_error": float(np.abs(S_g[b, :R] - S).max()), "max_row_error": ora.row_error(out_g[b], ref),
+               "max_large_entry_error": ora.large_entry_error(out_g[b], ref)}
+
+
+def bench_step(name, plan, alpha, replicas, dense=True, keep_outputs=False, p_mode=0):
     """scores + selection -> sparse attention on one post-watershed layer, everything resident in HBM.
     `plan` is a list of (lambda, steps, warmup, min_seconds); returns one result per entry."""
     import torch
@@ -154,6 +174,7 @@ def bench_step(name, plan, alpha, replicas, dense=True, keep_outputs=False):
     prefill = w.q_len > 1
     eb = 2 if w.dtype == "bf16" else 4
     eng = Engine(w)
+    ra.ra_set_prefill_precision(eng.ctx, p_mode)
     t_gen = time.perf_counter()
     view0 = device_view(w, 0, with_v=False, threads=16)
     view1 = device_view(w, 1, threads=16)
@@ -729,7 +750,8 @@ def main():
         sweep_here = args.workload == "cfg5" and not args.no_extras and args.alpha is None
         if sweep_here:
             plan.append((0.0, 20, 3, 0.0))  # same inputs, the "greater than the average" rule of Sec. 4.4: about 60 % kept
-        many, w = bench_step(args.workload, plan, args.alpha, args.replicas, dense=dense, keep_outputs=True)
+        many, w = bench_step(args.workload, plan, args.alpha, args.replicas, dense=dense, keep_outputs=True,
+                             p_mode=ra.RA_PREFILL_P_F16 if args.prefill_p == "f16" else ra.RA_PREFILL_P_BF16X2)
         res = many[0]
         gpu = res.pop("_gpu_outputs")
         for r in many[1:]:
@@ -746,6 +768,8 @@ def main():
     res.pop("_gpu_outputs", None)
     result.update(res)
     result.update(extras)
+    if args.workload != "cfg4" and result["config"].get("q_len", 1) > 1:
+        result["config"]["prefill_p"] = args.prefill_p
 
     if not args.no_extras and args.workload == "cfg5":
         # the other configurations, compact (each also runs on its own with --workload)
@@ -761,11 +785,24 @@ def main():
             return _compact(r[0])
 
         def run_cfg3():
-            r, _ = bench_step("cfg3", [(1.0, 50, 5, MIN_TIMED_SECONDS)], None, 0, dense=False)
-            r[0].pop("_gpu_outputs")
+            r, w3 = bench_step("cfg3", [(1.0, 50, 5, MIN_TIMED_SECONDS)], None, 0, dense=False, keep_outputs=True)
+            gpu3 = r[0].pop("_gpu_outputs")
             c = _compact(r[0])
             c["mfma_busy_source"] = MFMA_BUSY_SOURCE
             c["frac_of_bf16_mfma_peak"] = {k: v["kernel_TFLOP/s"] / MFMA_BF16_PEAK_TFLOPS for k, v in c["kernel_groups"].items()}
+            # the same step with the named fp16-P mode of the attention kernel (one pass over V instead of two)
+            h, _ = bench_step("cfg3", [(1.0, 50, 5, MIN_TIMED_SECONDS)], None, 0, dense=False, keep_outputs=True,
+                              p_mode=ra.RA_PREFILL_P_F16)
+            gpu3h = h[0].pop("_gpu_outputs")
+            g = h[0]["kernel_groups"]["ra_round_sparse_attn_prefill"]
+            c["attention_with_p_f16"] = {"mode": "RA_PREFILL_P_F16 (ra_set_prefill_precision; not the default)",
+                                         "kernel_ms": g["kernel_ms"], "kernel_TFLOP/s": g["kernel_TFLOP/s"],
+                                         "frac_of_bf16_mfma_peak": g["kernel_TFLOP/s"] / MFMA_BF16_PEAK_TFLOPS,
+                                         "ms_per_step": h[0]["ms_per_step"], "tokens/s": h[0]["value"]}
+            if not args.no_cpu_baseline:  # one sequence of the batch against the oracle, both modes
+                _, par = cpu_baseline_once(w3, 1.0, 0, gpu3)
+                _, parh = cpu_baseline_once(w3, 1.0, 0, gpu3h)
+                c["parity"] = {"sequence": 0, "p_bf16x2": par, "p_f16": parh}
             return c
 
         def run_cfg4():

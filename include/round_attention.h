@@ -286,6 +286,19 @@ int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const void* q, int q
                                  float* lse);
 
 /*
+ * How ra_round_sparse_attn_prefill with many query rows (q_len * Hq / Hkv > 32; Sec. 3.2 step 4) feeds the softmax
+ * probabilities P to the matrix cores for P.V.  A setting of the context; it changes no other call (not
+ * ra_watershed_attn_prefill either, whose scores decide the selection).
+ *   RA_PREFILL_P_BF16X2  (default) P as the sum of two bf16 numbers, two passes over V: about 16 bits of P,
+ *                        output error about 2e-5 of a row's largest magnitude
+ *   RA_PREFILL_P_F16     P rounded to fp16, V converted to fp16 on chip, one pass: a third fewer matrix-core
+ *                        instructions; output error about 1e-4 (the contract of every attention call is 2e-3).
+ *                        Values beyond fp16's range (|v| > 65504) saturate: use the default for such caches.
+ */
+typedef enum ra_prefill_precision { RA_PREFILL_P_BF16X2 = 0, RA_PREFILL_P_F16 = 1 } ra_prefill_precision;
+int ra_set_prefill_precision(ra_ctx* ctx, int mode);
+
+/*
  * Sec. 3.1, Observation 2 and Fig. 2b: the curve whose drop marks the watershed layer.  For each
  * layer l = 0 .. L-2 and each sequence, the mean over the later layers l' > l of
  * KL(P^l || P^l') = sum_r P^l_r ln(P^l_r / P^l'_r) (natural logarithm; a round with P^l_r = 0 adds

@@ -21,12 +21,13 @@ LIB_PATH = os.environ.get("RA_LIBRARY") or os.path.join(_HERE, "libround_attenti
 RA_F32, RA_BF16 = 0, 1
 RA_SEL_ADAPTIVE, RA_SEL_TOP_FRACTION, RA_SEL_THRESHOLD = 0, 1, 2
 RA_STAGE_ROUND_MAJOR, RA_STAGE_LAYER_MAJOR, RA_STAGE_GROUPED = 0, 1, 2
+RA_PREFILL_P_BF16X2, RA_PREFILL_P_F16 = 0, 1
 RA_OK, RA_ERR_INVALID_ARG, RA_ERR_UNSUPPORTED, RA_ERR_WORKSPACE, RA_ERR_STATE, RA_ERR_OOM, RA_ERR_HIP = \
     0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "ra_last_error", "ra_create", "ra_destroy", "ra_workspace_bytes", "ra_set_workspace",
-    "ra_profile_kernels", "ra_profile_last_ms",
+    "ra_profile_kernels", "ra_profile_last_ms", "ra_set_prefill_precision",
     "ra_round_scores", "ra_round_scores_select", "ra_select_rounds", "ra_round_sparse_attn_decode", "ra_round_sparse_attn_decode_noalloc",
     "ra_watershed_attn_decode",
     "ra_round_sparse_attn_prefill", "ra_watershed_attn_prefill",
@@ -87,6 +88,7 @@ def lib() -> C.CDLL:
         L.ra_workspace_bytes.argtypes = [C.POINTER(ra_problem), C.POINTER(C.c_size_t)]
         L.ra_set_workspace.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
         L.ra_profile_kernels.argtypes = [C.c_void_p, C.c_int]
+        L.ra_set_prefill_precision.argtypes = [C.c_void_p, C.c_int]
         L.ra_profile_last_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.ra_round_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(ra_kv_view),
                                       C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p]
@@ -218,6 +220,10 @@ def ra_set_workspace(ctx, workspace: Optional[torch.Tensor]) -> None:
         _check(lib().ra_set_workspace(ctx, None, 0))
     else:
         _check(lib().ra_set_workspace(ctx, workspace.data_ptr(), workspace.numel() * workspace.element_size()))
+
+
+def ra_set_prefill_precision(ctx, mode: int) -> None:
+    _check(lib().ra_set_prefill_precision(ctx, mode))
 
 
 def ra_profile_kernels(ctx, enable: bool) -> None:

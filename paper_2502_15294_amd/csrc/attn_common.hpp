@@ -40,6 +40,7 @@ struct AttnArgs {
     float* rec_ml;    // [records][inner][16][2]   running max of the raw logits, sum of 2^((logit - max) * c)
     int* seq_rec;     // [B][2] first record and number of records of every sequence (written by the kernel)
     int max_ranges;   // most ranges the batch's key tiles are cut into
+    int p_half;       // many-row kernel: probabilities as one fp16 operand instead of two bf16 (ra_set_prefill_precision)
 };
 
 // Workspace layout of one attention call; returns the bytes needed past the reserved head.

@@ -19,11 +19,42 @@
 // never restarted for that: the chunk's share is the difference of the running sum between the chunk's ends (a
 // mark that is rescaled together with the sum), exact to a few ulp of the sum, i.e. far below the 1e-5 the
 // normalised scores are held to.  Pieces then begin and end on chunk boundaries, so that one piece owns a chunk.
+//
+// P_HALF (ra_set_prefill_precision, not the default): P goes to the matrix cores once, as fp16, instead of twice
+// as hi + lo bf16.  The values are converted to fp16 on their way into LDS (a bf16 number is an fp16 number as
+// long as its magnitude lies in [2^-14, 65504]; larger ones saturate, smaller ones lose low bits), P is kept in
+// [2^-24, 2^15] by a softmax reference that lags the running maximum by at most 2^8 and a fixed scale of 2^7, it
+// is rounded to fp16 (nearest even) and the SAME rounded values are summed for the normaliser (dot2 against ones,
+// fp32 accumulate), so the rounding acts as a perturbation of the weights of at most 2^-12 each, of either sign,
+// that averages out over the keys.  One third fewer matrix-core instructions per tile; the output error grows
+// from about 2e-5 to about 1e-4 of the row's largest magnitude (contract: 2e-3).
 #include "attn_common.hpp"
 #include "mfma_util.hpp"
 #include "stream_kv.hpp"
 
 namespace ra {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ floatx4_t mfma16h(uint4 a, uint4 b, floatx4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+}
+// Two floats -> packed fp16 pair (low half = a): by truncation, exact for numbers that fp16 holds ...
+__device__ __forceinline__ uint32_t pack_half_rtz(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+// ... and rounded to nearest even (one v_cvt_pk_f16_f32): relative error <= 2^-12 in fp16's normal range.
+__device__ __forceinline__ uint32_t pack_half_rne(float a, float b) {
+    typedef float float2_t __attribute__((ext_vector_type(2)));
+    const float2_t f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, half2_t));
+}
+// Four bf16 numbers -> the same four numbers as fp16 (exact inside fp16's normal range).
+__device__ __forceinline__ uint2 bf16x4_to_half(uint2 x) {
+    return make_uint2(pack_half_rtz(as_f32(x.x << 16), as_f32(x.x & 0xffff0000u)),
+                      pack_half_rtz(as_f32(x.y << 16), as_f32(x.y & 0xffff0000u)));
+}
+constexpr int kHalfScaleLog2 = 7;  // P is carried as 2^7 x its value in the fp16 mode (see above)
 
 constexpr int kTileP = 32;                      // tokens per key tile
 constexpr int kNTP = 2;                         // 16-row tiles per wave
@@ -37,7 +68,7 @@ struct Share {
     uint2 v0, v1, v2, v3;  // V^T fragments (dt, half) = (2*wave, 0), (2*wave, 1), (2*wave + 1, 0), (2*wave + 1, 1)
 };
 
-template <bool PAGED, bool TILE_LSE>
+template <bool PAGED, bool TILE_LSE, bool P_HALF>
 __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, int n_rowblocks) {
     extern __shared__ __align__(16) char smem[];
     __shared__ int sU[kMaxBatch], sps[kMaxBatch + 1];
@@ -115,7 +146,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
         floatx4_t acc[kNTP][8];
         float m[kNTP], l[kNTP];
         float l_mark[kNTP];  // the running sum as it stood at the start of the current chunk (score output only)
-        const float slack = 16.f / a.c;
+        const float slack = (P_HALF ? 8.f : 16.f) / a.c;
 #pragma unroll
         for (int nt = 0; nt < kNTP; ++nt) {
             m[nt] = kNegBig;
@@ -231,10 +262,10 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             kd[(row + n) & 15] = sh.k0;
             kd[(row + 4 + n) & 15] = sh.k1;
             uint2* vd = reinterpret_cast<uint2*>(buf + 8192) + 4 * wave * 64 + lane;
-            vd[0] = sh.v0;
-            vd[64] = sh.v1;
-            vd[128] = sh.v2;
-            vd[192] = sh.v3;
+            vd[0] = P_HALF ? bf16x4_to_half(sh.v0) : sh.v0;
+            vd[64] = P_HALF ? bf16x4_to_half(sh.v1) : sh.v1;
+            vd[128] = P_HALF ? bf16x4_to_half(sh.v2) : sh.v2;
+            vd[192] = P_HALF ? bf16x4_to_half(sh.v3) : sh.v3;
         };
         auto consume = [&](const char* buf, int tok0, int len, bool is_cur) {
             const bool full = !is_cur && (len - tok0 >= kTileP);
@@ -296,29 +327,47 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                 const uint2 v0 = vb[(dt * 2 + 0) * 64 + lane], v1 = vb[(dt * 2 + 1) * 64 + lane];
                 vf[dt] = make_uint4(v0.x, v0.y, v1.x, v1.y);
             }
-            auto probabilities = [&](int nt, uint4& phi, uint4& plo) {  // P = hi + lo of row tile nt, and its row sums
-                const float mc = m[nt] * a.c;
+            auto probabilities = [&](int nt, uint4& phi, uint4& plo) {  // P (hi + lo, or fp16) of row tile nt, and its row sums
+                const float mc = m[nt] * a.c - (P_HALF ? (float)kHalfScaleLog2 : 0.f);
                 float p[8];
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) p[h * 4 + i] = fast_exp2(__builtin_fmaf(sc[nt][h][i], a.c, -mc));
-                const float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-                l[nt] += ps;
-                phi.x = pack_hi16(p[0], p[1]);
-                phi.y = pack_hi16(p[2], p[3]);
-                phi.z = pack_hi16(p[4], p[5]);
-                phi.w = pack_hi16(p[6], p[7]);
-                plo.x = pack_hi16(p[0] - trunc_bf16(p[0]), p[1] - trunc_bf16(p[1]));
-                plo.y = pack_hi16(p[2] - trunc_bf16(p[2]), p[3] - trunc_bf16(p[3]));
-                plo.z = pack_hi16(p[4] - trunc_bf16(p[4]), p[5] - trunc_bf16(p[5]));
-                plo.w = pack_hi16(p[6] - trunc_bf16(p[6]), p[7] - trunc_bf16(p[7]));
+                if constexpr (P_HALF) {
+                    phi.x = pack_half_rne(p[0], p[1]);
+                    phi.y = pack_half_rne(p[2], p[3]);
+                    phi.z = pack_half_rne(p[4], p[5]);
+                    phi.w = pack_half_rne(p[6], p[7]);
+                    const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+                    float ps = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, phi.x), ones, 0.f, false);
+                    ps = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, phi.y), ones, ps, false);
+                    ps = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, phi.z), ones, ps, false);
+                    ps = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, phi.w), ones, ps, false);
+                    l[nt] += ps;  // the rounded values, the ones the products use
+                    plo = phi;
+                } else {
+                    const float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+                    l[nt] += ps;
+                    phi.x = pack_hi16(p[0], p[1]);
+                    phi.y = pack_hi16(p[2], p[3]);
+                    phi.z = pack_hi16(p[4], p[5]);
+                    phi.w = pack_hi16(p[6], p[7]);
+                    plo.x = pack_hi16(p[0] - trunc_bf16(p[0]), p[1] - trunc_bf16(p[1]));
+                    plo.y = pack_hi16(p[2] - trunc_bf16(p[2]), p[3] - trunc_bf16(p[3]));
+                    plo.z = pack_hi16(p[4] - trunc_bf16(p[4]), p[5] - trunc_bf16(p[5]));
+                    plo.w = pack_hi16(p[6] - trunc_bf16(p[6]), p[7] - trunc_bf16(p[7]));
+                }
             };
             auto accumulate = [&](int nt, const uint4& phi, const uint4& plo) {
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt) {
-                    acc[nt][dt] = mfma16(vf[dt], phi, acc[nt][dt]);
-                    acc[nt][dt] = mfma16(vf[dt], plo, acc[nt][dt]);
+                    if constexpr (P_HALF) {
+                        acc[nt][dt] = mfma16h(vf[dt], phi, acc[nt][dt]);
+                    } else {
+                        acc[nt][dt] = mfma16(vf[dt], phi, acc[nt][dt]);
+                        acc[nt][dt] = mfma16(vf[dt], plo, acc[nt][dt]);
+                    }
                 }
             };
             // Row tile by row tile: the first tile's products can run on the matrix cores while the vector ALU
@@ -366,7 +415,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                                 const size_t head = rowid[nt] - ((size_t)b * q_len + qtok[nt]) * a.Hq;
                                 const size_t srow = ((size_t)b * a.Hq + head) * q_len + qtok[nt];
                                 a.tile_lse[srow * a.n_tiles_max + chunk] =
-                                    share > 0.f ? kLn2 * __builtin_fmaf(m[nt], a.c, fast_log2(share)) : -__builtin_inff();
+                                    share > 0.f ? kLn2 * (__builtin_fmaf(m[nt], a.c, fast_log2(share)) -
+                                                          (P_HALF ? (float)kHalfScaleLog2 : 0.f))
+                                                : -__builtin_inff();
                             }
                         }
                     }
@@ -379,6 +430,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
 #pragma unroll
         for (int nt = 0; nt < kNTP; ++nt) {
             l[nt] = xrow_sum4(l[nt]);
+            if constexpr (P_HALF) {  // take the fixed scale of P out again (a power of two: exact)
+                constexpr float unscale = 1.f / (float)(1 << kHalfScaleLog2);
+                l[nt] *= unscale;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) acc[nt][dt] *= unscale;
+            }
             if (!row_ok[nt]) continue;
             if (S_eff > 1) {
                 const size_t pr = rowid[nt] * a.S + s;
@@ -417,17 +474,16 @@ int launch_attn_prefill_mfma(const AttnArgs& a, bool paged, int num_cu, hipStrea
     long long grid = (long long)2 * num_cu;
     if (grid > max_pieces * Hkv * n_rowblocks) grid = max_pieces * Hkv * n_rowblocks;
     if (grid < 1) grid = 1;
-    if (a.tile_lse) {
-        if (paged)
-            RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<true, true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-        else
-            RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<false, true>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-    } else {
-        if (paged)
-            RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<true, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
-        else
-            RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<false, false>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks);
+    const bool lse = a.tile_lse != nullptr, half = a.p_half != 0;
+#define RA_PREFILL_CASE(P_, L_, H_)                                                                                  \
+    if (paged == P_ && lse == L_ && half == H_) {                                                                    \
+        RA_LAUNCH_TIMED((attn_prefill_mfma_kernel<P_, L_, H_>), dim3((unsigned)grid), dim3(256), smem, st, a, n_rowblocks); \
+        return RA_OK;                                                                                                \
     }
+    RA_PREFILL_CASE(false, false, false) RA_PREFILL_CASE(false, true, false) RA_PREFILL_CASE(true, false, false)
+    RA_PREFILL_CASE(true, true, false) RA_PREFILL_CASE(false, false, true) RA_PREFILL_CASE(false, true, true)
+    RA_PREFILL_CASE(true, false, true) RA_PREFILL_CASE(true, true, true)
+#undef RA_PREFILL_CASE
     return RA_OK;
 }
 

@@ -34,6 +34,7 @@ struct ra_ctx {
     int device = 0;
     int num_cu = 256;
     ra::Workspace ws;
+    int prefill_p_half = 0;  // ra_set_prefill_precision
     // kernel timing on request (ra_profile_kernels)
     bool profile = false, timed = false;
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;

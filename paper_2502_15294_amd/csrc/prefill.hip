@@ -100,6 +100,7 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
     a.rec_ml = few_rows ? reinterpret_cast<float*>(ctx->ws.base + mw.ml_off) : nullptr;
     a.seq_rec = reinterpret_cast<int*>(ctx->ws.base + kWsSeqRecOff);
     a.max_ranges = shape.max_ranges;
+    a.p_half = with_scores ? 0 : ctx->prefill_p_half;  // the watershed call's scores decide the selection: full precision
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (!(few_rows && attn_mfma_plans_inline(B, layer->R_max))) launch_plan(a, 32, st);
     {
@@ -146,4 +147,12 @@ extern "C" int ra_watershed_attn_prefill(ra_ctx* ctx, void* stream, const void* 
     RA_REQUIRE(scores != nullptr, RA_ERR_INVALID_ARG, "watershed prefill: scores is NULL");
     return prefill_impl(ctx, stream, q, q_len, Hq, watershed, nullptr, nullptr, cur_k, cur_v, cur_len, scale, out, lse,
                         scores_head, scores);
+}
+
+extern "C" int ra_set_prefill_precision(ra_ctx* ctx, int mode) {
+    RA_REQUIRE(ctx != nullptr, RA_ERR_INVALID_ARG, "ra_set_prefill_precision: ctx is NULL");
+    RA_REQUIRE(mode == RA_PREFILL_P_BF16X2 || mode == RA_PREFILL_P_F16, RA_ERR_INVALID_ARG,
+               "ra_set_prefill_precision: unknown mode %d", mode);
+    ctx->prefill_p_half = mode == RA_PREFILL_P_F16;
+    return RA_OK;
 }

@@ -413,12 +413,22 @@ PREFILL_CASES = {
 }
 
 
+# Bar of the named fp16-P mode of the many-row prefill kernel.  Each weight is rounded to fp16 (relative error
+# <= 2^-12, the same rounded values in numerator and denominator), so an output moves by at most
+# 2^-11 * sum_i p_i |v_i| / sum_i p_i; row_error divides by the row's largest OUTPUT, which for averaged values is
+# smaller than the mean |v|, hence a bar of 2^-10: half the 2e-3 contract, 20 times the default mode's bar.
+HALF_TOL = 2.0 ** -10
+
+
+@pytest.mark.parametrize("p_mode", [ra.RA_PREFILL_P_BF16X2, ra.RA_PREFILL_P_F16], ids=["p_bf16x2", "p_f16"])
 @pytest.mark.parametrize("name", list(PREFILL_CASES))
-def test_prefill_matches_oracle(name):
+def test_prefill_matches_oracle(name, p_mode):
     over, sels = PREFILL_CASES[name]
     w = make_workload("cfg3", **over)
     _say(f"prefill case {name}: B={w.B} q_len={w.q_len} cur_len={w.cur_len} Hq={w.Hq} block={w.block_size}")
     eng = Engine(w)
+    ra.ra_set_prefill_precision(eng.ctx, p_mode)
+    STREAM_TOL = HALF_TOL if p_mode == ra.RA_PREFILL_P_F16 else globals()["STREAM_TOL"]
     view = device_view(w, 1)
     q = to_device(w.q(1), w.dtype)
     ck = to_device(w.cur_k(1), w.dtype) if w.cur_len else None
@@ -431,7 +441,8 @@ def test_prefill_matches_oracle(name):
     err = ora.row_error(out, ref_o)
     _say(f"  row error {err:.3e}, lse error {np.abs(lse - ref_l).max():.3e}")
     assert err < OUT_TOL and err < STREAM_TOL
-    assert np.allclose(lse, ref_l, rtol=0, atol=2e-5 * max(1.0, np.abs(ref_l).max()))
+    lse_tol = 2e-5 if p_mode == ra.RA_PREFILL_P_BF16X2 else HALF_TOL   # ln of a sum of weights each rounded to fp16
+    assert np.allclose(lse, ref_l, rtol=0, atol=lse_tol * max(1.0, np.abs(ref_l).max()))
     eng.close()
 
 
@@ -484,10 +495,13 @@ def test_round_scores_prefill_shape_match_oracle(name):
     eng.close()
 
 
-def test_prefill_pipeline_end_to_end_reduced_config3():
+@pytest.mark.parametrize("p_mode", [ra.RA_PREFILL_P_BF16X2, ra.RA_PREFILL_P_F16], ids=["p_bf16x2", "p_f16"])
+def test_prefill_pipeline_end_to_end_reduced_config3(p_mode):
     """scores (q_len 128, causal current round) -> selection -> prefill attention, config 3 at reduced batch / context."""
     w = make_workload("cfg3", B=2, length=("lognormal", 400.0, 0.8, 8192))
     eng = Engine(w)
+    ra.ra_set_prefill_precision(eng.ctx, p_mode)
+    STREAM_TOL = HALF_TOL if p_mode == ra.RA_PREFILL_P_F16 else globals()["STREAM_TOL"]
     v0, v1 = device_view(w, 0, with_v=False), device_view(w, 1)
     P, S = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), v0, to_device(w.cur_k(0), w.dtype), scale=w.scale)
     sel_idx, n_sel = ra.ra_select_rounds(eng.ctx, S, v0.n_rounds)
@@ -690,6 +704,12 @@ def test_watershed_decode_attention_and_scores_match_oracle(name, staged):
     P2, S2 = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), view, scale=w.scale)
     torch.cuda.synchronize()
     assert torch.equal(out, out2) and torch.equal(lse, lse2)
+    # the fp16-P mode is for the post-watershed layers: the watershed call, whose scores decide the selection, ignores it
+    ra.ra_set_prefill_precision(eng.ctx, ra.RA_PREFILL_P_F16)
+    out3, lse3, P3, S3 = ra.ra_watershed_attn_prefill(eng.ctx, q, view, ck, cv, scale=w.scale)
+    ra.ra_set_prefill_precision(eng.ctx, ra.RA_PREFILL_P_BF16X2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out3) and torch.equal(lse, lse3) and torch.equal(P, P3) and torch.equal(S, S3)
     out, P, S, P2, S2 = out.cpu().numpy(), P.cpu().numpy(), S.cpu().numpy(), P2.cpu().numpy(), S2.cpu().numpy()
     assert np.abs(P - P2).max() < SCORE_TOL and np.abs(S - S2).max() < SCORE_TOL
     for b in (range(w.B) if w.B <= 4 else (0, w.B - 1)):
@@ -751,6 +771,12 @@ def test_watershed_prefill_attention_and_scores_match_oracle(name):
         # so the two results differ by the arithmetic's own error (both are held to the oracle below)
         assert ora.row_error(out.cpu().numpy(), out2.cpu().numpy()) < STREAM_TOL
         assert (lse - lse2).abs().max().item() < 2e-5
+    # the fp16-P mode is for the post-watershed layers: the watershed call, whose scores decide the selection, ignores it
+    ra.ra_set_prefill_precision(eng.ctx, ra.RA_PREFILL_P_F16)
+    out3, lse3, P3, S3 = ra.ra_watershed_attn_prefill(eng.ctx, q, view, ck, cv, scale=w.scale)
+    ra.ra_set_prefill_precision(eng.ctx, ra.RA_PREFILL_P_BF16X2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out3) and torch.equal(lse, lse3) and torch.equal(P, P3) and torch.equal(S, S3)
     out, P, S, P2, S2 = out.cpu().numpy(), P.cpu().numpy(), S.cpu().numpy(), P2.cpu().numpy(), S2.cpu().numpy()
     assert np.abs(P - P2).max() < SCORE_TOL and np.abs(S - S2).max() < SCORE_TOL
     for b in range(w.B):
