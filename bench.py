@@ -43,15 +43,20 @@ WORKLOADS = {
     "cfg5": "70B-shaped layer slice, bf16, B=64 decode, 64/8 heads, d=128, 50 rounds of U[300,1000] tokens, "
             "16-token paged blocks",
 }
-# HBM bytes per launch of the streaming kernels from hardware-counter runs (rocprofv3 --pmc FETCH_SIZE, then
-# WRITE_SIZE, each scaled by what the same counter reads for a copy kernel of known size).  These are RECORDED
-# figures from profiles/bench_default_hbm_traffic_counters.md, not measurements of the current run.
+# HBM bytes per launch of the attention kernel (read + written) from hardware-counter runs (rocprofv3 --pmc
+# FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB copy: 2 KiB and 1 KiB per
+# count).  RECORDED figures for the workload's own inputs at lambda = 1, copied from the files named below; they are
+# not measurements of the current run, and other lambda / alpha report null.
 RECORDED_TRAFFIC = {
-    ("cfg5", "ra_round_sparse_attn_decode"): None,
-    ("cfg5", "ra_round_scores_select"): None,
+    ("cfg5", "ra_round_sparse_attn_decode"): 1196328288 + 10483805,
+    ("cfg2", "ra_round_sparse_attn_decode"): 49680349 + 1630784,
 }
-TRAFFIC_SOURCE = "profiles/bench_default_hbm_traffic_counters.md (rocprofv3 --pmc runs of this command; recorded, not measured in this run)"
-MFMA_BUSY_SOURCE = "profiles/bench_cfg3_prefill_kernel_trace_and_sq_counters.md (rocprofv3 --pmc; recorded, not measured in this run)"
+TRAFFIC_SOURCES = {
+    "cfg5": "profiles/attn_mfma_kernel_cfg5_paged_decode.md",
+    "cfg2": "profiles/attn_mfma_kernel_cfg2_small_batch_decode.md",
+}
+MFMA_BUSY_SOURCE = "profiles/attn_prefill_mfma_kernel_cfg3_question_prefill.md (rocprofv3 --pmc; recorded, not measured in this run)"
+RECORDED_MFMA_BUSY = {"scores_prefill_mfma_kernel": 0.367, "attn_prefill_mfma_kernel": 0.443}
 
 
 def parse():
@@ -311,7 +316,9 @@ def bench_step(name, plan, alpha, replicas, dense=True, keep_outputs=False, p_mo
         else:
             roof = {"bound": "hbm", "kernel": attn_kernel, "achieved": g_attn["kernel_GB/s"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": g_attn["kernel_GB/s"] / HBM_PEAK_GBS,
-                    "traffic": RECORDED_TRAFFIC.get((w.name, attn_name)), "traffic_source": TRAFFIC_SOURCE,
+                    "traffic": RECORDED_TRAFFIC.get((w.name, attn_name)) if (lam == 1.0 and alpha is None) else None,
+                    "traffic_source": (TRAFFIC_SOURCES.get(w.name, "none recorded for this workload")
+                                       + " (rocprofv3 --pmc runs of this command; recorded, not measured in this run)"),
                     "whole_call_achieved": g_attn["GB/s"],
                     "algorithmic_bytes_per_launch": g_attn["bytes"], "kernel_us": g_attn["kernel_ms"] * 1e3,
                     "score_pass": {"kernel": scores_kernel, "achieved": groups["ra_round_scores_select"]["kernel_GB/s"],
@@ -788,6 +795,7 @@ def main():
             r, w3 = bench_step("cfg3", [(1.0, 50, 5, MIN_TIMED_SECONDS)], None, 0, dense=False, keep_outputs=True)
             gpu3 = r[0].pop("_gpu_outputs")
             c = _compact(r[0])
+            c["mfma_busy"] = RECORDED_MFMA_BUSY
             c["mfma_busy_source"] = MFMA_BUSY_SOURCE
             c["frac_of_bf16_mfma_peak"] = {k: v["kernel_TFLOP/s"] / MFMA_BF16_PEAK_TFLOPS for k, v in c["kernel_groups"].items()}
             # the same step with the named fp16-P mode of the attention kernel (one pass over V instead of two)

@@ -12,10 +12,9 @@
 // both r and b only grow, so  record(r, b) = r + b  is unique over all segments, and the records of one
 // sequence are consecutive: record_first(b) .. + n_parts(b) - 1.
 //
-// Hand-over without waiting: a wave that has written its record and seen the stores acknowledged adds one to
-// the arrival counter of its (sequence, KV head, row block).  The wave that finds n_parts - 1 there is the last:
-// it sets the counter back to zero for the next launch, reads all n_parts records and writes the output.  No
-// wave ever waits for another, so every wave exits whatever the order of execution.
+// Hand-over without waiting: a wave stores the record of its segment and is done; a second, small kernel, launched
+// behind the first on the same stream, reads the n_parts records of every sequence that was cut and writes its
+// output.  No wave ever waits for another, so every wave exits whatever the order of execution.
 //
 // Everything here is plain 32-bit integer arithmetic usable on host and device (the GPU has no fast 64-bit
 // divide); the host model in tests/host_model/ runs the same functions with one thread per wave.

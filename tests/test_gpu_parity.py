@@ -704,12 +704,6 @@ def test_watershed_decode_attention_and_scores_match_oracle(name, staged):
     P2, S2 = ra.ra_round_scores(eng.ctx, to_device(w.q(0), w.dtype), view, scale=w.scale)
     torch.cuda.synchronize()
     assert torch.equal(out, out2) and torch.equal(lse, lse2)
-    # the fp16-P mode is for the post-watershed layers: the watershed call, whose scores decide the selection, ignores it
-    ra.ra_set_prefill_precision(eng.ctx, ra.RA_PREFILL_P_F16)
-    out3, lse3, P3, S3 = ra.ra_watershed_attn_prefill(eng.ctx, q, view, ck, cv, scale=w.scale)
-    ra.ra_set_prefill_precision(eng.ctx, ra.RA_PREFILL_P_BF16X2)
-    torch.cuda.synchronize()
-    assert torch.equal(out, out3) and torch.equal(lse, lse3) and torch.equal(P, P3) and torch.equal(S, S3)
     out, P, S, P2, S2 = out.cpu().numpy(), P.cpu().numpy(), S.cpu().numpy(), P2.cpu().numpy(), S2.cpu().numpy()
     assert np.abs(P - P2).max() < SCORE_TOL and np.abs(S - S2).max() < SCORE_TOL
     for b in (range(w.B) if w.B <= 4 else (0, w.B - 1)):
