@@ -112,7 +112,9 @@ int main(int argc, char** argv) {
     std::mt19937 rng(seed);
     int bad = 0;
     for (int c = 0; c < cases; ++c) {
-        const int B = 1 + (int)(rng() % 24), inner = 1 + (int)(rng() % 4), n_waves = 1 + (int)(rng() % 48);
+        // mostly small batches; every tenth case a batch beyond one wavefront's lanes, up to the library's limit
+        const int B = c % 10 == 9 ? 65 + (int)(rng() % 960) : 1 + (int)(rng() % 24);
+        const int inner = 1 + (int)(rng() % 4), n_waves = 1 + (int)(rng() % 48);
         const int min_units = 1 + (int)(rng() % 4);
         int max_ranges = n_waves * (1 + (int)(rng() % 3)) / inner;  // also more ranges than waves: several items per wave
         if (max_ranges < 1) max_ranges = 1;

@@ -166,15 +166,26 @@ def test_random_many_sequences_decode(seed):
     """Batches past the size up to which the decode kernel plans a batch by itself (B * R_max > 1024): the planning
     kernel's tables, uneven round counts, short ragged rounds, random selections, per-sequence current lengths."""
     rng = np.random.default_rng(seed)
-    B = int(rng.integers(20, 33))
+    _many_sequences_case(rng, seed, B=int(rng.integers(20, 33)), max_R=60, max_len=90)
+
+
+@pytest.mark.parametrize("B", [65, 257, 1024])
+def test_batches_beyond_one_wavefront_of_sequences_decode(B):
+    """More sequences than a wavefront has lanes, up to the largest batch the library takes: the decode kernel then
+    finds a range's first sequence by bisection of the batch's tile prefix, and most ranges hold several sequences."""
+    rng = np.random.default_rng(9000 + B)
+    _many_sequences_case(rng, 9000 + B, B=B, max_R=4 if B > 300 else 17, max_len=70)
+
+
+def _many_sequences_case(rng, seed, B, max_R, max_len):
     G = int(rng.choice([1, 4, 8]))
-    lens = [[int(rng.choice(EDGE_LENS[:11])) if rng.random() < 0.4 else int(rng.integers(1, 90))
-             for _ in range(int(rng.integers(0, 61)))] for _ in range(B)]
-    lens[0] = [int(rng.integers(1, 90)) for _ in range(60)]          # R_max = 60 for certain
+    lens = [[int(rng.choice(EDGE_LENS[:11])) if rng.random() < 0.4 else int(rng.integers(1, max_len))
+             for _ in range(int(rng.integers(0, max_R + 1)))] for _ in range(B)]
+    lens[0] = [int(rng.integers(1, max_len)) for _ in range(max_R)]          # R_max = max_R for certain
     cur_cap = int(rng.choice([0, 24]))
     w = make_workload("cfg2", B=B, Hq=8 * G, Hkv=8, q_len=1, cur_len=cur_cap, lens=lens,
                       block_size=int(rng.choice([0, 16])), n_relevant=2)
-    assert w.B * w.R_max > 1024
+    assert w.B * w.R_max > 1024 or w.B > 64
     sels = [sorted(rng.choice(len(l), size=int(rng.integers(0, len(l) + 1)), replace=False).tolist()) if l else []
             for l in lens]
     cur_lens = [int(rng.integers(0, cur_cap + 1)) for _ in range(B)] if cur_cap else [0] * B
