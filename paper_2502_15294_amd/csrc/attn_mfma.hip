@@ -70,10 +70,8 @@ __device__ __forceinline__ int wave_exclusive_scan(int v, int lane, int& total) 
     return incl - v;
 }
 
-// A record: the accumulators of the 16 rows of a block, row-major [16][128], and (max, sum) per row.
-constexpr int kRecFloats = 16 * D128;
-
-// Merge of the records of every (sequence, KV head, row block) that was cut; grid (B * inner), block 256.
+// Merge of the records (a record: the accumulators of the 16 rows of a block, row-major [16][128], and (max, sum)
+// per row) of every (sequence, KV head, row block) that was cut; grid (B * inner), block 256.
 // Thread = (group, row, four channels): the rows of the block (at most eight per pass) times 32 channel quads fill
 // 32 .. 256 threads, and when they fill fewer the remaining threads form further groups that take every NG-th
 // record; the groups are then merged through LDS.  Four records per thread are in flight at a time.
