@@ -174,7 +174,7 @@ def test_batches_beyond_one_wavefront_of_sequences_decode(B):
     """More sequences than a wavefront has lanes, up to the largest batch the library takes: the decode kernel then
     finds a range's first sequence by bisection of the batch's tile prefix, and most ranges hold several sequences."""
     rng = np.random.default_rng(9000 + B)
-    _many_sequences_case(rng, 9000 + B, B=B, max_R=4 if B > 300 else 17, max_len=70)
+    _many_sequences_case(rng, 9000 + B, B=B, max_R={65: 17, 257: 6, 1024: 3}[B], max_len=70 if B < 1024 else 40)
 
 
 def _many_sequences_case(rng, seed, B, max_R, max_len):
