@@ -5,10 +5,11 @@
 //   * a work item is (piece of the sequence's key tiles, KV head, block of 128 query rows); its four
 //     waves own two 16-row tiles each and walk the key tiles in lockstep;
 //   * every 32-token tile (8 KB of keys, 8 KB of transposed values) is fetched from global memory ONCE per
-//     workgroup: each wave loads a quarter of the tile's MFMA operand fragments into registers while the
-//     previous tile is being consumed, writes them to one of two LDS buffers, and after one barrier all
-//     waves read the fragments they need straight in operand layout (fragment-major, 16 or 8 bytes per
-//     lane, conflict-free);
+//     workgroup: while the previous tile is being consumed each wave requests a quarter of the next one with
+//     loads that go from global memory straight into one of two LDS buffers (no registers, no LDS store
+//     instructions; only the values of the current round, which are gathered token by token, and the values of
+//     the fp16 mode, which are converted, pass through registers), and after one barrier all waves read the
+//     operand fragments they need, 16 bytes per lane, conflict-free;
 //   * with two buffers a single barrier per tile is enough: a wave can only write buffer X again after
 //     the barrier that every wave passes once it has finished reading X.
 // The launch is persistent with the balanced schedule of the decode kernel; pieces are merged by the same
@@ -64,9 +65,29 @@ constexpr int kPiecesPerWorkgroupP = 4;
 
 // A wave's quarter of a key/value tile on its way from global memory to LDS.
 struct Share {
-    uint4 k0, k1;          // chunk lane%16 of two key rows
-    uint2 v0, v1, v2, v3;  // V^T fragments (dt, half) = (2*wave, 0), (2*wave, 1), (2*wave + 1, 0), (2*wave + 1, 1)
+    uint4 v0, v1;  // V^T fragments dt = 2*wave, 2*wave + 1: tokens 8*(lane/16) .. +7 of channel dt*16 + lane%16
+    bool pending;  // the values are in these registers (current round, or fp16 mode) and still have to go to LDS
 };
+typedef const void __attribute__((address_space(1)))* gptr_t;
+typedef void __attribute__((address_space(3)))* lptr_t;
+// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane L's piece lands at
+// lds + 16 * L, `lds` being an LDS byte address that is the same in all lanes (it travels in M0).  Written as
+// instructions of their own because the compiler, given its builtin for them, makes every later LDS read wait for
+// the load to land (it cannot tell the two tile buffers apart), which exposes the whole memory latency once per
+// tile (measured: 180 against 157 microseconds); here the one wait sits where it belongs, before the barrier that
+// publishes the buffer (wait_for_direct_loads).  The compiler's own vector-memory counts do not see these loads,
+// which can only make one of its waits longer, never shorter: loads complete in order.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"  // M0 is named as clobbered; the compiler sets it anew before each of its own uses
+__device__ __forceinline__ void load_to_lds(const void* src, unsigned lds) {  // per-lane 64-bit address
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds) : "memory", "m0");
+}
+__device__ __forceinline__ void load_to_lds(const char* base, unsigned off, unsigned lds) {  // uniform base + lane offset
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(base), "s"(lds) : "memory", "m0");
+}
+// s_waitcnt vmcnt(0) (the other counters at their maxima: expcnt 7, lgkmcnt 15)
+__device__ __forceinline__ void wait_for_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+#pragma clang diagnostic pop
 
 template <bool PAGED, bool TILE_LSE, bool P_HALF>
 __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, int n_rowblocks) {
@@ -84,6 +105,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
     SlotTable tab;
     tab.carve(smem, cap);
     char* tiles = smem + ((SlotTable::bytes(cap) + 15) & ~(size_t)15);  // two tile buffers
+    const unsigned tiles_lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)tiles);
     int* ccum = reinterpret_cast<int*>(tiles + 2 * kTileBytes);        // [cap + 1] chunk prefix (score output only)
 
     const int inner = Hkv * n_rowblocks;
@@ -165,9 +187,23 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
         const char *tile_k = nullptr, *tile_v = nullptr;
         long long seg_tab = 0;                          // paged history: first block-table slot
         unsigned kstride = 256;                         // bytes from one token's keys to the next
-        const int row_a = 8 * wave + q4;                // this lane loads chunk n of tile rows row_a and row_a + 4
-        unsigned off_a = 0, off_b = 0;                  // their byte offsets from tile_k
-        const unsigned off_v = ((2 * wave * 16 + n) * 4 + q4) * 8;  // V^T fragment (dt = 2*wave) inside a 16-token block
+        // Direct loads: 16 bytes per lane, lane L's piece landing at (destination + 16 L).  Keys: the tile's LDS
+        // image is row-major, 256 bytes per row, row rho = 16 h + r being row r of the operand of half h, i.e. token
+        // 8 (r / 4) + 4 h + r % 4 of the tile (which makes a lane's eight probabilities eight consecutive tokens),
+        // and inside a row the 16-byte chunk x sits at position (x + r) mod 16: the rotation lets the operand reads
+        // (16 lanes = 16 rows, one chunk) touch every bank once.  This wave fills rows 8 wave .. + 7 with two loads
+        // of four whole rows each: 16 lanes per row, so the global side is as coalesced as a plain row copy.
+        int k_tok[2];       // token (inside the tile) of the row this lane helps to load, for the two loads
+        unsigned k_chunk[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int rho = 8 * wave + 4 * j + q4, h = rho >> 4, r = rho & 15;
+            k_tok[j] = 8 * (r >> 2) + 4 * h + (r & 3);
+            k_chunk[j] = (unsigned)((n - r) & 15) * 16u;
+        }
+        unsigned off_k[2] = {0, 0};                     // byte offsets from tile_k for a full tile
+        // V^T: tokens 8 * q4 .. + 7 of channel dt * 16 + n: block q4 / 2 of the tile, 16 contiguous bytes
+        const unsigned off_v = (unsigned)((2 * wave * 16 + n) * 32 + (q4 & 1) * 16);
         auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
         auto uni64 = [&](long long x) { return ((long long)uni((int)(x >> 32)) << 32) | (unsigned)uni((int)x); };
         auto open_seg = [&](int slot, int u) {  // ... and stand at its tile u - first
@@ -185,66 +221,78 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                 seg_k = kbase + ((size_t)uni64(tab.off_k[slot]) * Hkv + (size_t)g * seg_len) * 256;
                 seg_v = vbase + ((size_t)uni64(tab.off_v[slot]) * Hkv + (size_t)g * ((seg_len + 15) & ~15)) * 256;
             }
-            off_a = (unsigned)row_a * kstride + n * 16;
-            off_b = off_a + 4 * kstride;
+            off_k[0] = (unsigned)k_tok[0] * kstride + k_chunk[0];
+            off_k[1] = (unsigned)k_tok[1] * kstride + k_chunk[1];
             const int uin = u - seg_first;
             rows_left = seg_len - uin * kTileP;
             tile_k = seg_k + (size_t)uin * kTileP * kstride;
             tile_v = seg_v + (size_t)uin * 8192;
         };
-        // This wave's quarter of the next tile: key rows 8*wave .. +7 (chunk n of two rows per lane) and the
-        // V^T fragments (dt, half) = (2*wave, 0), (2*wave, 1), (2*wave + 1, 0), (2*wave + 1, 1); afterwards the
-        // loader stands at the tile that follows.  Rows and blocks past the segment's end re-read its last ones
-        // (their scores are masked).
-        auto load_share = [&]() -> Share {
+        // This wave's quarter of the next tile goes to `buf`: two K fragments and two V^T fragments.  Keys and the
+        // values of history rounds travel from global memory straight into LDS; the values of the current round
+        // (token-major: gathered with 2-byte loads) and, in the fp16 mode, all values (converted on the way) pass
+        // through registers and are written by store_share at the top of the next iteration.  Rows and blocks past
+        // the segment's end re-read its last ones (their scores are masked).  Afterwards the loader stands at the
+        // tile that follows.
+        auto load_tile = [&](unsigned buf_lds) -> Share {
             Share sh;
+            sh.pending = false;
+            sh.v0 = sh.v1 = make_uint4(0, 0, 0, 0);
             const int tok0 = seg_len - rows_left;
+            const unsigned kd = buf_lds + 8 * wave * 256, vd = buf_lds + 8192 + 2 * wave * 1024;
             if (!seg_cur && PAGED) {
                 const int blk0 = tok0 >> 4, blk1 = min(blk0 + 1, (seg_len - 1) >> 4);
                 const long long last = vw.max_blocks - 1;
                 const long long s0 = min(max(seg_tab + blk0, 0ll), last), s1 = min(max(seg_tab + blk1, 0ll), last);
                 const int p0 = max(uni(vw.block_table[(size_t)b * vw.max_blocks + s0]), 0);
                 const int p1 = max(uni(vw.block_table[(size_t)b * vw.max_blocks + s1]), 0);
-                const bool upper = wave >> 1;
-                const char* kb = kbase + ((size_t)(upper ? p1 : p0) * Hkv + g) * 4096;
-                const int last_row = seg_len - 1 - (upper ? blk1 : blk0) * 16;
-                const int r0 = min(8 * (wave & 1) + q4, last_row), r1 = min(8 * (wave & 1) + 4 + q4, last_row);
-                sh.k0 = *reinterpret_cast<const uint4*>(kb + r0 * 256 + n * 16);
-                sh.k1 = *reinterpret_cast<const uint4*>(kb + r1 * 256 + n * 16);
-                const char* vb0 = vbase + ((size_t)p0 * Hkv + g) * 4096;
-                const char* vb1 = vbase + ((size_t)p1 * Hkv + g) * 4096;
-                sh.v0 = *reinterpret_cast<const uint2*>(vb0 + off_v);
-                sh.v1 = *reinterpret_cast<const uint2*>(vb1 + off_v);
-                sh.v2 = *reinterpret_cast<const uint2*>(vb0 + off_v + 512);
-                sh.v3 = *reinterpret_cast<const uint2*>(vb1 + off_v + 512);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const bool upper = k_tok[j] >> 4;
+                    const int last_row = seg_len - 1 - (upper ? blk1 : blk0) * 16;
+                    const char* kb = kbase + ((size_t)(upper ? p1 : p0) * Hkv + g) * 4096;
+                    load_to_lds(kb + min(k_tok[j] & 15, last_row) * 256 + k_chunk[j], kd + j * 1024);
+                }
+                const char* vb = vbase + ((size_t)((q4 >> 1) ? p1 : p0) * Hkv + g) * 4096;
+                if constexpr (P_HALF) {
+                    sh.v0 = *reinterpret_cast<const uint4*>(vb + off_v);
+                    sh.v1 = *reinterpret_cast<const uint4*>(vb + off_v + 512);
+                    sh.pending = true;
+                } else {
+                    load_to_lds(vb + off_v, vd);
+                    load_to_lds(vb + off_v + 512, vd + 1024);
+                }
             } else {
                 if (rows_left >= kTileP) {
-                    sh.k0 = *reinterpret_cast<const uint4*>(tile_k + off_a);
-                    sh.k1 = *reinterpret_cast<const uint4*>(tile_k + off_b);
+                    load_to_lds(tile_k, off_k[0], kd);
+                    load_to_lds(tile_k, off_k[1], kd + 1024);
                 } else {
-                    sh.k0 = *reinterpret_cast<const uint4*>(tile_k + (unsigned)min(row_a, rows_left - 1) * kstride + n * 16);
-                    sh.k1 = *reinterpret_cast<const uint4*>(tile_k + (unsigned)min(row_a + 4, rows_left - 1) * kstride + n * 16);
+                    load_to_lds(tile_k, (unsigned)min(k_tok[0], rows_left - 1) * kstride + k_chunk[0], kd);
+                    load_to_lds(tile_k, (unsigned)min(k_tok[1], rows_left - 1) * kstride + k_chunk[1], kd + 1024);
                 }
-                if (seg_cur) {  // token-major values: gather 4 tokens of one channel with 2-byte loads
-                    auto gather = [&](int dt, int h) {
-                        uint32_t e[4];
+                if (seg_cur) {  // token-major values: gather 8 tokens of one channel with 2-byte loads
+                    auto gather = [&](int dt) {
+                        uint32_t e[8];
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            const int tok = min(tok0 + h * 16 + q4 * 4 + t, seg_len - 1);
+                        for (int t = 0; t < 8; ++t) {
+                            const int tok = min(tok0 + q4 * 8 + t, seg_len - 1);
                             e[t] = *reinterpret_cast<const unsigned short*>(seg_v + (size_t)tok * kstride + (dt * 16 + n) * 2);
                         }
-                        return make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
+                        return make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
                     };
-                    sh.v0 = gather(2 * wave, 0);
-                    sh.v1 = gather(2 * wave, 1);
-                    sh.v2 = gather(2 * wave + 1, 0);
-                    sh.v3 = gather(2 * wave + 1, 1);
+                    sh.v0 = gather(2 * wave);
+                    sh.v1 = gather(2 * wave + 1);
+                    sh.pending = true;
                 } else {
-                    const unsigned second = rows_left > 16 ? 4096u : 0u;  // the tile's second 16-token block, if any
-                    sh.v0 = *reinterpret_cast<const uint2*>(tile_v + off_v);
-                    sh.v1 = *reinterpret_cast<const uint2*>(tile_v + (off_v + second));
-                    sh.v2 = *reinterpret_cast<const uint2*>(tile_v + (off_v + 512));
-                    sh.v3 = *reinterpret_cast<const uint2*>(tile_v + (off_v + second + 512));
+                    const unsigned second = (q4 >> 1) && rows_left > 16 ? 4096u : 0u;  // the tile's second 16-token block, if any
+                    if constexpr (P_HALF) {
+                        sh.v0 = *reinterpret_cast<const uint4*>(tile_v + (off_v + second));
+                        sh.v1 = *reinterpret_cast<const uint4*>(tile_v + (off_v + second + 512));
+                        sh.pending = true;
+                    } else {
+                        load_to_lds(tile_v, off_v + second, vd);
+                        load_to_lds(tile_v, off_v + second + 512, vd + 1024);
+                    }
                 }
             }
             rows_left -= kTileP;
@@ -252,30 +300,29 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             tile_v += 8192;
             return sh;
         };
-        // LDS tile: K operand fragment (half, kk) holds its 64 lanes' 16-byte pieces at
-        //   ((half*4 + kk)*64 + q4*16 + ((n + 4*kk + q4) % 16)) * 16,
-        // a rotation inside each 16-piece group that makes both the row-wise writes below and the operand reads
-        // (16 lanes = 16 rows of one channel group) touch every bank once.  V fragments are stored as loaded.
-        auto store_share = [&](char* buf, const Share& sh) {
-            uint4* kd = reinterpret_cast<uint4*>(buf) + ((wave >> 1) * 4 + (n >> 2)) * 64 + (n & 3) * 16;
-            const int row = 8 * (wave & 1) + q4;  // lane holds chunk n (kk = n/4, piece n%4) of rows `row`, `row + 4`
-            kd[(row + n) & 15] = sh.k0;
-            kd[(row + 4 + n) & 15] = sh.k1;
-            uint2* vd = reinterpret_cast<uint2*>(buf + 8192) + 4 * wave * 64 + lane;
-            vd[0] = P_HALF ? bf16x4_to_half(sh.v0) : sh.v0;
-            vd[64] = P_HALF ? bf16x4_to_half(sh.v1) : sh.v1;
-            vd[128] = P_HALF ? bf16x4_to_half(sh.v2) : sh.v2;
-            vd[192] = P_HALF ? bf16x4_to_half(sh.v3) : sh.v3;
+        // V^T fragment dt holds lane L's 16 bytes at (8192 + dt*1024 + 16*L).
+        auto store_share = [&](char* buf, const Share& sh) {  // the values that came through registers
+            if (!sh.pending) return;
+            uint4* vd = reinterpret_cast<uint4*>(buf + 8192) + 2 * wave * 64 + lane;
+            if constexpr (P_HALF) {
+                const uint2 a0 = bf16x4_to_half(make_uint2(sh.v0.x, sh.v0.y)), a1 = bf16x4_to_half(make_uint2(sh.v0.z, sh.v0.w));
+                const uint2 b0 = bf16x4_to_half(make_uint2(sh.v1.x, sh.v1.y)), b1 = bf16x4_to_half(make_uint2(sh.v1.z, sh.v1.w));
+                vd[0] = make_uint4(a0.x, a0.y, a1.x, a1.y);
+                vd[64] = make_uint4(b0.x, b0.y, b1.x, b1.y);
+            } else {
+                vd[0] = sh.v0;
+                vd[64] = sh.v1;
+            }
         };
         auto consume = [&](const char* buf, int tok0, int len, bool is_cur) {
             const bool full = !is_cur && (len - tok0 >= kTileP);
             const uint4* kb = reinterpret_cast<const uint4*>(buf);
-            const uint2* vb = reinterpret_cast<const uint2*>(buf + 8192);
+            const uint4* vb = reinterpret_cast<const uint4*>(buf + 8192);
             uint4 kf[2][4];
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) kf[h][kk] = kb[(h * 4 + kk) * 64 + q4 * 16 + ((n + 4 * kk + q4) & 15)];
+                for (int kk = 0; kk < 4; ++kk) kf[h][kk] = kb[(h * 16 + n) * 16 + ((kk * 4 + q4 + n) & 15)];
             floatx4_t sc[kNTP][2];
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)  // four independent chains interleaved: no instruction waits for the one before
@@ -295,7 +342,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                     for (int h = 0; h < 2; ++h)
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            if (tok0 + h * 16 + q4 * 4 + i >= lim) sc[nt][h][i] = -__builtin_inff();
+                            if (tok0 + q4 * 8 + h * 4 + i >= lim) sc[nt][h][i] = -__builtin_inff();
                 }
             }
             // The reference logit m of a row is only raised when some logit exceeds it by more than `slack`
@@ -323,10 +370,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             }
             uint4 vf[8];  // V^T operand fragments of the tile, shared by both row tiles
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                const uint2 v0 = vb[(dt * 2 + 0) * 64 + lane], v1 = vb[(dt * 2 + 1) * 64 + lane];
-                vf[dt] = make_uint4(v0.x, v0.y, v1.x, v1.y);
-            }
+            for (int dt = 0; dt < 8; ++dt) vf[dt] = vb[dt * 64 + lane];
             auto probabilities = [&](int nt, uint4& phi, uint4& plo) {  // P (hi + lo, or fp16) of row tile nt, and its row sums
                 const float mc = m[nt] * a.c - (P_HALF ? (float)kHalfScaleLog2 : 0.f);
                 float p[8];
@@ -384,11 +428,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
             int slot = find_slot(tab.cum, n_slots, u_lo);
             open_seg(slot, u_lo);
             int c_tok0 = seg_len - rows_left;
-            Share sh = load_share();
+            Share sh = load_tile(tiles_lds);
             int bufsel = 0;
             for (int u = u_lo; u < u_hi; ++u) {
                 char* buf = tiles + bufsel * kTileBytes;
                 store_share(buf, sh);
+                wait_for_direct_loads();  // this wave's quarter of the tile has landed in LDS
                 const int len = seg_len, tok0 = c_tok0;  // of the tile just stored
                 const bool is_cur = seg_cur;
                 const int t_slot = slot, t_first = seg_first, t_end = seg_end;
@@ -399,7 +444,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, i
                         open_seg(slot, u + 1);
                     }
                     c_tok0 = seg_len - rows_left;
-                    sh = load_share();
+                    sh = load_tile(tiles_lds + (bufsel ^ 1) * kTileBytes);
                 }
                 consume(buf, tok0, len, is_cur);
                 if constexpr (TILE_LSE) {
