@@ -68,26 +68,6 @@ struct Share {
     uint4 v0, v1;  // V^T fragments dt = 2*wave, 2*wave + 1: tokens 8*(lane/16) .. +7 of channel dt*16 + lane%16
     bool pending;  // the values are in these registers (current round, or fp16 mode) and still have to go to LDS
 };
-typedef const void __attribute__((address_space(1)))* gptr_t;
-typedef void __attribute__((address_space(3)))* lptr_t;
-// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane L's piece lands at
-// lds + 16 * L, `lds` being an LDS byte address that is the same in all lanes (it travels in M0).  Written as
-// instructions of their own because the compiler, given its builtin for them, makes every later LDS read wait for
-// the load to land (it cannot tell the two tile buffers apart), which exposes the whole memory latency once per
-// tile (measured: 180 against 157 microseconds); here the one wait sits where it belongs, before the barrier that
-// publishes the buffer (wait_for_direct_loads).  The compiler's own vector-memory counts do not see these loads,
-// which can only make one of its waits longer, never shorter: loads complete in order.
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"  // M0 is named as clobbered; the compiler sets it anew before each of its own uses
-__device__ __forceinline__ void load_to_lds(const void* src, unsigned lds) {  // per-lane 64-bit address
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds) : "memory", "m0");
-}
-__device__ __forceinline__ void load_to_lds(const char* base, unsigned off, unsigned lds) {  // uniform base + lane offset
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(base), "s"(lds) : "memory", "m0");
-}
-// s_waitcnt vmcnt(0) (the other counters at their maxima: expcnt 7, lgkmcnt 15)
-__device__ __forceinline__ void wait_for_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }
-#pragma clang diagnostic pop
 
 template <bool PAGED, bool TILE_LSE, bool P_HALF>
 __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a, int n_rowblocks) {

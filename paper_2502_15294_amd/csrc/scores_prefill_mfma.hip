@@ -7,10 +7,10 @@
 //
 //   * a work item is (piece of the sequence's chunks, KV head, block of 256 query rows): four waves with
 //     four 16-row tiles each walk the key tiles of the piece's chunks in lockstep;
-//   * every 32-token key tile (8 KB) is fetched from global memory once per workgroup with whole-row
-//     coalesced loads, one tile ahead, written to one of two LDS buffers in matrix-operand order (rotated
-//     inside each 16-piece group so that neither the row-wise writes nor the operand reads conflict), and
-//     read from there by all four waves; one barrier per tile;
+//   * every 32-token key tile (8 KB) is fetched from global memory once per workgroup, one tile ahead, with
+//     whole-row coalesced loads that go straight into one of two LDS buffers (no registers, no LDS stores): the
+//     tile's image there is row-major with the 16-byte chunks of row r rotated by r, so that the operand reads
+//     (16 lanes = 16 rows, one chunk) touch every bank once; all four waves read it; one barrier per tile;
 //   * the reference logit of a lane is only raised when one of its logits exceeds it by 2^16 after scaling,
 //     so the common tile costs one multiply-add, one exponential and one add per logit;
 //   * persistent launch with the batch-wide balanced schedule used by the attention kernels.  The schedule
@@ -91,6 +91,7 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
     SlotTable tab;
     tab.carve(smem, cap);
     char* tiles = smem + ((SlotTable::bytes(cap) + 15) & ~(size_t)15);  // two key-tile buffers
+    const unsigned tiles_lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)tiles);
 
     const int inner = Hkv * n_rowblocks;
     const long long slots = ((long long)gridDim.x * kPiecesPerWorkgroupS + inner - 1) / inner;
@@ -153,8 +154,12 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
         const char *seg_k = nullptr, *tile_k = nullptr;  // contiguous history / current round
         long long seg_tab = 0;                           // paged history: first block-table slot
         unsigned kstride = 256;                          // bytes from one token's keys to the next
-        const int row_a = 8 * wave + q4;                 // this lane loads chunk n of tile rows row_a and row_a + 4
-        unsigned off_a = 0, off_b = 0;                   // their byte offsets from tile_k
+        // This wave fills rows 8 wave .. + 7 of the tile's LDS image (row = token of the tile, 256 bytes) with two
+        // loads of four whole rows each, 16 lanes per row; lane L's 16 bytes land at position L % 16 of its row,
+        // where chunk (L % 16 - row) mod 16 belongs.
+        const int row_a = 8 * wave + q4;                 // this lane helps to load tile rows row_a and row_a + 4
+        const unsigned chunk_a = (unsigned)((n - row_a) & 15) * 16u, chunk_b = (unsigned)((n - row_a - 4) & 15) * 16u;
+        unsigned off_a = 0, off_b = 0;                   // byte offsets from tile_k for a full tile
         auto open_seg = [&](int slot) {
             seg_len = uni(tab.len[slot]);
             seg_first = uni(tab.cum[slot]);
@@ -167,17 +172,19 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
                 seg_tab = uni64(tab.off_k[slot]);
             else
                 seg_k = kbase + ((size_t)uni64(tab.off_k[slot]) * Hkv + (size_t)g * seg_len) * 256;
-            off_a = (unsigned)row_a * kstride + n * 16;
-            off_b = off_a + 4 * kstride;
+            off_a = (unsigned)row_a * kstride + chunk_a;
+            off_b = (unsigned)(row_a + 4) * kstride + chunk_b;
         };
         auto open_chunk = [&](int u) {  // of the open segment
             const int tok0 = (u - seg_first) * kChunkTokens;
             rows_left = seg_len - tok0;
             tile_k = seg_k + (size_t)tok0 * kstride;
         };
-        // This wave's quarter (rows 8*wave .. +7) of the next key tile; afterwards the loader stands at the tile
-        // that follows.  Rows past the segment's end re-read its last row (their scores are masked).
-        auto load_share = [&](uint4& k0, uint4& k1) {
+        // This wave's quarter (rows 8*wave .. +7) of the next key tile goes to the buffer at LDS address `buf_lds`;
+        // afterwards the loader stands at the tile that follows.  Rows past the segment's end re-read its last row
+        // (their scores are masked).
+        auto load_tile = [&](unsigned buf_lds) {
+            const unsigned kd = buf_lds + 8 * wave * 256;
             if (!seg_cur && PAGED) {
                 const int tok0 = seg_len - rows_left;
                 const int blk = min((tok0 >> 4) + (wave >> 1), (seg_len - 1) >> 4);
@@ -186,25 +193,17 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
                 const char* kb = kbase + ((size_t)pb * Hkv + g) * 4096;
                 const int last_row = seg_len - 1 - blk * 16;
                 const int r0 = min(8 * (wave & 1) + q4, last_row), r1 = min(8 * (wave & 1) + 4 + q4, last_row);
-                k0 = *reinterpret_cast<const uint4*>(kb + r0 * 256 + n * 16);
-                k1 = *reinterpret_cast<const uint4*>(kb + r1 * 256 + n * 16);
+                load_to_lds(kb, (unsigned)r0 * 256u + chunk_a, kd);
+                load_to_lds(kb, (unsigned)r1 * 256u + chunk_b, kd + 1024);
             } else if (rows_left >= kTileSP) {
-                k0 = *reinterpret_cast<const uint4*>(tile_k + off_a);
-                k1 = *reinterpret_cast<const uint4*>(tile_k + off_b);
+                load_to_lds(tile_k, off_a, kd);
+                load_to_lds(tile_k, off_b, kd + 1024);
             } else {
-                k0 = *reinterpret_cast<const uint4*>(tile_k + (unsigned)min(row_a, rows_left - 1) * kstride + n * 16);
-                k1 = *reinterpret_cast<const uint4*>(tile_k + (unsigned)min(row_a + 4, rows_left - 1) * kstride + n * 16);
+                load_to_lds(tile_k, (unsigned)min(row_a, rows_left - 1) * kstride + chunk_a, kd);
+                load_to_lds(tile_k, (unsigned)min(row_a + 4, rows_left - 1) * kstride + chunk_b, kd + 1024);
             }
             rows_left -= kTileSP;
             tile_k += (size_t)kTileSP * kstride;
-        };
-        // K operand fragment (half, kk) holds its 64 lanes' 16-byte pieces at
-        //   ((half*4 + kk)*64 + q4*16 + ((n + 4*kk + q4) % 16)) * 16.
-        auto store_share = [&](char* buf, const uint4& k0, const uint4& k1) {
-            uint4* kd = reinterpret_cast<uint4*>(buf) + ((wave >> 1) * 4 + (n >> 2)) * 64 + (n & 3) * 16;
-            const int row = 8 * (wave & 1) + q4;  // lane holds chunk n (kk = n/4, piece n%4) of rows `row`, `row + 4`
-            kd[(row + n) & 15] = k0;
-            kd[(row + 4 + n) & 15] = k1;
         };
         auto consume = [&](const char* buf, int tok0, int len, bool is_cur) {
             const bool full = !is_cur && (len - tok0 >= kTileSP);
@@ -214,7 +213,7 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) kf[h][kk] = kb[(h * 4 + kk) * 64 + q4 * 16 + ((n + 4 * kk + q4) & 15)];
+                for (int kk = 0; kk < 4; ++kk) kf[h][kk] = kb[(h * 16 + n) * 16 + ((kk * 4 + q4 + n) & 15)];
             asm volatile("" ::: "memory");  // all eight fragment reads are in flight before the first product is issued
 #pragma unroll
             for (int h = 0; h < 2; ++h)
@@ -284,13 +283,12 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
         open_seg(slot);
         open_chunk(u_lo);
         int lu = u_lo, lj = 0;  // the tile the loader fetches next: tile lj of chunk lu
-        uint4 k0, k1;
         int c_tok0 = seg_len - rows_left;
-        load_share(k0, k1);
+        load_tile(tiles_lds);
         int bufsel = 0;
         while (true) {
             char* buf = tiles + bufsel * kKTileBytes;
-            store_share(buf, k0, k1);
+            wait_for_direct_loads();  // this wave's quarter of the tile has landed in LDS
             // the tile just stored, as the consumer needs it; it ends its chunk if the chunk or the segment ends
             const int c_len = seg_len, c_u = lu, c_t = c_tok0;
             const bool c_cur = seg_cur, c_last = lj + 1 == kTilesPerChunk || rows_left <= 0;
@@ -310,7 +308,7 @@ __global__ __launch_bounds__(256, kWorkgroupsPerCuS) void scores_prefill_mfma_ke
             }
             if (more) {
                 c_tok0 = seg_len - rows_left;
-                load_share(k0, k1);
+                load_tile(tiles_lds + (bufsel ^ 1) * kKTileBytes);
             }
             consume(buf, c_t, c_len, c_cur);
             if (c_last) finish_chunk(c_u);
