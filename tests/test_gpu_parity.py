@@ -410,6 +410,9 @@ PREFILL_CASES = {
                                         lens=[[300, 17, 16, 1, 999, 50], [31, 32, 33, 0, 64, 5]]), [[0, 3, 4], [0, 1, 2, 3, 5]]),
     "q24_many_short_rounds": (dict(B=2, R=300, q_len=24, cur_len=24, length=("uniform", 1, 40)),
                               [list(range(0, 300, 3)), list(range(5, 300, 7))]),
+    # paged cache, eight heads per KV head, four row blocks, several pieces per sequence
+    "q64_paged_g8_long_rounds": (dict(B=2, R=12, q_len=64, cur_len=70, Hq=64, block_size=16, length=("uniform", 300, 1000)),
+                                 [[0, 2, 3, 5, 7, 8, 10, 11], [1, 4, 6, 9]]),
 }
 
 
