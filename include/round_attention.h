@@ -292,7 +292,8 @@ int ra_round_sparse_attn_prefill(ra_ctx* ctx, void* stream, const void* q, int q
  *   RA_PREFILL_P_BF16X2  (default) P as the sum of two bf16 numbers, two passes over V: about 16 bits of P,
  *                        output error about 2e-5 of a row's largest magnitude
  *   RA_PREFILL_P_F16     P rounded to fp16, V converted to fp16 on chip, one pass: a third fewer matrix-core
- *                        instructions; output error about 1e-4 (the contract of every attention call is 2e-3).
+ *                        instructions; output error about 4e-4 of a row's largest magnitude, 20 times the
+ *                        default's (the contract of every attention call is 2e-3).
  *                        Values beyond fp16's range (|v| > 65504) saturate: use the default for such caches.
  */
 typedef enum ra_prefill_precision { RA_PREFILL_P_BF16X2 = 0, RA_PREFILL_P_F16 = 1 } ra_prefill_precision;

@@ -28,7 +28,7 @@
 // is rounded to fp16 (nearest even) and the SAME rounded values are summed for the normaliser (dot2 against ones,
 // fp32 accumulate), so the rounding acts as a perturbation of the weights of at most 2^-12 each, of either sign,
 // that averages out over the keys.  One third fewer matrix-core instructions per tile; the output error grows
-// from about 2e-5 to about 1e-4 of the row's largest magnitude (contract: 2e-3).
+// from about 2e-5 to about 4e-4 of the row's largest magnitude (contract: 2e-3).
 #include "attn_common.hpp"
 #include "mfma_util.hpp"
 #include "stream_kv.hpp"
