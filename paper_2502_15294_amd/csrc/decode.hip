@@ -3,10 +3,11 @@
 // current round.  HBM-bandwidth bound: K and V of every selected token are read exactly once and
 // serve all Hq/Hkv query heads of their KV head.
 //
-// This file holds the entry point, the merge of split pieces, and the generic vector-ALU kernel used
-// for fp32 caches and head_dim 64; bf16 with head_dim 128 goes to the matrix-core kernel.
+// This file holds the entry points, the planning kernel, and the generic vector-ALU kernel with its merge kernel,
+// used for fp32 caches and head_dim 64; bf16 with head_dim 128 goes to the matrix-core kernel (attn_mfma.hip),
+// which has a schedule of its own (one wavefront per equal range of the batch's key tiles).
 //
-// Work decomposition (both kernels): grid (S, Hkv, B).  A workgroup (4 wavefronts) owns KV head g of
+// Work decomposition of the generic kernel: grid (S, Hkv, B).  A workgroup (4 wavefronts) owns KV head g of
 // sequence b and the s-th of S_eff equal shares of that sequence's work units, S_eff <= S being chosen
 // on the device from the number of selected tokens.  Its waves take units round-robin, keep an
 // online-softmax state in registers and are merged through LDS into one piece (max, sum, d
