@@ -18,7 +18,12 @@ __device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c) {
 }
 // Largest of the eight logits a lane holds of one 16-row x 32-token score tile.
 __device__ __forceinline__ float max8(floatx4_t a, floatx4_t b) {
-    return vmax(vmax3(a[0], a[1], a[2]), vmax3(vmax3(a[3], b[0], b[1]), b[2], b[3]));
+    float m = vmax(a[0], a[1]);  // a chain: the compiler pairs its links into three-operand maxima
+#pragma unroll
+    for (int i = 2; i < 4; ++i) m = vmax(m, a[i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) m = vmax(m, b[i]);
+    return m;
 }
 // Two floats -> packed bf16 pair by truncation (low half = a, high half = b).
 __device__ __forceinline__ uint32_t pack_trunc(float a, float b) { return (as_u32(b) & 0xffff0000u) | (as_u32(a) >> 16); }

@@ -31,17 +31,14 @@ __device__ __forceinline__ float row16_sum(float v) {
     v += dpp_mov<0x140>(v);  // row_mirror
     return v;
 }
-// Maxima without the NaN-quieting copies the compiler puts in front of fmaxf (three instructions per call).
-__device__ __forceinline__ float vmax(float a, float b) {
-    float d;
-    asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
-    return d;
-}
-__device__ __forceinline__ float vmax3(float a, float b, float c) {
-    float d;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-    return d;
-}
+// Maxima are ordinary float code on purpose.  The compiler inserts the wait states that the hardware leaves to
+// software (a vector instruction that reads the result of a matrix-core product still in flight, a DPP or lane-swap
+// instruction that reads a register just written), and it does so only for instructions it can see: an asm
+// statement with v_max_f32 inside gets none.  Such a statement here once read the previous tile's logits (on a
+// wave's first tile: whatever the registers held before) whenever the scheduler happened to put it within a few
+// instructions of the products: a reference logit that was still valid but differed from launch to launch, and with
+// it the last bits of the outputs.  The price is a few copies that quiet signalling NaNs in front of some maxima.
+__device__ __forceinline__ float vmax(float a, float b) { return __builtin_fmaxf(a, b); }
 // Reductions over the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48); every lane ends with the
 // result.  v_permlane16_swap / v_permlane32_swap applied to two copies of a value hand each lane the values of
 // both rows of a pair (of both halves of the wave), so the exchange stays in the vector ALU.
@@ -206,13 +203,19 @@ typedef void __attribute__((address_space(3)))* lptr_t;
 // tile (measured: 180 against 157 microseconds); here the one wait sits where it belongs, before the barrier that
 // publishes the buffer (wait_for_direct_loads).  The compiler's own vector-memory counts do not see these loads,
 // which can only make one of its waits longer, never shorter: loads complete in order.
+// An asm statement is opaque to the compiler's hazard handling, so the wait states the hardware leaves to software
+// are written out here: a scalar write of M0 needs one before an instruction that takes its LDS address from M0
+// (the compiler puts the same s_nop behind its own M0 writes), and an SGPR written by a vector instruction
+// (v_readfirstlane, or v_readlane when the compiler reloads a spilled SGPR) needs five before a vector-memory
+// instruction reads it as its base address: the form with a uniform base therefore waits s_nop 3, which with the
+// M0 write makes five whatever came right before the statement.
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"  // M0 is named as clobbered; the compiler sets it anew before each of its own uses
 __device__ __forceinline__ void load_to_lds(const void* src, unsigned lds) {  // per-lane 64-bit address
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds) : "memory", "m0");
 }
 __device__ __forceinline__ void load_to_lds(const char* base, unsigned off, unsigned lds) {  // uniform base + lane offset
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(base), "s"(lds) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 3\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(base), "s"(lds) : "memory", "m0");
 }
 // s_waitcnt vmcnt(0) (the other counters at their maxima: expcnt 7, lgkmcnt 15)
 __device__ __forceinline__ void wait_for_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }
