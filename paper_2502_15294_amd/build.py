@@ -69,5 +69,60 @@ def build_example() -> str:
     return EXAMPLE
 
 
+# ---- the same sources under other instruction schedules ------------------------------------------------------
+# Results must not depend on how the compiler orders instructions.  A wait state the hardware leaves to software
+# and the source forgets (an instruction hidden from the compiler, a missing barrier) shows up as outputs that differ
+# in their last bits between builds that differ only in the scheduling strategy, so the GPU tests compare such
+# builds with the product build bit by bit (tests/test_gpu_schedule_independence.py).  They are optional: built by
+# `python -m paper_2502_15294_amd.build --alt-schedules`, skipped by the test when absent or stale.
+ALT_STRATEGIES = ("iterative-ilp", "iterative-minreg")
+ALT_DIR = os.path.join(HERE, "_alt")
+
+
+def sources_digest() -> str:
+    """sha1 over the kernel sources and the boundary header: names a build's inputs."""
+    import hashlib
+    h = hashlib.sha1()
+    for path in sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC)) + [os.path.join(ROOT, "include", "round_attention.h")]:
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()
+
+
+def alt_library(strategy: str) -> str:
+    return os.path.join(ALT_DIR, f"libround_attention.{strategy}.so")
+
+
+def build_alt_schedules(jobs: int = 6) -> list:
+    """The whole library once per strategy in ALT_STRATEGIES, each with a stamp file holding sources_digest()."""
+    libs = []
+    for strategy in ALT_STRATEGIES:
+        obj_dir = os.path.join(OBJ, "alt_" + strategy)
+        os.makedirs(obj_dir, exist_ok=True)
+        os.makedirs(ALT_DIR, exist_ok=True)
+
+        def compile_one(src, obj_dir=obj_dir, strategy=strategy):
+            obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
+            cmd = [_hipcc(), *FLAGS, "-mllvm", f"-amdgpu-sched-strategy={strategy}", "-c", os.path.join(CSRC, src), "-o", obj]
+            r = subprocess.run(cmd, capture_output=True, text=True)
+            if r.returncode != 0:
+                raise RuntimeError(f"hipcc ({strategy}) failed on {src}:\n{r.stderr[-4000:]}")
+            return obj
+
+        with ThreadPoolExecutor(max_workers=jobs) as ex:
+            objs = list(ex.map(compile_one, SOURCES))
+        lib = alt_library(strategy)
+        r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"link ({strategy}) failed:\n{r.stderr[-4000:]}")
+        with open(lib + ".stamp", "w") as f:
+            f.write(sources_digest())
+        libs.append(lib)
+    return libs
+
+
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv or True))
+    print(build(force=True))
+    if "--alt-schedules" in sys.argv:
+        for lib in build_alt_schedules():
+            print(lib)
