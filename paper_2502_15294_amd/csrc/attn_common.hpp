@@ -6,6 +6,16 @@
 
 namespace ra {
 
+// Share of the batch's key tiles that the first half of the decode kernel's ranges gets beyond one half, in
+// 1/1000 (RangeCut in range_schedule.hpp).  The launch puts two workgroups on every compute unit and the hardware
+// dispatches the first half of the grid first; for the whole kernel the waves that came first on a unit are served
+// ahead of the others (oldest first), so with equal ranges they end early and the chip runs half empty at the end.
+// Measured on the large paged workload at 13.9 % kept, kernel time against the skew: 0: 217.0-217.9 us, 20: 215.7,
+// 40: 215.4-216.0, 60: 213.2, 80: 211.4, 90: 212.4-213.0, 100: 212.4, 140: 216.6, 180: 217.7, 220: 220.6 (59.7 %
+// kept: 857 -> 841-848 us at 60-100; 6 % kept: ranges too short to be skewed; long-context workload: 460-461 us with
+// and without).  Should another part dispatch in another order, the cost is bounded by the skew itself.
+constexpr int kRangeSkew = 90;
+
 struct AttnArgs {
     DevView view;
     const void* q;             // [B][q_len][Hq][D]
@@ -40,6 +50,7 @@ struct AttnArgs {
     float* rec_ml;    // [records][inner][16][2]   running max of the raw logits, sum of 2^((logit - max) * c)
     int* seq_rec;     // [B][2] first record and number of records of every sequence (written by the kernel)
     int max_ranges;   // most ranges the batch's key tiles are cut into
+    int range_skew;   // in 1/1000: how much more than half of the tiles the first half of the ranges gets (see RangeCut)
     int p_half;       // many-row kernel: probabilities as one fp16 operand instead of two bf16 (ra_set_prefill_precision)
 };
 

@@ -289,7 +289,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
         return;
     }
 
-    const RangeCut cut = range_cut((unsigned)total, a.min_units, a.max_ranges);
+    const RangeCut cut = range_cut((unsigned)total, a.min_units, a.max_ranges, a.range_skew);
     const int n_items = (int)cut.n_ranges * inner;
     if (blockIdx.x == 0)  // for the merge kernel: first record and number of records of every sequence
         for (int b = tid; b < B; b += 256) {

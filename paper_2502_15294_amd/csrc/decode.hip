@@ -461,6 +461,7 @@ static int decode_impl(ra_ctx* ctx, const Workspace* scratch, void* stream, cons
     a.rec_ml = mfma ? reinterpret_cast<float*>(ws.base + mw.ml_off) : nullptr;
     a.seq_rec = reinterpret_cast<int*>(ws.base + kWsSeqRecOff);
     a.max_ranges = shape.max_ranges;
+    a.range_skew = kRangeSkew;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const bool paged = layer->block_size != 0;

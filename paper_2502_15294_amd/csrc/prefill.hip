@@ -100,6 +100,7 @@ static int prefill_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int
     a.rec_ml = few_rows ? reinterpret_cast<float*>(ctx->ws.base + mw.ml_off) : nullptr;
     a.seq_rec = reinterpret_cast<int*>(ctx->ws.base + kWsSeqRecOff);
     a.max_ranges = shape.max_ranges;
+    a.range_skew = kRangeSkew;
     a.p_half = with_scores ? 0 : ctx->prefill_p_half;  // the watershed call's scores decide the selection: full precision
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (!(few_rows && attn_mfma_plans_inline(B, layer->R_max))) launch_plan(a, 32, st);

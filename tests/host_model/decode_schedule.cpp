@@ -27,7 +27,7 @@
 using namespace ra;
 
 struct Launch {
-    int B, inner, max_ranges, min_units, n_waves;
+    int B, inner, max_ranges, min_units, n_waves, skew;
     std::vector<int> U;      // tiles per sequence
     std::vector<int> begin;  // prefix, begin[B] = total
     std::vector<int> rec_val;  // [records][inner] tiles the record stands for (plain memory)
@@ -45,7 +45,7 @@ static void fail(Launch& L, const char* what, int a, int b) {
 static void wave(Launch& L, int w, unsigned jitter) {
     const unsigned total = (unsigned)L.begin[L.B];
     if (total == 0) return;
-    const RangeCut cut = range_cut(total, L.min_units, L.max_ranges);
+    const RangeCut cut = range_cut(total, L.min_units, L.max_ranges, L.skew);
     int n_items = (int)cut.n_ranges * L.inner;
 #ifdef PLANT_SKIP_LAST_ITEM
     n_items -= 1;  // planted mistake: the last work item is never handed out
@@ -88,7 +88,7 @@ static void wave(Launch& L, int w, unsigned jitter) {
 static void merge_step(Launch& L) {
     const unsigned total = (unsigned)L.begin[L.B];
     if (total == 0) return;
-    const RangeCut cut = range_cut(total, L.min_units, L.max_ranges);
+    const RangeCut cut = range_cut(total, L.min_units, L.max_ranges, L.skew);
     for (int b = 0; b < L.B; ++b) {
         if (L.U[b] == 0) continue;
         const SeqParts parts = seq_parts(cut, L.begin[b], L.begin[b + 1]);  // what block 0 of the kernel announces
@@ -118,16 +118,18 @@ int main(int argc, char** argv) {
         const int min_units = 1 + (int)(rng() % 4);
         int max_ranges = n_waves * (1 + (int)(rng() % 3)) / inner;  // also more ranges than waves: several items per wave
         if (max_ranges < 1) max_ranges = 1;
-        const int style = (int)(rng() % 4);
+        const int style = (int)(rng() % 5);
+        const int skew = c % 3 == 0 ? 0 : 1 + (int)(rng() % 200);  // two thirds of the cases with unequal halves
         for (int launch = 0; launch < 2; ++launch) {
             Launch L(record_capacity(max_ranges, B), B, inner);
-            L.B = B; L.inner = inner; L.max_ranges = max_ranges; L.min_units = min_units; L.n_waves = n_waves;
+            L.B = B; L.inner = inner; L.max_ranges = max_ranges; L.min_units = min_units; L.n_waves = n_waves; L.skew = skew;
             L.U.resize(B);
             for (int b = 0; b < B; ++b) {
                 int u = (int)(rng() % 40);
                 if (style == 1) u = (rng() % 3) ? 0 : (int)(rng() % 300);  // many empty sequences
                 if (style == 2) u = b == 0 ? 2000 : (int)(rng() % 3);      // one long, many tiny
                 if (style == 3) u = 1;                                      // one tile each
+                if (style == 4) u = 200 + (int)(rng() % 800);               // long ranges: the skew is in force
                 L.U[b] = u;
             }
             L.begin.assign(B + 1, 0);
@@ -144,20 +146,33 @@ int main(int argc, char** argv) {
             bad += L.errors.load();
         }
     }
-    // range arithmetic on its own: the ranges tile [0, total), differ by at most one tile, none is shorter than
-    // min_units (unless there is only one), and range_of_tile inverts range_begin
-    for (int c = 0; c < 2000; ++c) {
-        const unsigned total = 1 + (unsigned)(rng() % 100000);
+    // range arithmetic on its own: the ranges tile [0, total); without skew they differ by at most one tile; with
+    // skew each half does, the first half is the longer one and holds its share of the tiles; none is shorter than
+    // min_units (unless there is only one); range_of_tile inverts range_begin
+    for (int c = 0; c < 4000; ++c) {
+        const bool big = c % 2 == 1;
+        const unsigned total = 1 + (unsigned)(rng() % (big ? 4000000 : 100000));
         const int min_units = 1 + (int)(rng() % 8), max_ranges = 1 + (int)(rng() % 300);
-        const RangeCut cut = range_cut(total, min_units, max_ranges);
+        const int skew = c % 4 < 2 ? 0 : 1 + (int)(rng() % 200);
+        const RangeCut cut = range_cut(total, min_units, max_ranges, skew);
         if (range_begin(cut, 0) != 0 || range_begin(cut, cut.n_ranges) != total || (int)cut.n_ranges > max_ranges) { ++bad; continue; }
-        unsigned lo = total, hi = 0;
+        unsigned lo[2] = {total, total}, hi[2] = {0, 0};
         for (unsigned r = 0; r < cut.n_ranges; ++r) {
             const unsigned len = range_begin(cut, r + 1) - range_begin(cut, r);
-            lo = len < lo ? len : lo;
-            hi = len > hi ? len : hi;
+            const int k = r < cut.n_a ? 0 : 1;
+            lo[k] = len < lo[k] ? len : lo[k];
+            hi[k] = len > hi[k] ? len : hi[k];
         }
-        if (hi - lo > 1 || (cut.n_ranges > 1 && (int)lo < min_units)) ++bad;
+        const bool skewed = cut.n_a != cut.n_ranges;
+        if (hi[0] - lo[0] > 1 || (skewed && hi[1] - lo[1] > 1)) ++bad;
+        if (skew == 0 && skewed) ++bad;
+        if (skewed) {
+            if (cut.n_a * 2 != cut.n_ranges || lo[0] < lo[1] || hi[0] < hi[1] || lo[1] < kSkewMinTiles / 2) ++bad;
+            const double share = (double)cut.total_a / total, want = (1000.0 + skew) / 2000.0;
+            if (share > want + 1e-9 || share < want - 2.0 / total - 1e-9) ++bad;
+        }
+        const unsigned shortest = skewed && lo[1] < lo[0] ? lo[1] : lo[0];
+        if (cut.n_ranges > 1 && (int)shortest < min_units) ++bad;
         for (int k = 0; k < 20; ++k) {
             const unsigned t = (unsigned)(rng() % total);
             const unsigned r = range_of_tile(cut, t);
