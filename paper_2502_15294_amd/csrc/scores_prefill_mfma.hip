@@ -27,7 +27,7 @@ constexpr int kNTS = 4;                          // 16-row tiles per wave
 constexpr int kRowsPerItemS = 4 * kNTS * 16;     // 256
 constexpr int kTilesPerChunk = kChunkTokens / kTileSP;
 constexpr int kKTileBytes = 8192;
-constexpr int kPiecesPerWorkgroupS = 2;
+constexpr int kPiecesPerWorkgroupS = 1;  // measured on the 4 x 32 K-token question-prefill workload: 1: 167-172 us, 2: 174-180, 3: 176
 constexpr int kWorkgroupsPerCuS = 3;
 
 // Planning kernel, grid (B): the table of segments of sequence b (all history rounds, then the current round)
