@@ -453,7 +453,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                         for (int kk = 0; kk < 4; ++kk) t.k[h][kk] = kq[kk * 4 + q4];
                         const uint2* vq = reinterpret_cast<const uint2*>(vp);
 #pragma unroll
-                        for (int dt = 0; dt < 8; ++dt) t.v[dt][h] = vq[(dt * 16 + n) * 4 + q4];  // 4 x 8 bytes per channel
+                        // 4 x 8 bytes per channel: an instruction reads 512 contiguous bytes, whole cache lines, which is
+                        // what the non-temporal hint needs to pay (see load_once)
+                        for (int dt = 0; dt < 8; ++dt) t.v[dt][h] = load_once(vq + (dt * 16 + n) * 4 + q4);
                     }
                 }
             };
