@@ -142,9 +142,9 @@ int ra_set_workspace(ra_ctx* ctx, void* device_ptr, size_t bytes);
 int ra_profile_kernels(ra_ctx* ctx, int enable);
 int ra_profile_last_ms(ra_ctx* ctx, float* ms_out);
 /*
- * Second measurement aid: the bandwidth a plain read kernel (16-byte loads, grid-stride, nothing else) reaches
- * on this GPU over the caller's device buffer, the practical ceiling the streaming kernels are compared with
- * beside the published peak.  One untimed pass, then `iters` timed passes between two HIP events on `stream`.
+ * Second measurement aid: the bandwidth a plain read kernel (non-temporal 16-byte loads, every wave streaming its
+ * own contiguous span, nothing else) reaches on this GPU over the caller's device buffer, the practical ceiling
+ * the streaming kernels are compared with beside the published peak.  One untimed pass, then `iters` timed passes between two HIP events on `stream`.
  * Unlike the compute calls this one WAITS for its kernels and creates (and destroys) two events; the buffer
  * should be much larger than the 256 MB of last-level cache.  Needs a workspace (it keeps one word there).
  *   device_buf  device memory, 16-byte aligned; bytes a multiple of 16;  gb_per_s  host, 1e9 bytes per second

@@ -109,6 +109,11 @@ struct RowOps<BF16, EPL> {
 // reads nothing else.  And the hint must not sit behind a run-time condition: written as `flag ? load_once(p) : *p`
 // the decode kernel ran at 320 instead of 212 microseconds (the loads of a tile then sit in separate branches, and
 // the two tiles the kernel keeps in flight no longer overlap).
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_once(const uint4* p) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint2 load_once(const uint2* p) {
     const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
