@@ -48,6 +48,7 @@ struct TileRef {
     int u_seq;         // index of the tile inside the sequence's table
     bool is_cur;       // the segment is the current round (token-major keys and values)
     long long ok, ov;  // start of the segment's keys / values (tokens, or block-table slots when paged)
+    int pb0, pb1;      // paged history: physical blocks of the tile's two 16-token halves
 };
 
 __device__ __forceinline__ int lane_get(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
@@ -388,6 +389,21 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                 s_ov = lane_get64(w_ov, j);
             };
             open_slot();
+            // Paged layout: the physical blocks of the tiles ahead, 64 block-table entries at a time in this wave's
+            // registers.  A look-up per tile would be a load that the tile's own loads depend on, and loads return in
+            // order: it would come back only after everything still in flight, so no tile could be requested before
+            // the one before it had arrived.  With the window the walk waits once per 32 tiles (or segment).
+            long long bt_lo = 0;  // block-table slot of lane 0's entry
+            int bt_val = 0, bt_n = 0;
+            auto block_of = [&](long long sl) {  // sl clamped to the table
+                if (sl < bt_lo || sl >= bt_lo + bt_n) {
+                    bt_lo = sl;
+                    bt_n = 64;
+                    const long long mine = min(sl + lane, (long long)vw.max_blocks - 1);
+                    bt_val = vw.block_table[(size_t)b * vw.max_blocks + mine];
+                }
+                return max(lane_get(bt_val, (int)(sl - bt_lo)), 0);
+            };
             auto tile_at = [&](int u) {  // u >= the tile of the last call
                 while (u >= s_end) {
                     ++slot;
@@ -400,6 +416,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                 t.is_cur = slot >= n_hist;
                 t.ok = s_ok;
                 t.ov = s_ov;
+                t.pb0 = t.pb1 = 0;
+                if (PAGED && !t.is_cur) {
+                    const int nblk = (s_len + 15) >> 4;
+                    const long long last = (long long)vw.max_blocks - 1;
+                    const long long sl0 = min(max(s_ok + min(t.uin * 2, nblk - 1), 0ll), last);
+                    const long long sl1 = min(max(s_ok + min(t.uin * 2 + 1, nblk - 1), 0ll), last);
+                    t.pb0 = block_of(sl0);
+                    t.pb1 = block_of(sl1);
+                }
                 return t;
             };
 
@@ -437,10 +462,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                     } else {
                         const char *kp, *vp;
                         if (PAGED) {
-                            long long si = r.ok + blk;
-                            si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
-                            int pb = vw.block_table[(size_t)b * vw.max_blocks + si];
-                            pb = pb < 0 ? 0 : pb;
+                            const int pb = h ? r.pb1 : r.pb0;
                             kp = kbase + ((((size_t)pb * Hkv + g) * 16 + rin) * D128) * 2;
                             vp = vbase + (((size_t)pb * Hkv + g) * D128 * 16) * 2;
                         } else {

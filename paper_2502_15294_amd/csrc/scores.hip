@@ -338,7 +338,56 @@ __global__ __launch_bounds__(kFinishWaves * 64) void scores_finish_rows_kernel(F
 #pragma unroll
     for (int k = 0; k < KPL; ++k) qatt[k] = 0.f;
     float* mybuf = rowbuf + (size_t)wave * a.n_chunks_max;
-    for (int i = blockIdx.z * kFinishWaves + wave; i < a.q_len && !overflow; i += kFinishWaves * gridDim.z) {
+    // One query token (then gridDim.z is 1): instead of leaving seven waves idle and one lane per round walking its
+    // values one after the other, the eight waves share the rounds, and a wave folds a round's values with all its
+    // lanes (coalesced reads; the second pass over the same values comes from cache).  The round's log-sum-exps meet
+    // in LDS and wave 0 normalises them as below.
+    const bool one_token = a.q_len == 1 && !a.has_cur;
+    if (one_token && !overflow) {
+        const float* row = a.part + ((size_t)b * a.Hq + h) * a.n_chunks_max;
+        if (stage_rows) {  // the whole row into LDS with one round trip (the launch made room for it)
+            for (int c = tid; c < hist_chunks; c += kFinishWaves * 64) rowbuf[c] = row[c];
+            __syncthreads();
+            row = rowbuf;
+        }
+        float* round_lse = hs;  // [R_max] of the [kFinishWaves][R_max] floats; rewritten below after a barrier
+        for (int r = wave; r < R; r += kFinishWaves) {
+            const int lo = cum[r], hi = cum[r + 1];
+            float mx = -__builtin_inff();
+            for (int k = lo + lane; k < hi; k += 64) mx = fmaxf(mx, row[k]);
+            mx = wave_max(mx);
+            float sum = 0.f;
+            if (mx != -__builtin_inff())
+                for (int k = lo + lane; k < hi; k += 64) sum += __expf(row[k] - mx);
+            sum = wave_sum(sum);
+            if (lane == 0) round_lse[r] = mx == -__builtin_inff() ? mx : mx + __logf(sum);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            float lv[KPL];
+            float mx = -__builtin_inff();
+#pragma unroll
+            for (int k = 0; k < KPL; ++k) {
+                const int r = lane + 64 * k;
+                lv[k] = r < R ? round_lse[r] : -__builtin_inff();
+                mx = fmaxf(mx, lv[k]);
+            }
+            mx = wave_max(mx);
+            if (mx != -__builtin_inff()) {
+                float e[KPL], sum = 0.f;
+#pragma unroll
+                for (int k = 0; k < KPL; ++k) {
+                    e[k] = __expf(lv[k] - mx);
+                    sum += e[k];
+                }
+                const float inv = 1.f / wave_sum(sum);
+#pragma unroll
+                for (int k = 0; k < KPL; ++k) qatt[k] = e[k] * inv;
+            }
+        }
+        __syncthreads();  // round_lse is part of hs, which every wave writes next
+    }
+    for (int i = blockIdx.z * kFinishWaves + wave; i < a.q_len && !overflow && !one_token; i += kFinishWaves * gridDim.z) {
         const float* row = a.part + (((size_t)b * a.Hq + h) * a.q_len + i) * a.n_chunks_max;
         if (stage_rows) {
             for (int c = lane; c < all_chunks; c += 64) mybuf[c] = row[c];
@@ -489,9 +538,13 @@ void launch_scores_finish_rows(const FinishArgs& f, int B, float* p_part, int Z,
     const int R_max = f.R_max, Hq = f.Hq, n_chunks_max = f.n_chunks_max;
     const size_t fin_smem = (size_t)(R_max + 2) * sizeof(int) + (size_t)kFinishWaves * R_max * sizeof(float);
     const dim3 fin_block(kFinishWaves * 64);
-    const bool stage_rows =
+    bool stage_rows =
         n_chunks_max <= kRowBufMax && fin_smem + (size_t)kFinishWaves * n_chunks_max * sizeof(float) <= 60 * 1024;
-    const size_t smem = fin_smem + (stage_rows ? (size_t)kFinishWaves * n_chunks_max * sizeof(float) : 0);
+    size_t smem = fin_smem + (stage_rows ? (size_t)kFinishWaves * n_chunks_max * sizeof(float) : 0);
+    if (f.q_len == 1 && !f.has_cur) {  // one row per workgroup, shared by its waves: staged whole if it fits
+        stage_rows = fin_smem + (size_t)n_chunks_max * sizeof(float) <= 60 * 1024;
+        smem = fin_smem + (stage_rows ? (size_t)n_chunks_max * sizeof(float) : 0);
+    }
     const dim3 fgrid(B, Hq, Z);
     if (R_max <= 64)
         hipLaunchKernelGGL((scores_finish_rows_kernel<1>), fgrid, fin_block, smem, st, f, p_part, stage_rows);
