@@ -15,14 +15,17 @@ namespace ra {
 
 constexpr int kTileS = 32;
 
+// A 32-token key tile on its way from memory: load j holds 16 bytes (chunk lane%16) of the row of token
+// 4 j + lane/16, so that one load instruction reads four whole rows (eight whole cache lines).
 struct KTile {
-    uint4 k[2][4];  // [half][kk]: 8 channels kk*32 + 8*(lane/16) .. of token half*16 + lane%16
+    uint4 r[8];
 };
 
 template <bool PAGED>
 __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     extern __shared__ __align__(16) char smem[];
     __shared__ float sm[4][16], sl[4][16];
+    __shared__ uint4 strip[4][512];  // per wave: one key tile, row-major, the 16-byte chunks of row r rotated by r
     const DevView& vw = a.view;
     const int Hkv = vw.Hkv;
     const int c = blockIdx.x, b = blockIdx.z;
@@ -98,29 +101,39 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     }
 
     const char* kbase = reinterpret_cast<const char*>(vw.k);
+    // Whole rows per load instruction, non-temporal: every key is read once, and this pass, which streams the whole
+    // watershed layer, then leaves the caches to what the next kernels need (segment tables, block tables).  Rows
+    // past the segment's end re-read its last row (their scores are masked), so every address stays inside it.
     auto issue = [&](int tok0, KTile& t) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int blk = min((tok0 >> 4) + h, nblk - 1);   // halves past the end re-read the last block
-            const int rin = min(n, len - 1 - blk * 16);
+        for (int j = 0; j < 8; ++j) {
+            const int tok = min(tok0 + 4 * j + q4, len - 1);
             const char* kp;
             if (is_cur) {
-                kp = reinterpret_cast<const char*>(a.cur_k) + ((((size_t)b * a.cur_len + blk * 16 + rin) * Hkv + g) * 128) * 2;
+                kp = reinterpret_cast<const char*>(a.cur_k) + (((size_t)b * a.cur_len + tok) * Hkv + g) * 256;
             } else if (PAGED) {
-                long long si = off + blk;
+                long long si = off + (min(tok0 + 4 * j, len - 1) >> 4);  // the four rows of a load share a block
                 si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
                 const int pb = max(vw.block_table[(size_t)b * vw.max_blocks + si], 0);
-                kp = kbase + ((((size_t)pb * Hkv + g) * 16 + rin) * 128) * 2;
+                kp = kbase + (((size_t)pb * Hkv + g) * 16 + (tok & 15)) * 256;
             } else {
-                kp = kbase + ((((size_t)off * Hkv + (size_t)g * len + blk * 16 + rin) * 128)) * 2;
+                kp = kbase + ((size_t)off * Hkv + (size_t)g * len + tok) * 256;
             }
-            const uint4* kq = reinterpret_cast<const uint4*>(kp);
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) t.k[h][kk] = kq[kk * 4 + q4];
+            t.r[j] = load_once(reinterpret_cast<const uint4*>(kp) + n);
         }
     };
     auto consume = [&](const KTile& t, int tok0) {
         const bool full = !is_cur && (len - tok0 >= kTileS);
+        // through the wave's LDS strip into the operand layout: lane (n, q4) needs chunk kk*4 + q4 of row h*16 + n.
+        // (Same wave: LDS operations complete in program order, so the next tile's writes follow these reads.)
+        uint4* st = strip[wave];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st[(4 * j + q4) * 16 + ((n + 4 * j + q4) & 15)] = t.r[j];
+        uint4 kf[2][4];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) kf[h][kk] = st[(h * 16 + n) * 16 + ((kk * 4 + q4 + n) & 15)];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             floatx4_t sc[2];
@@ -128,7 +141,7 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
             for (int h = 0; h < 2; ++h) {
                 sc[h] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) sc[h] = mfma16(t.k[h][kk], qf[nt][kk], sc[h]);
+                for (int kk = 0; kk < 4; ++kk) sc[h] = mfma16(kf[h][kk], qf[nt][kk], sc[h]);
             }
             if (!full) {
 #pragma unroll

@@ -104,9 +104,12 @@ struct RowOps<BF16, EPL> {
 // plain read of 4 GiB reaches 7.0-7.1 TB/s this way against 5.9-6.2 TB/s with ordinary loads on the same MI355X (each
 // wave streaming its own span, 16- or 8-byte loads, 512 or 1024 contiguous bytes per instruction), and the decode
 // kernel's value tiles, which have that shape, took it from 212 to 194 microseconds on the large paged workload.
-// It does not pay for the key tiles as the matrix-core kernels read them (16 rows x 64 bytes per instruction, two
-// instructions to a cache line): no change in the decode kernel, 738 -> 878 microseconds in the score kernel, which
-// reads nothing else.  And the hint must not sit behind a run-time condition: written as `flag ? load_once(p) : *p`
+// It does not pay for key tiles read in the operand layout of the matrix cores (16 rows x 64 bytes per instruction,
+// two instructions to a cache line): no change in the decode kernel, 738 -> 878 microseconds in the score kernel, which
+// reads nothing else.  The score kernel therefore loads its keys as whole rows (four rows, eight cache lines per
+// instruction) and turns them into the operand layout through LDS: 738 -> 732 microseconds for itself, and the
+// kernels that follow find their tables still in the caches (decode at 6 % kept 95 -> 85 microseconds, the whole
+// small-batch step 70 -> 66).  And the hint must not sit behind a run-time condition: written as `flag ? load_once(p) : *p`
 // the decode kernel ran at 320 instead of 212 microseconds (the loads of a tile then sit in separate branches, and
 // the two tiles the kernel keeps in flight no longer overlap).
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
