@@ -8,13 +8,13 @@ namespace ra {
 
 // Share of the batch's key tiles that the first half of the decode kernel's ranges gets beyond one half, in
 // 1/1000 (RangeCut in range_schedule.hpp).  The launch puts two workgroups on every compute unit and the hardware
-// dispatches the first half of the grid first; for the whole kernel the waves that came first on a unit are served
-// ahead of the others (oldest first), so with equal ranges they end early and the chip runs half empty at the end.
-// Measured on the large paged workload at 13.9 % kept, kernel time against the skew: 0: 217.0-217.9 us, 20: 215.7,
-// 40: 215.4-216.0, 60: 213.2, 80: 211.4, 90: 212.4-213.0, 100: 212.4, 140: 216.6, 180: 217.7, 220: 220.6 (59.7 %
-// kept: 857 -> 841-848 us at 60-100; 6 % kept: ranges too short to be skewed; long-context workload: 460-461 us with
-// and without).  Should another part dispatch in another order, the cost is bounded by the skew itself.
-constexpr int kRangeSkew = 90;
+// dispatches the first half of the grid first; while all loads were ordinary ones, the waves that came first on a
+// unit were served ahead of the others for the whole kernel and ended early, and a skew of 90 took the kernel from
+// 217 to 212 microseconds on the large paged workload at 13.9 % kept (0: 217.0-217.9, 20: 215.7, 40: 215.4-216.0,
+// 60: 213.2, 80: 211.4, 100: 212.4, 140: 216.6, 180: 217.7, 220: 220.6).  Since the value tiles are read with
+// non-temporal loads (194-199 microseconds) the skew no longer matters (0: 199.1, 50: 199.8, 90: 198.6-201.0,
+// 130: 200.7; 59.7 % kept: 778-783 for all four), so the ranges are equal again; the two-class cut stays available.
+constexpr int kRangeSkew = 0;
 
 struct AttnArgs {
     DevView view;
