@@ -7,7 +7,9 @@
 // This kernel serves up to 16 query rows per KV head (decode, very short questions); more rows use the
 // kernel that shares key tiles through LDS.
 // Work item: (chunk c of 256 tokens, KV head g, sequence b) -> one log-sum-exp per row.  The four waves
-// take two key tiles each, all loads issued up front, and are merged through LDS.
+// take two key tiles each, all loads issued up front, and are merged through LDS.  The keys come in as whole rows
+// with non-temporal loads (this pass reads the whole layer once and should leave the caches alone) and reach the
+// operand layout through an 8 KB strip of LDS per wave.
 #include "scores_common.hpp"
 #include "mfma_util.hpp"
 
