@@ -13,7 +13,11 @@ namespace ra {
 // 217 to 212 microseconds on the large paged workload at 13.9 % kept (0: 217.0-217.9, 20: 215.7, 40: 215.4-216.0,
 // 60: 213.2, 80: 211.4, 100: 212.4, 140: 216.6, 180: 217.7, 220: 220.6).  Since the value tiles are read with
 // non-temporal loads (194-199 microseconds) the skew no longer matters (0: 199.1, 50: 199.8, 90: 198.6-201.0,
-// 130: 200.7; 59.7 % kept: 778-783 for all four), so the ranges are equal again; the two-class cut stays available.
+// 130: 200.7; 59.7 % kept: 778-783 for all four).  Time stamps show why: a wave keeps two tiles in flight and the
+// hardware serves the first-dispatched wave of a SIMD at 0.27 tiles per microsecond whatever the other one gets
+// (0.20 with equal ranges, 0.15 when the first has 65 % of the tiles), so a skew only moves time between the two
+// phases; both halves end together at a skew of 300, which gains 1.4 % (192.0-193.2 against 194.7-195.9) and would
+// cost up to 30 % on a part that serves its waves evenly.  The ranges are equal; the two-class cut stays available.
 constexpr int kRangeSkew = 0;
 
 struct AttnArgs {
