@@ -214,7 +214,9 @@ int ra_workspace_bytes(const ra_problem* p, size_t* bytes_out) {
     if (few > attn) attn = few;
     // score intermediates: one log-sum-exp per (row, 256-token chunk), plus up to eight partial per-head score rows
     const size_t chunks = (size_t)(p->max_tokens / 256) + p->R_max + 2;
-    const size_t sc = rows * chunks * sizeof(float) + (size_t)8 * p->B * p->Hq * p->R_max * sizeof(float) + 256;
+    // and a 16-byte descriptor per (sequence, chunk)
+    const size_t sc = rows * chunks * sizeof(float) + (size_t)8 * p->B * p->Hq * p->R_max * sizeof(float) + 256 +
+                      (size_t)p->B * chunks * 16 + 256;
     // decode at the watershed layer keeps, besides the attention partials, one log-sum-exp per (row, 32-token tile)
     const size_t tiles = (size_t)(p->max_tokens / 32) + p->R_max + 2;
     const size_t fused = align_up(attn, 256) + align_up(rows * tiles * sizeof(float), 256) +

@@ -635,9 +635,11 @@ static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int 
     if (mfma) RA_REQUIRE(G <= 16, RA_ERR_UNSUPPORTED, "round_scores: Hq / Hkv = %d exceeds 16", G);
     if (many_rows) RA_REQUIRE(B <= kMaxBatch, RA_ERR_UNSUPPORTED, "round_scores: batch %d exceeds %d", B, kMaxBatch);
     const size_t plan_bytes = many_rows ? align_up((size_t)B * plan_stride(R_max + 1), 256) : 0;
-    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= kWsReserved + part_bytes + p_bytes + plan_bytes,
+    // few rows on the matrix cores: one 16-byte descriptor per (sequence, chunk)
+    const size_t desc_bytes = mfma && !many_rows ? align_up((size_t)B * n_chunks_max * 16, 256) : 0;
+    RA_REQUIRE(ctx->ws.base != nullptr && ctx->ws.bytes >= kWsReserved + part_bytes + p_bytes + plan_bytes + desc_bytes,
                RA_ERR_WORKSPACE, "round_scores: workspace has %zu bytes, this call needs %zu", ctx->ws.bytes,
-               kWsReserved + part_bytes + p_bytes + plan_bytes);
+               kWsReserved + part_bytes + p_bytes + plan_bytes + desc_bytes);
 
     ScoreArgs a;
     a.view = to_dev(watershed);
@@ -651,6 +653,7 @@ static int scores_impl(ra_ctx* ctx, void* stream, const void* q, int q_len, int 
     a.c = scale * kLog2e;
     a.part = reinterpret_cast<float*>(ctx->ws.base + kWsReserved);
     a.plan = ctx->ws.base + kWsReserved + part_bytes + p_bytes;
+    a.chunks = desc_bytes ? ctx->ws.base + kWsReserved + part_bytes + p_bytes + plan_bytes : nullptr;
     a.S = 1 << 20;
     a.min_units = 16;
 

@@ -17,6 +17,7 @@ struct ScoreArgs {
     int chunk_tokens;   // tokens per chunk (a chunk never crosses a round)
     float c;            // scale * log2(e)
     float* part;        // [B][Hq][q_len][n_chunks_max] natural-log sum-exp of the scaled logits of one chunk
+    void* chunks = nullptr;  // few-row kernel only: room for [B][n_chunks_max] 16-byte chunk descriptors, or null
     // many-row kernel only: room for its segment tables and the bounds of its schedule
     const char* plan;   // [B][plan_stride(R_max + 1)]
     int S, min_units;   // a sequence is cut into at most S pieces of at least min_units key tiles

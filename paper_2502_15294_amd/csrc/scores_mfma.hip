@@ -10,12 +10,18 @@
 // take two key tiles each, all loads issued up front, and are merged through LDS.  The keys come in as whole rows
 // with non-temporal loads (this pass reads the whole layer once and should leave the caches alone) and reach the
 // operand layout through an 8 KB strip of LDS per wave.
+// Which round a chunk belongs to comes from the sequence's table, built in LDS by every workgroup in small launches;
+// in large ones, where a workgroup starts while the compute unit's vector memory queue is full of other workgroups'
+// key tiles, from a descriptor that a small kernel wrote beforehand and that arrives by a scalar load.
 #include "scores_common.hpp"
 #include "mfma_util.hpp"
 
 namespace ra {
 
 constexpr int kTileS = 32;
+// Launches of at least this many workgroups (twice what the chip holds at once) read chunk descriptors: 732 -> 668
+// microseconds on 4.3 GB of keys, 38.7 -> 33.8 on 199 MB; below it the descriptor kernel costs more than it saves.
+constexpr long long kDescMinWorkgroups = 2048;
 
 // A 32-token key tile on its way from memory: load j holds 16 bytes (chunk lane%16) of the row of token
 // 4 j + lane/16, so that one load instruction reads four whole rows (eight whole cache lines).
@@ -23,7 +29,78 @@ struct KTile {
     uint4 r[8];
 };
 
-template <bool PAGED>
+// Where chunk c of a sequence lies: written once per call by scores_chunks_kernel for the large launches, whose
+// workgroups then start with one scalar load instead of building the sequence's table themselves.
+struct ChunkDesc {
+    long long off;  // the segment's offset in the store (tokens, or blocks when paged)
+    int len;        // tokens of the segment
+    int tok0_bits;  // first token of the chunk within the segment (a multiple of 256) | 1 current round | 2 exists
+};
+static_assert(sizeof(ChunkDesc) == 16, "one 16-byte scalar load");
+
+// A load whose address is the same in every lane and whose memory no kernel of this launch writes: through the
+// constant address space, so that it is a scalar load.  Scalar loads do not queue behind the compute unit's vector
+// loads, which is where a workgroup of a saturated launch otherwise waits for its first table entry.
+typedef const __attribute__((address_space(4))) u32x4_t* scalar_u32x4_ptr;
+typedef const __attribute__((address_space(4))) int* scalar_int_ptr;
+__device__ __forceinline__ uint4 load_uniform(const uint4* p) {
+    const u32x4_t v = *(scalar_u32x4_ptr)(uintptr_t)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ int load_uniform(const int* p) { return *(scalar_int_ptr)(uintptr_t)p; }
+
+// The chunk table of sequence b in LDS (t_off, t_len, t_cum[n_slots + 1]); all threads of the workgroup call it.
+__device__ __forceinline__ void build_chunk_table(const ScoreArgs& a, int b, int tid, long long* t_off, int* t_len,
+                                                  int* t_cum, int& n_hist, int& n_slots) {
+    const DevView& vw = a.view;
+    // The first 256 table entries are asked for before the round count has arrived (entries past it are
+    // dropped): one memory round trip instead of two at the start of every workgroup.
+    int len0 = 0;
+    long long off0 = 0;
+    if (tid < vw.R_max) {
+        len0 = vw.seg_len[(size_t)b * vw.R_max + tid];
+        off0 = vw.seg_off[(size_t)b * vw.R_max + tid];
+    }
+    n_hist = min(max(vw.n_rounds[b], 0), vw.R_max);
+    n_slots = n_hist + (a.cur_k && a.cur_len > 0 ? 1 : 0);
+    for (int s = tid; s < n_slots; s += 256) {
+        int len = a.cur_len;
+        long long off = 0;
+        if (s < n_hist) {
+            len = max(s < 256 ? len0 : vw.seg_len[(size_t)b * vw.R_max + s], 0);
+            off = s < 256 ? off0 : vw.seg_off[(size_t)b * vw.R_max + s];
+        }
+        t_len[s] = len;
+        t_off[s] = off;
+        t_cum[s] = chunks_of(len);
+    }
+    exclusive_scan_units(t_cum, n_slots);
+}
+
+// One workgroup per sequence: the descriptor of every chunk the launch has a workgroup for.
+__global__ __launch_bounds__(256) void scores_chunks_kernel(ScoreArgs a, ChunkDesc* desc) {
+    extern __shared__ __align__(16) char smem[];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int cap = a.view.R_max + 1;
+    long long* t_off = reinterpret_cast<long long*>(smem);
+    int* t_len = reinterpret_cast<int*>(t_off + cap);
+    int* t_cum = t_len + cap;
+    int n_hist, n_slots;
+    build_chunk_table(a, b, tid, t_off, t_len, t_cum, n_hist, n_slots);
+    const int total = n_slots > 0 ? t_cum[n_slots] : 0;
+    for (int c = tid; c < a.n_chunks_max; c += 256) {
+        ChunkDesc d = {0, 0, 0};
+        if (c < total) {
+            const int slot = find_slot(t_cum, n_slots, c);
+            d.off = t_off[slot];
+            d.len = t_len[slot];
+            d.tok0_bits = (c - t_cum[slot]) * kChunkTokens | (slot >= n_hist ? 1 : 0) | 2;
+        }
+        desc[(size_t)b * a.n_chunks_max + c] = d;
+    }
+}
+
+template <bool PAGED, bool DESC>
 __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     extern __shared__ __align__(16) char smem[];
     __shared__ float sm[4][16], sl[4][16];
@@ -40,40 +117,31 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     constexpr int NT = 1, RB = 16;
 
     // ---- which round does chunk c belong to? -------------------------------------------------------
-    const int cap = vw.R_max + 1;
-    long long* t_off = reinterpret_cast<long long*>(smem);
-    int* t_len = reinterpret_cast<int*>(t_off + cap);
-    int* t_cum = t_len + cap;
-    // The first 256 table entries are asked for before the round count has arrived (entries past it are
-    // dropped): one memory round trip instead of two at the start of every workgroup.
-    int len0 = 0;
-    long long off0 = 0;
-    if (tid < vw.R_max) {
-        len0 = vw.seg_len[(size_t)b * vw.R_max + tid];
-        off0 = vw.seg_off[(size_t)b * vw.R_max + tid];
+    int len, chunk_tok0;
+    long long off;
+    bool is_cur;
+    if constexpr (DESC) {
+        const uint4 raw = load_uniform(reinterpret_cast<const uint4*>(a.chunks) + (size_t)b * a.n_chunks_max + c);
+        if (!(raw.w & 2)) return;
+        off = (long long)(((unsigned long long)raw.y << 32) | raw.x);
+        len = (int)raw.z;
+        is_cur = raw.w & 1;
+        chunk_tok0 = (int)(raw.w & ~255u);
+    } else {
+        const int cap = vw.R_max + 1;
+        long long* t_off = reinterpret_cast<long long*>(smem);
+        int* t_len = reinterpret_cast<int*>(t_off + cap);
+        int* t_cum = t_len + cap;
+        int n_hist, n_slots;
+        build_chunk_table(a, b, tid, t_off, t_len, t_cum, n_hist, n_slots);
+        const int total = n_slots > 0 ? t_cum[n_slots] : 0;
+        if (c >= total) return;
+        const int slot = find_slot(t_cum, n_slots, c);
+        len = t_len[slot];
+        off = t_off[slot];
+        is_cur = slot >= n_hist;
+        chunk_tok0 = (c - t_cum[slot]) * kChunkTokens;
     }
-    const int n_hist = min(max(vw.n_rounds[b], 0), vw.R_max);
-    const int n_slots = n_hist + (a.cur_k && a.cur_len > 0 ? 1 : 0);
-    for (int s = tid; s < n_slots; s += 256) {
-        int len = a.cur_len;
-        long long off = 0;
-        if (s < n_hist) {
-            len = max(s < 256 ? len0 : vw.seg_len[(size_t)b * vw.R_max + s], 0);
-            off = s < 256 ? off0 : vw.seg_off[(size_t)b * vw.R_max + s];
-        }
-        t_len[s] = len;
-        t_off[s] = off;
-        t_cum[s] = chunks_of(len);
-    }
-    exclusive_scan_units(t_cum, n_slots);
-    const int total = n_slots > 0 ? t_cum[n_slots] : 0;
-    if (c >= total) return;
-    const int slot = find_slot(t_cum, n_slots, c);
-    const int len = t_len[slot];
-    const long long off = t_off[slot];
-    const bool is_cur = slot >= n_hist;
-    const int chunk_tok0 = (c - t_cum[slot]) * kChunkTokens;
-    const int nblk = (len + 15) >> 4;
 
     // ---- this wave's query rows -----------------------------------------------------------------------
     int lim[NT];
@@ -116,7 +184,8 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
             } else if (PAGED) {
                 long long si = off + (min(tok0 + 4 * j, len - 1) >> 4);  // the four rows of a load share a block
                 si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
-                const int pb = max(vw.block_table[(size_t)b * vw.max_blocks + si], 0);
+                const int* bt = vw.block_table + (size_t)b * vw.max_blocks + si;  // the same in all lanes
+                const int pb = max(DESC ? load_uniform(bt) : *bt, 0);
                 kp = kbase + (((size_t)pb * Hkv + g) * 16 + (tok & 15)) * 256;
             } else {
                 kp = kbase + ((size_t)off * Hkv + (size_t)g * len + tok) * 256;
@@ -218,10 +287,20 @@ int launch_scores_mfma(const ScoreArgs& a, bool paged, int /*num_cu*/, hipStream
     const size_t tab_bytes = (size_t)(a.view.R_max + 1) * 16 + 16;
     if (rows_total > 16) return fail(RA_ERR_UNSUPPORTED, "round_scores: %d query rows per KV head in the 16-row kernel", rows_total);
     const dim3 grid(a.n_chunks_max, a.view.Hkv, a.view.B);
+    // From a few workgroups per slot of the chip on, a small kernel writes every chunk's descriptor first
+    if (a.chunks && (long long)a.n_chunks_max * a.view.Hkv * a.view.B >= kDescMinWorkgroups) {
+        hipLaunchKernelGGL(scores_chunks_kernel, dim3(a.view.B), dim3(256), tab_bytes, st, a,
+                           reinterpret_cast<ChunkDesc*>(a.chunks));
+        if (paged)
+            RA_LAUNCH_TIMED((scores_mfma_kernel<true, true>), grid, dim3(256), 0, st, a);
+        else
+            RA_LAUNCH_TIMED((scores_mfma_kernel<false, true>), grid, dim3(256), 0, st, a);
+        return RA_OK;
+    }
     if (paged)
-        RA_LAUNCH_TIMED((scores_mfma_kernel<true>), grid, dim3(256), tab_bytes, st, a);
+        RA_LAUNCH_TIMED((scores_mfma_kernel<true, false>), grid, dim3(256), tab_bytes, st, a);
     else
-        RA_LAUNCH_TIMED((scores_mfma_kernel<false>), grid, dim3(256), tab_bytes, st, a);
+        RA_LAUNCH_TIMED((scores_mfma_kernel<false, false>), grid, dim3(256), tab_bytes, st, a);
     return RA_OK;
 }
 

@@ -724,6 +724,44 @@ def test_watershed_decode_attention_and_scores_match_oracle(name, staged):
     eng.close()
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,over", [("cfg2", dict(B=2)), ("cfg2", dict(B=2, block_size=16)),
+                                        ("cfg2", dict(B=3, cur_len=40))], ids=["contiguous", "paged", "current_round"])
+def test_score_pass_does_not_depend_on_the_declared_capacity(name, over):
+    """A store that declares room for a longer history gets a launch large enough for the score kernel to read
+    per-chunk descriptors instead of building each sequence's table in every workgroup: same chunks, same
+    arithmetic, so the scores, the per-head scores and the selection must be the same bits."""
+    w = make_workload(name, **over)
+    _say(f"score capacity case: B={w.B} R_max={w.R_max} cur_len={w.cur_len} block={w.block_size}")
+    extra = 40000                                  # 156 more chunks per sequence: past the switch for any B >= 2
+    eng = Engine(w, extra_tokens=extra)
+    view = device_view(w, 0)
+    k, v, seg_off, seg_len, n_rounds, bt, seg_off_v = view.tensors
+    roomy = ra.KVView(k, v, seg_off, seg_len, n_rounds, view.Hkv, view.d, view.c.max_tokens + extra,
+                      block_table=bt, block_size=view.c.block_size, seg_off_v=seg_off_v)
+    assert (view.c.max_tokens // 256 + w.R_max + 1) * view.Hkv * w.B < 2048 <= (extra // 256) * view.Hkv * w.B
+    q = to_device(w.q(0), w.dtype)
+    ck = to_device(w.cur_k(0), w.dtype) if w.cur_len else None
+    params = ra.make_select_params(lam=1.0)
+    got = []
+    for vw in (view, roomy):
+        if ck is None:
+            P, S, idx, n = ra.ra_round_scores_select(eng.ctx, q, vw, params, scale=w.scale)
+            got.append((P, S, idx, n))
+        else:  # several query tokens' worth of masses: the current round's keys are read as well
+            acc = torch.zeros(w.B, w.Hq, w.R_max, dtype=torch.float32, device="cuda")
+            P, S = ra.ra_round_scores_accumulate(eng.ctx, q, vw, acc, cur_k=ck, scale=w.scale)
+            got.append((P, S, acc))
+    torch.cuda.synchronize()
+    for x, y in zip(*got):
+        assert torch.equal(x, y)
+    rP, rS = pipeline.scores_for_sequence(w, 0) if ck is None else (None, None)
+    if rP is not None:
+        R = w.n_rounds(0)
+        assert np.abs(got[1][0][0, :, :R].cpu().numpy() - rP).max() < SCORE_TOL
+    eng.close()
+
+
 def test_watershed_decode_rejects_what_it_cannot_do():
     w = make_workload("cfg1")                     # fp32, d = 64
     eng = Engine(w)
