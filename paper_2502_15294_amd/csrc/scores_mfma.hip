@@ -174,22 +174,53 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     // Whole rows per load instruction, non-temporal: every key is read once, and this pass, which streams the whole
     // watershed layer, then leaves the caches to what the next kernels need (segment tables, block tables).  Rows
     // past the segment's end re-read its last row (their scores are masked), so every address stays inside it.
-    auto issue = [&](int tok0, KTile& t) {
+    // Row t of a tile's half hh is at base[hh] + (t & mask) * pitch: one form for the current round, a contiguous
+    // segment and the two blocks of a paged tile (the second one clamped to the segment's last block, as the rows
+    // are), so that the load loop has no branches.  The block look-ups of both of the wave's tiles are made, for any
+    // kind of segment and with clamped indices, before its first key load: they are in flight together, where a
+    // look-up between the key loads would be waited for right there, one round trip per load instruction.
+    struct TileBase {
+        const char* base[2];
+    };
+    const long long pitch = is_cur ? (long long)Hkv * 256 : 256;
+    const int mask = (PAGED && !is_cur) ? 15 : -1;
+    auto bases_of = [&](const int (&tok0)[2], TileBase (&tb)[2]) {
+        if constexpr (PAGED) {
+            const int* bt[2][2];
+            int pb[2][2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    long long si = off + (min(tok0[j] + 16 * hh, len - 1) >> 4);
+                    si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
+                    bt[j][hh] = vw.block_table + (size_t)b * vw.max_blocks + si;  // the same in all lanes
+                }
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) pb[j][hh] = DESC ? load_uniform(bt[j][hh]) : *bt[j][hh];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh)
+                    tb[j].base[hh] = kbase + ((size_t)max(pb[j][hh], 0) * Hkv + g) * 16 * 256;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) tb[j].base[0] = tb[j].base[1] = kbase + ((size_t)off * Hkv + (size_t)g * len) * 256;
+        }
+        if (is_cur) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                tb[j].base[0] = tb[j].base[1] =
+                    reinterpret_cast<const char*>(a.cur_k) + ((size_t)b * a.cur_len * Hkv + g) * 256;
+        }
+    };
+    auto issue = [&](int tok0, const TileBase& tb, KTile& t) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int tok = min(tok0 + 4 * j + q4, len - 1);
-            const char* kp;
-            if (is_cur) {
-                kp = reinterpret_cast<const char*>(a.cur_k) + (((size_t)b * a.cur_len + tok) * Hkv + g) * 256;
-            } else if (PAGED) {
-                long long si = off + (min(tok0 + 4 * j, len - 1) >> 4);  // the four rows of a load share a block
-                si = si < 0 ? 0 : (si >= vw.max_blocks ? vw.max_blocks - 1 : si);
-                const int* bt = vw.block_table + (size_t)b * vw.max_blocks + si;  // the same in all lanes
-                const int pb = max(DESC ? load_uniform(bt) : *bt, 0);
-                kp = kbase + (((size_t)pb * Hkv + g) * 16 + (tok & 15)) * 256;
-            } else {
-                kp = kbase + ((size_t)off * Hkv + (size_t)g * len + tok) * 256;
-            }
+            const char* kp = tb.base[j >> 2] + (long long)(tok & mask) * pitch;
             t.r[j] = load_once(reinterpret_cast<const uint4*>(kp) + n);
         }
     };
@@ -241,11 +272,13 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     {
         KTile t[2];
         int tok0[2];
+        TileBase tb[2];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            tok0[j] = chunk_tok0 + (j * 4 + wave) * kTileS;  // the four waves read adjacent tiles
-            if (tok0[j] < len) issue(tok0[j], t[j]);
-        }
+        for (int j = 0; j < 2; ++j) tok0[j] = chunk_tok0 + (j * 4 + wave) * kTileS;  // the four waves read adjacent tiles
+        bases_of(tok0, tb);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (tok0[j] < len) issue(tok0[j], tb[j], t[j]);
 #pragma unroll
         for (int j = 0; j < 2; ++j)
             if (tok0[j] < len) consume(t[j], tok0[j]);
