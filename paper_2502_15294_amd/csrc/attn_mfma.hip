@@ -380,7 +380,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             int s_len, s_first, s_end;  // the slot the walk stands in: tokens, first tile, tile after the last
             long long s_ok, s_ov;
             auto open_slot = [&]() {
-                if (slot - win_lo >= 63) fill_window(slot);  // entry slot + 1 must be in the window too
+                if (slot - win_lo >= 63) {  // entry slot + 1 must be in the window too
+                    fill_window(slot);
+                    wait_for_loads_so_far();  // here, once per window, not after the join on every segment
+                }
                 const int j = slot - win_lo;
                 s_len = lane_get(w_len, j);
                 s_first = lane_get(w_cum, j);
@@ -401,6 +404,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
                     bt_n = 64;
                     const long long mine = min(sl + lane, (long long)vw.max_blocks - 1);
                     bt_val = vw.block_table[(size_t)b * vw.max_blocks + mine];
+                    wait_for_loads_so_far();  // here, once per window, not after the join on every tile
                 }
                 return max(lane_get(bt_val, (int)(sl - bt_lo)), 0);
             };

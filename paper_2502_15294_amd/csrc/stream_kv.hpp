@@ -243,6 +243,10 @@ __device__ __forceinline__ void load_to_lds(const char* base, unsigned off, unsi
 }
 // s_waitcnt vmcnt(0) (the other counters at their maxima: expcnt 7, lgkmcnt 15)
 __device__ __forceinline__ void wait_for_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+// The same wait, for a load that is issued only on some paths and used after they meet.  Left to the compiler, the
+// wait lands after the join and is a wait for everything (with a conditional load in between, the number of younger
+// loads is no constant), on every pass; written into the branch, right behind the load, it is paid only there.
+__device__ __forceinline__ void wait_for_loads_so_far() { __builtin_amdgcn_s_waitcnt(0x0f70); }
 #pragma clang diagnostic pop
 
 // ---- balanced schedule of a whole batch ------------------------------------------------------------
