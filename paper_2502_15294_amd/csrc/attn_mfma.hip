@@ -572,8 +572,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             };
 
             // ---- stream the tiles u_lo .. u_hi - 1 --------------------------------------------------------
-            // Two tile buffers used alternately: the loads of one tile are in flight while the other is consumed,
-            // and no register that is still being loaded is ever copied.
+            // Two tile buffers used alternately, and no register that is still being loaded is ever copied.  The
+            // next request sits under a condition, so the compiler waits for all outstanding loads before a tile's
+            // first product: both tiles are requested back to back and arrive together.  A form of this loop whose
+            // waits leave the other tile's loads outstanding was measured and is no faster: with eight waves per
+            // compute unit the memory system is full either way.
             {
                 KVTile ta, tb;
                 TileRef ref_a, ref_b;
