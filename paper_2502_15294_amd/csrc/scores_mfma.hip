@@ -10,9 +10,11 @@
 // take two key tiles each, all loads issued up front, and are merged through LDS.  The keys come in as whole rows
 // with non-temporal loads (this pass reads the whole layer once and should leave the caches alone) and reach the
 // operand layout through an 8 KB strip of LDS per wave.
-// Which round a chunk belongs to comes from the sequence's table, built in LDS by every workgroup in small launches;
-// in large ones, where a workgroup starts while the compute unit's vector memory queue is full of other workgroups'
-// key tiles, from a descriptor that a small kernel wrote beforehand and that arrives by a scalar load.
+// Which round a chunk belongs to: a workgroup starts while the compute unit's vector memory queue is full of other
+// workgroups' key tiles, so what it needs to find its round should not come through that queue.  In large launches
+// it is a descriptor that a small kernel wrote beforehand and that arrives by one scalar load; for sequences of up
+// to 32 rounds the rounds' lengths by scalar loads and a prefix sum over the lanes, with no kernel before; otherwise
+// the sequence's table built in LDS from vector loads.
 #include "scores_common.hpp"
 #include "mfma_util.hpp"
 
@@ -22,6 +24,9 @@ constexpr int kTileS = 32;
 // Launches of at least this many workgroups (twice what the chip holds at once) read chunk descriptors: 732 -> 668
 // microseconds on 4.3 GB of keys, 38.7 -> 33.8 on 199 MB; below it the descriptor kernel costs more than it saves.
 constexpr long long kDescMinWorkgroups = 2048;
+// ... and with few rounds, where a workgroup can find its round from scalar loads alone (about 0.1 microseconds of
+// scalar work at every start, against 4 microseconds once for the descriptor kernel), only from here on
+constexpr long long kDescMinWorkgroupsFewRounds = 32768;
 
 // A 32-token key tile on its way from memory: load j holds 16 bytes (chunk lane%16) of the row of token
 // 4 j + lane/16, so that one load instruction reads four whole rows (eight whole cache lines).
@@ -48,6 +53,11 @@ __device__ __forceinline__ uint4 load_uniform(const uint4* p) {
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ int load_uniform(const int* p) { return *(scalar_int_ptr)(uintptr_t)p; }
+typedef const __attribute__((address_space(4))) u32x2_t* scalar_u32x2_ptr;
+__device__ __forceinline__ uint2 load_uniform(const uint2* p) {
+    const u32x2_t v = *(scalar_u32x2_ptr)(uintptr_t)p;
+    return make_uint2(v.x, v.y);
+}
 
 // The chunk table of sequence b in LDS (t_off, t_len, t_cum[n_slots + 1]); all threads of the workgroup call it.
 __device__ __forceinline__ void build_chunk_table(const ScoreArgs& a, int b, int tid, long long* t_off, int* t_len,
@@ -100,8 +110,15 @@ __global__ __launch_bounds__(256) void scores_chunks_kernel(ScoreArgs a, ChunkDe
     }
 }
 
-template <bool PAGED, bool DESC>
+// How a workgroup finds its chunk's round
+constexpr int kTableInLds = 0;    // the sequence's table built in LDS from vector loads (any number of rounds)
+constexpr int kDescriptors = 1;   // one scalar load of what scores_chunks_kernel wrote (large launches)
+constexpr int kTableScalar = 2;   // at most kScalarRounds rounds: their lengths by scalar loads, the prefix in
+constexpr int kScalarRounds = 32; // scalar registers: no LDS, no barrier, no vector load, and no kernel before
+
+template <bool PAGED, int TAB>
 __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
+    constexpr bool DESC = TAB != kTableInLds;  // the table's loads go the scalar way
     extern __shared__ __align__(16) char smem[];
     __shared__ float sm[4][16], sl[4][16];
     __shared__ uint4 strip[4][512];  // per wave: one key tile, row-major, the 16-byte chunks of row r rotated by r
@@ -120,7 +137,38 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
     int len, chunk_tok0;
     long long off;
     bool is_cur;
-    if constexpr (DESC) {
+    if constexpr (TAB == kTableScalar) {
+        // Every length is asked for at once (the index clamped to the table, so nothing outside it is read) and
+        // lands in lane s of one register; the current round's length goes to the lane after the history's.  A
+        // prefix sum over the lanes' chunk counts then tells which lane's segment holds chunk c.
+        const int n_hist = min(max(load_uniform(vw.n_rounds + b), 0), vw.R_max);
+        int lens = 0;
+#pragma unroll
+        for (int s = 0; s < kScalarRounds; ++s) {
+            const int v = load_uniform(vw.seg_len + (size_t)b * vw.R_max + min(s, vw.R_max - 1));
+            lens = lane == s ? v : lens;
+        }
+        const bool use_cur = a.cur_k && a.cur_len > 0;
+        const int mine = lane < n_hist ? max(lens, 0) : (lane == n_hist && use_cur ? a.cur_len : 0);
+        const int nc = chunks_of(mine);
+        int incl = nc;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        const unsigned long long hit = __ballot(c >= incl - nc && c < incl);  // at most one lane
+        if (hit == 0) return;
+        const int slot = __ffsll((long long)hit) - 1;
+        len = __builtin_amdgcn_readlane(mine, slot);
+        chunk_tok0 = (c - __builtin_amdgcn_readlane(incl - nc, slot)) * kChunkTokens;
+        is_cur = slot >= n_hist;
+        off = 0;
+        if (!is_cur) {
+            const uint2 o = load_uniform(reinterpret_cast<const uint2*>(vw.seg_off + (size_t)b * vw.R_max + slot));
+            off = (long long)(((unsigned long long)o.y << 32) | o.x);
+        }
+    } else if constexpr (TAB == kDescriptors) {
         const uint4 raw = load_uniform(reinterpret_cast<const uint4*>(a.chunks) + (size_t)b * a.n_chunks_max + c);
         if (!(raw.w & 2)) return;
         off = (long long)(((unsigned long long)raw.y << 32) | raw.x);
@@ -321,19 +369,27 @@ int launch_scores_mfma(const ScoreArgs& a, bool paged, int /*num_cu*/, hipStream
     if (rows_total > 16) return fail(RA_ERR_UNSUPPORTED, "round_scores: %d query rows per KV head in the 16-row kernel", rows_total);
     const dim3 grid(a.n_chunks_max, a.view.Hkv, a.view.B);
     // From a few workgroups per slot of the chip on, a small kernel writes every chunk's descriptor first
-    if (a.chunks && (long long)a.n_chunks_max * a.view.Hkv * a.view.B >= kDescMinWorkgroups) {
+    const long long n_wg = (long long)a.n_chunks_max * a.view.Hkv * a.view.B;
+    if (a.chunks && n_wg >= (a.view.R_max <= kScalarRounds ? kDescMinWorkgroupsFewRounds : kDescMinWorkgroups)) {
         hipLaunchKernelGGL(scores_chunks_kernel, dim3(a.view.B), dim3(256), tab_bytes, st, a,
                            reinterpret_cast<ChunkDesc*>(a.chunks));
         if (paged)
-            RA_LAUNCH_TIMED((scores_mfma_kernel<true, true>), grid, dim3(256), 0, st, a);
+            RA_LAUNCH_TIMED((scores_mfma_kernel<true, kDescriptors>), grid, dim3(256), 0, st, a);
         else
-            RA_LAUNCH_TIMED((scores_mfma_kernel<false, true>), grid, dim3(256), 0, st, a);
+            RA_LAUNCH_TIMED((scores_mfma_kernel<false, kDescriptors>), grid, dim3(256), 0, st, a);
+        return RA_OK;
+    }
+    if (a.view.R_max <= kScalarRounds) {
+        if (paged)
+            RA_LAUNCH_TIMED((scores_mfma_kernel<true, kTableScalar>), grid, dim3(256), 0, st, a);
+        else
+            RA_LAUNCH_TIMED((scores_mfma_kernel<false, kTableScalar>), grid, dim3(256), 0, st, a);
         return RA_OK;
     }
     if (paged)
-        RA_LAUNCH_TIMED((scores_mfma_kernel<true, false>), grid, dim3(256), tab_bytes, st, a);
+        RA_LAUNCH_TIMED((scores_mfma_kernel<true, kTableInLds>), grid, dim3(256), tab_bytes, st, a);
     else
-        RA_LAUNCH_TIMED((scores_mfma_kernel<false, false>), grid, dim3(256), tab_bytes, st, a);
+        RA_LAUNCH_TIMED((scores_mfma_kernel<false, kTableInLds>), grid, dim3(256), tab_bytes, st, a);
     return RA_OK;
 }
 
