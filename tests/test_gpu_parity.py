@@ -133,6 +133,11 @@ SCORE_CASES = {
     # one query token, 64 heads x more than 256 partial values each: finished head by head, then averaged
     "bf16_g8_many_chunks": ("cfg5", dict(B=2, R=300, block_size=0, length=("uniform", 1, 40))),
     "bf16_g8_many_chunks_paged": ("cfg5", dict(B=3, R=270, length=("uniform", 1, 40))),
+    # on either side of the number of rounds up to which a workgroup finds its round from scalar loads alone
+    "bf16_32_rounds_cur": ("cfg2", dict(B=2, R=32, q_len=2, cur_len=300, length=("uniform", 0, 600))),
+    "bf16_33_rounds_cur": ("cfg2", dict(B=2, R=33, q_len=2, cur_len=300, length=("uniform", 0, 600))),
+    "bf16_32_rounds_paged": ("cfg5", dict(B=2, R=32, length=("uniform", 0, 600))),
+    "bf16_1_round": ("cfg2", dict(B=2, R=1, length=("uniform", 500, 600))),
 }
 
 
