@@ -151,11 +151,17 @@ __global__ __launch_bounds__(256) void scores_mfma_kernel(ScoreArgs a) {
         const bool use_cur = a.cur_k && a.cur_len > 0;
         const int mine = lane < n_hist ? max(lens, 0) : (lane == n_hist && use_cur ? a.cur_len : 0);
         const int nc = chunks_of(mine);
+        // inclusive prefix over the lanes: shifts inside the rows of 16 lanes (zeros come in at a row's start), then
+        // the totals of the rows before added from scalar registers -- no trip through LDS
         int incl = nc;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(incl, o, 64);
-            if (lane >= o) incl += t;
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xf, 0xf, false);  // row_shr:1
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xf, 0xf, false);  // row_shr:2
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xf, 0xf, false);  // row_shr:4
+        incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xf, 0xf, false);  // row_shr:8
+        {
+            const int t0 = __builtin_amdgcn_readlane(incl, 15), t1 = __builtin_amdgcn_readlane(incl, 31),
+                      t2 = __builtin_amdgcn_readlane(incl, 47);
+            incl += lane < 16 ? 0 : (lane < 32 ? t0 : (lane < 48 ? t0 + t1 : t0 + t1 + t2));
         }
         const unsigned long long hit = __ballot(c >= incl - nc && c < incl);  // at most one lane
         if (hit == 0) return;
