@@ -48,15 +48,15 @@ WORKLOADS = {
 # count).  RECORDED figures for the workload's own inputs at lambda = 1, copied from the files named below; they are
 # not measurements of the current run, and other lambda / alpha report null.
 RECORDED_TRAFFIC = {
-    ("cfg5", "ra_round_sparse_attn_decode"): 1198651113 + 10484698,
-    ("cfg2", "ra_round_sparse_attn_decode"): 49698301 + 1630784,
+    ("cfg5", "ra_round_sparse_attn_decode"): 1195381647 + 6290240,
+    ("cfg2", "ra_round_sparse_attn_decode"): 49712375 + 1630784,
 }
 TRAFFIC_SOURCES = {
     "cfg5": "profiles/attn_mfma_kernel_cfg5_paged_decode.md",
     "cfg2": "profiles/attn_mfma_kernel_cfg2_small_batch_decode.md",
 }
 MFMA_BUSY_SOURCE = "profiles/attn_prefill_mfma_kernel_cfg3_question_prefill.md (rocprofv3 --pmc; recorded, not measured in this run)"
-RECORDED_MFMA_BUSY = {"scores_prefill_mfma_kernel": 0.381, "attn_prefill_mfma_kernel": 0.475}
+RECORDED_MFMA_BUSY = {"scores_prefill_mfma_kernel": 0.381, "attn_prefill_mfma_kernel": 0.476}
 
 
 def parse():

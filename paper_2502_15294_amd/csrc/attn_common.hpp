@@ -7,17 +7,15 @@
 namespace ra {
 
 // Share of the batch's key tiles that the first half of the decode kernel's ranges gets beyond one half, in
-// 1/1000 (RangeCut in range_schedule.hpp).  The launch puts two workgroups on every compute unit and the hardware
-// dispatches the first half of the grid first; while all loads were ordinary ones, the waves that came first on a
-// unit were served ahead of the others for the whole kernel and ended early, and a skew of 90 took the kernel from
-// 217 to 212 microseconds on the large paged workload at 13.9 % kept (0: 217.0-217.9, 20: 215.7, 40: 215.4-216.0,
-// 60: 213.2, 80: 211.4, 100: 212.4, 140: 216.6, 180: 217.7, 220: 220.6).  Since the value tiles are read with
-// non-temporal loads (194-199 microseconds) the skew no longer matters (0: 199.1, 50: 199.8, 90: 198.6-201.0,
-// 130: 200.7; 59.7 % kept: 778-783 for all four).  Time stamps show why: a wave keeps two tiles in flight and the
-// hardware serves the first-dispatched wave of a SIMD at 0.27 tiles per microsecond whatever the other one gets
-// (0.20 with equal ranges, 0.15 when the first has 65 % of the tiles), so a skew only moves time between the two
-// phases; both halves end together at a skew of 300, which gains 1.4 % (192.0-193.2 against 194.7-195.9) and would
-// cost up to 30 % on a part that serves its waves evenly.  The ranges are equal; the two-class cut stays available.
+// 1/1000 (RangeCut in range_schedule.hpp).  It is 0: the launch puts one workgroup on every compute unit, one wave on
+// every SIMD, and all waves stream at the same rate.  The two-class cut dates from the launch with two workgroups per
+// unit, whose second workgroup's waves shared their SIMD with an older wave that the hardware served first (0.27
+// against 0.20 tiles per microsecond for the whole kernel): while all loads were ordinary ones a skew of 90 took the
+// kernel from 217 to 212 microseconds on the large paged workload at 13.9 % kept (0: 217.0-217.9, 20: 215.7,
+// 40: 215.4-216.0, 60: 213.2, 80: 211.4, 100: 212.4, 140: 216.6, 180: 217.7, 220: 220.6); behind the non-temporal
+// value loads it no longer mattered (0: 199.1, 50: 199.8, 90: 198.6-201.0, 130: 200.7), since the first wave of a
+// SIMD got its 0.27 whatever the other one got, and a skew only moved time between the two phases.  The cut stays
+// available for a part or a launch shape that serves its waves unevenly.
 constexpr int kRangeSkew = 0;
 
 struct AttnArgs {

@@ -575,8 +575,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a, int n_row
             // Two tile buffers used alternately, and no register that is still being loaded is ever copied.  The
             // next request sits under a condition, so the compiler waits for all outstanding loads before a tile's
             // first product: both tiles are requested back to back and arrive together.  A form of this loop whose
-            // waits leave the other tile's loads outstanding was measured and is no faster: with eight waves per
-            // compute unit the memory system is full either way.
+            // waits leave the other tile's loads outstanding was measured and is no faster: the memory system is
+            // full either way.
             {
                 KVTile ta, tb;
                 TileRef ref_a, ref_b;
