@@ -27,6 +27,10 @@ constexpr long long kDescMinWorkgroups = 2048;
 // ... and with few rounds, where a workgroup can find its round from scalar loads alone (about 0.1 microseconds of
 // scalar work at every start, against 4 microseconds once for the descriptor kernel), only from here on
 constexpr long long kDescMinWorkgroupsFewRounds = 32768;
+// LDS that the large launches ask for and do not use: with it three workgroups fit a compute unit instead of four
+// (34 + 12 KB each of 160 KB), which streams 1 % faster there (664-665 -> 657-660 microseconds on 4.3 GB of keys;
+// two workgroups: 736, one: 1151).  The small launches, a few workgroups per slot in all, lose with it (34.6 -> 35.3).
+constexpr size_t kDescLdsPad = 12 * 1024;
 
 // A 32-token key tile on its way from memory: load j holds 16 bytes (chunk lane%16) of the row of token
 // 4 j + lane/16, so that one load instruction reads four whole rows (eight whole cache lines).
@@ -380,9 +384,9 @@ int launch_scores_mfma(const ScoreArgs& a, bool paged, int /*num_cu*/, hipStream
         hipLaunchKernelGGL(scores_chunks_kernel, dim3(a.view.B), dim3(256), tab_bytes, st, a,
                            reinterpret_cast<ChunkDesc*>(a.chunks));
         if (paged)
-            RA_LAUNCH_TIMED((scores_mfma_kernel<true, kDescriptors>), grid, dim3(256), 0, st, a);
+            RA_LAUNCH_TIMED((scores_mfma_kernel<true, kDescriptors>), grid, dim3(256), kDescLdsPad, st, a);
         else
-            RA_LAUNCH_TIMED((scores_mfma_kernel<false, kDescriptors>), grid, dim3(256), 0, st, a);
+            RA_LAUNCH_TIMED((scores_mfma_kernel<false, kDescriptors>), grid, dim3(256), kDescLdsPad, st, a);
         return RA_OK;
     }
     if (a.view.R_max <= kScalarRounds) {
