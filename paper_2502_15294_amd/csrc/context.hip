@@ -132,12 +132,12 @@ int ra_profile_last_ms(ra_ctx* ctx, float* ms_out) {
 
 namespace ra {
 // Plain streaming read: every wave streams its own contiguous span with non-temporal 16-byte loads (1 KB per load
-// instruction, eight in flight), everything folded into one word per wave so that the loads cannot be dropped.  What
+// instruction, sixteen in flight), everything folded into one word per wave so that the loads cannot be dropped.  What
 // this reaches is the practical ceiling the streaming kernels are compared with.  Measured on one MI355X over 4 GiB:
-// this form 6.9-7.1 TB/s; the same with ordinary loads 6.0-6.2; grid-stride with ordinary loads 5.5-5.9, with
-// non-temporal loads 5.9-6.5.
+// this form 7.0-7.15 TB/s with one to eight workgroups per compute unit (eight loads in flight: 6.9-7.05); the same
+// with ordinary loads 6.0-6.2; grid-stride with ordinary loads 5.5-5.9, with non-temporal loads 5.9-6.5.
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ p, size_t n, unsigned* __restrict__ sink) {
-    constexpr int kInFlight = 8;
+    constexpr int kInFlight = 16;
     const size_t waves = (size_t)gridDim.x * 4, w = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const size_t per = (n / waves) & ~(size_t)63;  // 16-byte words per wave, whole kilobytes
     const int lane = threadIdx.x & 63;
@@ -178,7 +178,7 @@ int ra_measure_read_bandwidth(ra_ctx* ctx, void* stream, const void* device_buf,
     RA_HIP_CHECK(hipEventCreate(&e0));
     RA_HIP_CHECK(hipEventCreate(&e1));
     unsigned* sink = reinterpret_cast<unsigned*>(ctx->ws.base + kWsReserved - 64);  // a spare word of the reserved head
-    const dim3 grid(ctx->num_cu * 4), block(256);  // four workgroups per compute unit (2, 4, 8 and 16 measured alike)
+    const dim3 grid(ctx->num_cu * 2), block(256);  // two workgroups per compute unit (1, 2, 3, 4 and 8 measured alike)
     hipLaunchKernelGGL(ra::stream_read_kernel, grid, block, 0, st, static_cast<const uint4*>(device_buf), bytes / 16, sink);
     hipError_t e = hipEventRecord(e0, st);
     for (int i = 0; i < iters && e == hipSuccess; ++i)
