@@ -31,6 +31,7 @@ constexpr long long kDescMinWorkgroupsFewRounds = 32768;
 // (34 + 12 KB each of 160 KB), which streams 1 % faster there (664-665 -> 657-660 microseconds on 4.3 GB of keys;
 // two workgroups: 736, one: 1151).  The small launches, a few workgroups per slot in all, lose with it (34.6 -> 35.3).
 constexpr size_t kDescLdsPad = 12 * 1024;
+constexpr long long kDescPadMinWorkgroups = 16384;  // launches of at least this many workgroups get the padding
 
 // A 32-token key tile on its way from memory: load j holds 16 bytes (chunk lane%16) of the row of token
 // 4 j + lane/16, so that one load instruction reads four whole rows (eight whole cache lines).
@@ -383,10 +384,11 @@ int launch_scores_mfma(const ScoreArgs& a, bool paged, int /*num_cu*/, hipStream
     if (a.chunks && n_wg >= (a.view.R_max <= kScalarRounds ? kDescMinWorkgroupsFewRounds : kDescMinWorkgroups)) {
         hipLaunchKernelGGL(scores_chunks_kernel, dim3(a.view.B), dim3(256), tab_bytes, st, a,
                            reinterpret_cast<ChunkDesc*>(a.chunks));
+        const size_t pad = n_wg >= kDescPadMinWorkgroups ? kDescLdsPad : 0;
         if (paged)
-            RA_LAUNCH_TIMED((scores_mfma_kernel<true, kDescriptors>), grid, dim3(256), kDescLdsPad, st, a);
+            RA_LAUNCH_TIMED((scores_mfma_kernel<true, kDescriptors>), grid, dim3(256), pad, st, a);
         else
-            RA_LAUNCH_TIMED((scores_mfma_kernel<false, kDescriptors>), grid, dim3(256), kDescLdsPad, st, a);
+            RA_LAUNCH_TIMED((scores_mfma_kernel<false, kDescriptors>), grid, dim3(256), pad, st, a);
         return RA_OK;
     }
     if (a.view.R_max <= kScalarRounds) {
