@@ -48,8 +48,8 @@ WORKLOADS = {
 # count).  RECORDED figures for the workload's own inputs at lambda = 1, copied from the files named below; they are
 # not measurements of the current run, and other lambda / alpha report null.
 RECORDED_TRAFFIC = {
-    ("cfg5", "ra_round_sparse_attn_decode"): 1195385890 + 6290233,
-    ("cfg2", "ra_round_sparse_attn_decode"): 49711881 + 1630784,
+    ("cfg5", "ra_round_sparse_attn_decode"): 1195384732 + 6290224,
+    ("cfg2", "ra_round_sparse_attn_decode"): 49712314 + 1630784,
 }
 TRAFFIC_SOURCES = {
     "cfg5": "profiles/attn_mfma_kernel_cfg5_paged_decode.md",
