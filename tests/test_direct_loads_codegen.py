@@ -61,3 +61,54 @@ def test_no_vector_arithmetic_hides_in_asm_statements():
             if body and "global_load_lds_dwordx4" not in body:
                 bad.append(f"{name}: {body!r}")
     assert not bad, "asm statements with instructions the compiler cannot see:\n" + "\n".join(bad)
+
+
+def _kernel_bodies(asm_text):
+    """Mangled kernel name -> its instructions (comments, directives and labels dropped)."""
+    bodies, name = {}, None
+    for line in asm_text.splitlines():
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            name = m.group(1)
+            bodies[name] = []
+            continue
+        l = line.strip()
+        if l.startswith(".Lfunc_end"):
+            name = None
+        if name and l and not l.startswith((";", ".", "//")) and not l.endswith(":"):
+            bodies[name].append(l)
+    return bodies
+
+
+def test_score_kernel_finds_its_chunk_by_scalar_loads(tmp_path):
+    """The workgroups of the decode-shape score kernel start while their compute unit's vector memory queue is full of
+    other workgroups' key tiles, so what tells a workgroup where its chunk lies must not come through that queue: the
+    chunk descriptor, the rounds' lengths and the paged walk's block ids are read through the constant address space.
+    If they turned into vector loads the results would stay right and the kernel would lose a tenth of its speed;
+    this test looks at the generated code instead (no GPU needed)."""
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not found")
+    out = tmp_path / "scores_mfma.s"
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-S", "--cuda-device-only", "-o", str(out),
+           os.path.join(CSRC, "scores_mfma.hip")]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    bodies = _kernel_bodies(out.read_text())
+    kernels = {k: v for k, v in bodies.items() if "scores_mfma_kernel" in k}
+    assert len(kernels) == 6, sorted(kernels)          # paged or not x table in LDS / descriptors / scalar table
+    for name, code in kernels.items():
+        mode = int(re.search(r"ELi(\d)E", name).group(1))
+        paged = "ILb1E" in name
+        narrow = [l for l in code if re.match(r"global_load_(dword|dwordx2|ushort|ubyte)\b", l)]
+        wide = [l for l in code if l.startswith("global_load_dwordx4")]
+        assert len(wide) >= 20, f"{name}: the key and query loads are gone"
+        if mode == 0:
+            assert narrow, f"{name}: the table in LDS is built from vector loads"
+            continue
+        # descriptors (1) and scalar table (2): every load that is not a key or query load is a scalar one
+        assert not narrow, f"{name}: a table or block-table entry is read by a vector load: {narrow[:3]}"
+        scalar = [l for l in code if l.startswith("s_load_dword")]
+        assert len(scalar) >= (4 if mode == 1 else 32) + (4 if paged else 0), f"{name}: {len(scalar)} scalar loads"
+        if mode == 1:
+            assert any(l.startswith("s_load_dwordx4") for l in code), f"{name}: no 16-byte descriptor load"
